@@ -1,0 +1,288 @@
+"""Pins for the CPU oracle: each check ties `oracle/mha_oracle.py` to something other than
+itself -- brute force with naive exponentials, closed forms, limits, the invariants of the
+paper's bias appendix, and numbers the paper prints.  CPU only."""
+import math
+import os
+
+import numpy as np
+import pytest
+
+from oracle import mha_oracle as orc
+from paper_2503_05840_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ------------------------------------------------------------------------------------------
+# brute force: eq. 4, 5, 2 written with python floats and loops, exp without a max shift
+# ------------------------------------------------------------------------------------------
+def brute_force_decode(x_q, X, W_K, W_V, h):
+    n, d = len(X), len(X[0])
+    e = len(W_K[0])
+    d_k = e // h
+    K = [[sum(X[t][a] * W_K[a][c] for a in range(d)) for c in range(e)] for t in range(n)]
+    V = [[sum(X[t][a] * W_V[a][c] for a in range(d)) for c in range(e)] for t in range(n)]
+    out = [0.0] * e
+    for i in range(h):
+        lo = i * d_k
+        w = []
+        for t in range(n):
+            dot = sum(x_q[lo + j] * K[t][lo + j] for j in range(d_k))
+            w.append(math.exp(dot / math.sqrt(d_k)))
+        z = sum(w)
+        for j in range(d_k):
+            out[lo + j] = sum(w[t] / z * V[t][lo + j] for t in range(n))
+    return out
+
+
+@pytest.mark.parametrize("n,d,h,seed", [(1, 4, 2, 0), (3, 4, 1, 1), (5, 8, 2, 2), (8, 6, 3, 3), (7, 8, 4, 4)])
+def test_vanilla_matches_brute_force(n, d, h, seed):
+    rng = np.random.default_rng(seed)
+    X = rng.standard_normal((n, d))
+    W_K = rng.standard_normal((d, d))
+    W_V = rng.standard_normal((d, d))
+    q = rng.standard_normal(d)
+    ref = brute_force_decode(q.tolist(), X.tolist(), W_K.tolist(), W_V.tolist(), h)
+    got = orc.vanilla_decode_from_x(q, X, W_K, W_V, h)
+    np.testing.assert_allclose(got, ref, rtol=1e-12, atol=1e-13)
+
+
+def test_brute_force_nonsquare_projection():
+    """e = h*d_k > d_model (the non-square section's shapes), still eq. 2 per head."""
+    rng = np.random.default_rng(11)
+    n, d, h, d_k = 6, 3, 4, 2
+    X = rng.standard_normal((n, d))
+    W_K = rng.standard_normal((d, h * d_k))
+    W_V = rng.standard_normal((d, h * d_k))
+    q = rng.standard_normal(h * d_k)
+    ref = brute_force_decode(q.tolist(), X.tolist(), W_K.tolist(), W_V.tolist(), h)
+    np.testing.assert_allclose(orc.vanilla_decode_from_x(q, X, W_K, W_V, h), ref, rtol=1e-12)
+    np.testing.assert_allclose(orc.xcache_decode_absorbed(q, X, W_K, W_V, h), ref, rtol=1e-11)
+
+
+def test_hand_worked_softmax_weights():
+    """d_k = 4, two cached rows, keys chosen so q.k/sqrt(d_k) = ln1, ln3 -> p = (1/4, 3/4).
+    Catches a missing or wrong 1/sqrt(d_k)."""
+    d_k = 4
+    q = np.array([2.0, 0.0, 0.0, 0.0])
+    K = np.array([[0.0, 5.0, 1.0, -2.0],
+                  [math.log(3.0) * math.sqrt(d_k) / 2.0, 7.0, 0.0, 1.0]])
+    V = np.array([[1.0, 0.0, 4.0, 8.0], [5.0, 4.0, 0.0, -8.0]])
+    P = orc.attention_probs(q, K, 1)
+    np.testing.assert_allclose(P, [[0.25, 0.75]], rtol=1e-14)
+    np.testing.assert_allclose(orc.vanilla_decode(q, K, V, 1), [4.0, 3.0, 1.0, -4.0], rtol=1e-14)
+
+
+def test_heads_are_column_blocks():
+    """Two heads with different queries: head 0 uniform (q=0), head 1 one-hot in the limit."""
+    K = np.array([[0.0, 0.0, 1.0, 0.0], [0.0, 0.0, 0.0, 0.0], [0.0, 0.0, -1.0, 0.0]])
+    V = np.arange(12.0).reshape(3, 4)
+    q = np.array([0.0, 0.0, 200.0, 0.0])
+    out = orc.vanilla_decode(q, K, V, 2)
+    np.testing.assert_allclose(out[:2], V[:, :2].mean(axis=0), rtol=1e-14)
+    np.testing.assert_allclose(out[2:], V[0, 2:], rtol=1e-12)
+
+
+# ------------------------------------------------------------------------------------------
+# invariants and limits
+# ------------------------------------------------------------------------------------------
+def _small_problem(seed=5, n=33, d=24, h=3):
+    rng = np.random.default_rng(seed)
+    X = rng.standard_normal((n, d))
+    W_K = rng.standard_normal((d, d)) / math.sqrt(d)
+    W_V = rng.standard_normal((d, d)) / math.sqrt(d)
+    q = rng.standard_normal(d)
+    return X, W_K, W_V, q, h
+
+
+def test_probs_sum_to_one():
+    X, W_K, W_V, q, h = _small_problem()
+    P = orc.attention_probs(q * 7.0, orc.project(X, W_K), h)
+    assert P.shape == (h, X.shape[0])
+    np.testing.assert_allclose(P.sum(axis=1), 1.0, rtol=0, atol=1e-14)
+    assert (P >= 0).all()
+
+
+def test_zero_query_gives_mean_value():
+    X, W_K, W_V, q, h = _small_problem()
+    out = orc.vanilla_decode_from_x(np.zeros_like(q), X, W_K, W_V, h)
+    np.testing.assert_allclose(out, X.mean(axis=0) @ W_V, rtol=1e-12, atol=1e-14)
+
+
+def test_single_row_context_returns_that_value():
+    X, W_K, W_V, q, h = _small_problem(n=1)
+    np.testing.assert_allclose(orc.vanilla_decode_from_x(q, X, W_K, W_V, h), X[0] @ W_V, rtol=1e-13)
+
+
+def test_row_permutation_invariance():
+    X, W_K, W_V, q, h = _small_problem()
+    perm = np.random.default_rng(0).permutation(X.shape[0])
+    a = orc.vanilla_decode_from_x(q, X, W_K, W_V, h)
+    b = orc.vanilla_decode_from_x(q, X[perm], W_K, W_V, h)
+    np.testing.assert_allclose(a, b, rtol=1e-12, atol=1e-15)
+
+
+def test_large_query_selects_argmax_row_per_head():
+    X, W_K, W_V, q, h = _small_problem()
+    K, V = orc.project(X, W_K), orc.project(X, W_V)
+    d_k = K.shape[1] // h
+    out = orc.vanilla_decode(q * 1e4, K, V, h)
+    for i in range(h):
+        cols = slice(i * d_k, (i + 1) * d_k)
+        t = int(np.argmax(K[:, cols] @ q[cols]))
+        np.testing.assert_allclose(out[cols], V[t, cols], rtol=1e-9)
+
+
+def test_key_bias_cancels_and_value_bias_passes_through():
+    """Bias appendix: a constant vector added to every key leaves the softmax unchanged;
+    a constant added to every value is added to the output (weights sum to 1)."""
+    X, W_K, W_V, q, h = _small_problem()
+    K, V = orc.project(X, W_K), orc.project(X, W_V)
+    rng = np.random.default_rng(9)
+    c = rng.standard_normal(K.shape[1])
+    b = rng.standard_normal(V.shape[1])
+    np.testing.assert_allclose(orc.attention_probs(q, K + c, h), orc.attention_probs(q, K, h),
+                               rtol=1e-11, atol=1e-15)
+    np.testing.assert_allclose(orc.vanilla_decode(q, K, V + b, h), orc.vanilla_decode(q, K, V, h) + b,
+                               rtol=1e-12, atol=1e-14)
+
+
+# ------------------------------------------------------------------------------------------
+# eq. 6 / eq. 7 / App. A on the synthetic well-conditioned W_K
+# ------------------------------------------------------------------------------------------
+@pytest.fixture(scope="module")
+def cfg0_problem():
+    return synth.make_problem(synth.CONFIGS[0])
+
+
+def test_wkv_closed_form_from_construction(cfg0_problem):
+    """W_K = U diag(s) V^T / sqrt(d)  =>  W_K^-1 = sqrt(d) V diag(1/s) U^T."""
+    w = cfg0_problem.w
+    d = w.W_K.shape[0]
+    closed = math.sqrt(d) * (w.Vt.T / w.s) @ w.U.T @ w.W_V
+    got = orc.wkv_by_inverse(w.W_K, w.W_V)
+    assert np.abs(got - closed).max() <= 1e-11 * np.abs(closed).max()
+
+
+def test_wkv_special_cases():
+    rng = np.random.default_rng(3)
+    d = 12
+    W_V = rng.standard_normal((d, d))
+    np.testing.assert_allclose(orc.wkv_by_inverse(np.eye(d), W_V), W_V, rtol=1e-14)
+    W_K = rng.standard_normal((d, d))
+    np.testing.assert_allclose(orc.wkv_by_inverse(W_K, W_K), np.eye(d), atol=1e-11)
+    perm = rng.permutation(d)
+    Pm = np.eye(d)[perm]                       # (Pm W)[r] = W[perm[r]];  Pm^-1 = Pm^T
+    np.testing.assert_allclose(orc.wkv_by_inverse(Pm, W_V), Pm.T @ W_V, rtol=1e-14)
+
+
+def test_appendix_a_acceptance_check(cfg0_problem):
+    w = cfg0_problem.w
+    W_KV = orc.wkv_by_inverse(w.W_K, w.W_V)
+    assert np.allclose(w.W_K @ W_KV, w.W_V)              # the paper's own check, numpy defaults
+
+
+def test_v_from_k_identity(cfg0_problem):
+    w, sq = cfg0_problem.w, cfg0_problem.seqs[0]
+    W_KV = orc.wkv_by_inverse(w.W_K, w.W_V)
+    V = orc.project(sq.X, w.W_V)
+    V2 = orc.project(sq.X, w.W_K) @ W_KV
+    assert np.abs(V - V2).max() <= 1e-10 * np.abs(V).max()
+
+
+def test_option1_equals_option2_equals_vanilla(cfg0_problem):
+    p = cfg0_problem
+    w, sq, q, h = p.w, p.seqs[0], p.q[0], p.cfg.H
+    K = orc.project(sq.X, w.W_K)
+    W_KV = orc.wkv_by_inverse(w.W_K, w.W_V)
+    ref = orc.vanilla_decode_from_x(q, sq.X, w.W_K, w.W_V, h)
+    o1 = orc.slim_option1(q, K, W_KV, h)
+    o2 = orc.slim_option2(q, K, W_KV, h)
+    scale = np.abs(ref).max()
+    assert np.abs(o1 - ref).max() <= 1e-11 * scale
+    assert np.abs(o2 - ref).max() <= 1e-11 * scale
+
+
+def test_xcache_score_identity_and_output():
+    cfg = synth.scaled(synth.CONFIGS[4], B=1, H=8, d=64, d_k=16, T=50)
+    p = synth.make_problem(cfg)
+    w, sq, q = p.w, p.seqs[0], p.q[0]
+    K = orc.project(sq.X, w.W_K)
+    for i in (0, 3, 7):
+        cols = slice(i * cfg.d_k, (i + 1) * cfg.d_k)
+        lhs = (w.W_K[:, cols] @ q[cols]) @ sq.X.T
+        rhs = K[:, cols] @ q[cols]
+        np.testing.assert_allclose(lhs, rhs, rtol=1e-11, atol=1e-13)
+    ref = orc.vanilla_decode_from_x(q, sq.X, w.W_K, w.W_V, cfg.H)
+    got = orc.xcache_decode_absorbed(q, sq.X, w.W_K, w.W_V, cfg.H)
+    assert np.abs(got - ref).max() <= 1e-11 * np.abs(ref).max()
+
+
+def test_split_merge_equals_unsplit():
+    X, W_K, W_V, q, h = _small_problem(n=41)
+    K, V = orc.project(X, W_K), orc.project(X, W_V)
+    ref = orc.vanilla_decode(q * 9.0, K, V, h)
+    rng = np.random.default_rng(21)
+    for trial in range(5):
+        perm = rng.permutation(41)
+        cuts = np.sort(rng.choice(np.arange(1, 41), size=rng.integers(1, 8), replace=False))
+        pieces = [p for p in np.split(perm, cuts) if len(p)]
+        got = orc.split_merge_decode(q * 9.0, K, V, h, pieces)
+        np.testing.assert_allclose(got, ref, rtol=1e-12, atol=1e-14)
+    # length-1 pieces only
+    got = orc.split_merge_decode(q * 9.0, K, V, h, [np.array([t]) for t in range(41)])
+    np.testing.assert_allclose(got, ref, rtol=1e-12, atol=1e-14)
+
+
+# ------------------------------------------------------------------------------------------
+# numbers the paper prints
+# ------------------------------------------------------------------------------------------
+def _table2_rows():
+    rows = {}
+    with open(os.path.join(GOLDEN, "table2_complexity.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            name, proj, ops, reads = [s.strip() for s in line.split("|")]
+            rows[name] = (proj, ops, reads)
+    return rows
+
+
+@pytest.mark.parametrize("n,d,h", [(16384, 4096, 32), (1500, 1280, 20), (7, 64, 4)])
+def test_table2_op_and_read_counts(n, d, h):
+    env = {"n": n, "d": d, "h": h}
+    for variant, (proj, ops, reads) in _table2_rows().items():
+        got_ops, got_reads = orc.mha_ops_reads(n, d, h, variant)
+        assert got_ops == eval(ops, {}, env), variant
+        assert got_reads == eval(reads, {}, env), variant
+        assert orc.projection_ops(n, d, variant) == eval(proj, {}, env), variant
+    o, r = orc.mha_ops_reads(n, d, h, "optimized")
+    assert o / r == 2 * h + 2                              # intensity column
+
+
+def test_whisper_table_reads_and_speedups():
+    with open(os.path.join(GOLDEN, "whisper_table.txt")) as f:
+        rows = [l.split() for l in f if l.strip() and not l.startswith("#")]
+    assert len(rows) == 5
+    for r in rows:
+        d, layers, d_ffn = int(r[1]), int(r[2]), int(r[3])
+        v = [float(x) for x in r[4:]]
+        reads_b1, reads_b64, speed = v[6:9], v[9:12], v[12:14]
+        for opt in range(3):
+            assert abs(orc.whisper_reads_per_token(d, layers, d_ffn, 1, opt) / 1e6 - reads_b1[opt]) <= 0.051
+            assert abs(orc.whisper_reads_per_token(d, layers, d_ffn, 64, opt) / 1e6 - reads_b64[opt]) <= 0.051
+        base = orc.whisper_reads_per_token(d, layers, d_ffn, 64, 0)
+        for k, opt in enumerate((1, 2)):
+            assert abs(base / orc.whisper_reads_per_token(d, layers, d_ffn, 64, opt) - speed[k]) <= 0.051
+
+
+def test_phi3_worked_example():
+    """Intro example: 3.8 GB params, 25 GB KV-cache at 128k (1 byte per element):
+    B=1: 28.8 -> 16.3 GB, 1.8x;  B=16: (400+3.8)/(200+3.8) = 2x (as printed, rounded)."""
+    d, layers, n = 3072, 32, 128 * 1024
+    _, reads_v = orc.mha_ops_reads(n, d, 32, "vanilla")
+    _, reads_s = orc.mha_ops_reads(n, d, 32, "optimized")
+    kv_gb, k_gb = reads_v * layers / 1e9, reads_s * layers / 1e9
+    assert round(kv_gb) == 26 and abs(k_gb - kv_gb / 2) < 1e-9      # Table 1 prints 25.8B
+    assert round((25 + 3.8) / (12.5 + 3.8), 1) == 1.8
+    assert round((400 + 3.8) / (200 + 3.8)) == 2
