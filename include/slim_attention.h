@@ -1,0 +1,125 @@
+/*
+ * slim_attention.h -- C ABI of the MI355X (gfx950) slim-attention decode library.
+ *
+ * One multi-head-attention generation step that reads only a K-cache (paper: "K-cache is
+ * all you need", eq. 6 and eq. 7 option 2):
+ *
+ *     p_h   = softmax(q_h K_h^T / sqrt(d_k))              (eq. 2, no causal mask)
+ *     out_h = (p_h K) W_KV[:, h-th column block]          (eq. 7, option 2)
+ *     W_KV  = W_K^{-1} W_V                                (eq. 6, prepared once, offline)
+ *
+ * Conventions shared by every entry point
+ *   - Row vectors, weights are W[in][out] row-major, head h owns the column block
+ *     [h*d_k, (h+1)*d_k) of the projection width e = H*d_k (text below eq. 2).
+ *   - "host" pointers are ordinary CPU memory; "device" pointers are HIP device memory of
+ *     the current device.  All buffers are owned by the caller; the library never frees or
+ *     retains them beyond the call (device work is asynchronous on `stream`, so the caller
+ *     keeps buffers alive until the stream has passed the call).
+ *   - Device pointers must be 16-byte aligned; row pitches are dense.
+ *   - Every function returns SLIM_OK (0) or a negative SLIM_ERR_* code; nothing throws or
+ *     aborts.  Argument errors are detected on the host before anything is launched.
+ *   - q is the already projected, un-scaled query (the library applies 1/sqrt(d_k)); out is
+ *     concat(head_1..head_H) before W_O (eq. 5).  Attention runs over exactly the cached
+ *     rows handed in (the caller appends the new token's key first if it wants it attended).
+ */
+#ifndef SLIM_ATTENTION_H
+#define SLIM_ATTENTION_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* ---- status codes ------------------------------------------------------------------- */
+#define SLIM_OK              0
+#define SLIM_ERR_ARG        -1   /* null pointer, negative size                              */
+#define SLIM_ERR_SHAPE      -2   /* d % H != 0, d_k not a multiple of the 16-byte vector, T<1 */
+#define SLIM_ERR_DTYPE      -3   /* dtype is neither SLIM_F32 nor SLIM_BF16                   */
+#define SLIM_ERR_ALIGN      -4   /* a device pointer is not 16-byte aligned                   */
+#define SLIM_ERR_WORKSPACE  -5   /* caller workspace smaller than slim_workspace_bytes()      */
+#define SLIM_ERR_SINGULAR   -6   /* W_K is singular to working precision (zero pivot)         */
+#define SLIM_ERR_ILLCOND    -7   /* result written, but rcond(W_K) < 1e-12: do not trust it   */
+#define SLIM_ERR_LAUNCH     -8   /* HIP reported an error at allocation or launch             */
+#define SLIM_ERR_SEQLEN     -9   /* a host-side sequence length is < 1 or > T                 */
+
+/* ---- element types of the cache and of packed weights -------------------------------- */
+#define SLIM_F32   0
+#define SLIM_BF16  1
+
+const char* slim_strerror(int code);
+
+/* ---- offline weight transform (host, fp64, not on the timed path) --------------------- */
+
+/* eq. 6:  W_KV = W_K^{-1} W_V, computed as an LU solve with partial pivoting in fp64
+ * (App. A uses fp64 for the inversion; solving W_K W_KV = W_V is the same result with
+ * fewer operations than forming the inverse).
+ *   Wk, Wv  : host, row-major d x d fp64, read only
+ *   Wkv     : host, row-major d x d fp64, written
+ *   rcond_out: host, nullable; receives a 1-norm reciprocal condition estimate of W_K
+ * Returns SLIM_ERR_SINGULAR (Wkv untouched garbage) on a zero pivot or non-finite input,
+ * SLIM_ERR_ILLCOND (Wkv written) when the estimate is below 1e-12. */
+int slim_prepare_wkv(const double* Wk, const double* Wv, double* Wkv, int d, double* rcond_out);
+
+/* Cast a host fp64 row-major rows x cols matrix to the device element type (round to
+ * nearest even, via fp32 for bf16), same row-major layout.  This is the form `W_KV`
+ * (d x d) and the X-cache weights (d_model x e) are handed to the decode calls; the
+ * caller copies `dst_host` (rows*cols*elemsize bytes, host) to the device. */
+int slim_pack_weights(const double* W, void* dst_host, int rows, int cols, int dtype);
+
+/* ---- options -------------------------------------------------------------------------- */
+typedef struct slim_opts {
+  int            dtype;          /* SLIM_F32 | SLIM_BF16: elements of Kcache/Vcache/X and weights */
+  const int32_t* seq_lens;       /* device [B], nullable => every sequence attends T rows;
+                                    1 <= seq_lens[b] <= T (ragged batches)                        */
+  const int32_t* seq_lens_host;  /* host copy of seq_lens, nullable; lets the host balance
+                                    work across the chip for ragged batches and is validated      */
+  int64_t        t_stride;       /* cache rows between consecutive sequences, 0 => T              */
+  void*          workspace;      /* device scratch, nullable => library-owned, grown on demand
+                                    with hipMalloc and kept per device until process exit         */
+  size_t         workspace_bytes;
+  void*          stream;         /* hipStream_t, null => the null stream                          */
+  int            variant;        /* 0 = library's choice; other values select an implementation
+                                    (see SLIM_VARIANT_*), for tests and tuning                    */
+} slim_opts;
+
+#define SLIM_VARIANT_AUTO      0
+#define SLIM_VARIANT_GENERIC   1   /* plain vector-ALU kernels, any supported shape            */
+#define SLIM_VARIANT_TWOPASS   2   /* bf16: MFMA weighted sum, K read in a score pass and a sum pass */
+#define SLIM_VARIANT_FUSED     3   /* bf16: single pass over K, scores exchanged between workgroups */
+
+/* Upper bound of the device scratch any decode call below needs for this shape. */
+size_t slim_workspace_bytes(int B, int H, int T, int d, int dtype);
+
+/* ---- the decode step ------------------------------------------------------------------- */
+
+/* eq. 7 option 2 for B sequences, one new token each.
+ *   q      : device fp32 [B][d]           projected, un-scaled queries
+ *   Kcache : device dtype [B][t_stride][d] cached keys K = X W_K (eq. 4); only rows
+ *            [0, seq_lens[b]) of sequence b are read
+ *   W_KV   : device dtype [d][d]          from slim_prepare_wkv + slim_pack_weights
+ *   out    : device fp32 [B][d]           concat of heads, written
+ *   d = H*d_k.  No V-cache exists anywhere in this call. */
+int slim_decode(const void* q, const void* Kcache, const void* W_KV, void* out,
+                int B, int H, int T, int d, const slim_opts* opts);
+
+/* The same step the vanilla way (eq. 2 with a stored V-cache, Table 2 row "Vanilla"):
+ * reads K and V, 2*T*d cache elements per sequence.  The same-GPU comparison kernel. */
+int vanilla_kv_decode(const void* q, const void* Kcache, const void* Vcache, void* out,
+                      int B, int H, int T, int d, const slim_opts* opts);
+
+/* Non-square projections (e = H*d_k > d_model), option 2 of that section (Fig. 4): the
+ * cache holds the layer input X; scores use (q_h W_K,h^T) X^T, the output (p_h X) W_V,h.
+ *   q   : device fp32 [B][e]
+ *   X   : device dtype [B][t_stride][d_model]
+ *   W_K, W_V : device dtype [d_model][e] row-major (slim_pack_weights)
+ *   out : device fp32 [B][e] */
+int slim_decode_xcache(const void* q, const void* X, const void* W_K, const void* W_V,
+                       void* out, int B, int H, int T, int d_model, int d_k,
+                       const slim_opts* opts);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SLIM_ATTENTION_H */

@@ -1,0 +1,166 @@
+"""Thin ctypes binding over the C ABI declared in include/slim_attention.h.
+
+Argument marshalling only: every step of the decode path runs inside the library's HIP
+kernels.  torch is used for device memory and the current stream, nothing else.  There is no
+CPU fallback: if the built library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libslim_attention.so")
+
+SLIM_OK = 0
+SLIM_F32, SLIM_BF16 = 0, 1
+VARIANT_AUTO, VARIANT_GENERIC, VARIANT_TWOPASS, VARIANT_FUSED = 0, 1, 2, 3
+DTYPES = {"f32": SLIM_F32, "bf16": SLIM_BF16}
+
+EXPORTS = ("slim_strerror", "slim_prepare_wkv", "slim_pack_weights", "slim_workspace_bytes",
+           "slim_decode", "vanilla_kv_decode", "slim_decode_xcache")
+
+
+class SlimOpts(ctypes.Structure):
+    _fields_ = [
+        ("dtype", ctypes.c_int),
+        ("seq_lens", ctypes.c_void_p),
+        ("seq_lens_host", ctypes.c_void_p),
+        ("t_stride", ctypes.c_int64),
+        ("workspace", ctypes.c_void_p),
+        ("workspace_bytes", ctypes.c_size_t),
+        ("stream", ctypes.c_void_p),
+        ("variant", ctypes.c_int),
+    ]
+
+
+class SlimError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        super().__init__(f"{what}: {strerror(code)} ({code})")
+        self.code = code
+
+
+_lib = None
+
+
+def load():
+    """Loads the in-tree library (after torch, so both share one HIP runtime)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} is not built; run `python -m paper_2503_05840_amd.build` "
+            "(there is no fallback path)")
+    import torch  # noqa: F401  (loads libamdhip64 first)
+    lib = ctypes.CDLL(LIB_PATH, mode=ctypes.RTLD_GLOBAL)
+    vp, ci, cd = ctypes.c_void_p, ctypes.c_int, ctypes.POINTER(ctypes.c_double)
+    lib.slim_strerror.restype = ctypes.c_char_p
+    lib.slim_strerror.argtypes = [ci]
+    lib.slim_prepare_wkv.restype = ci
+    lib.slim_prepare_wkv.argtypes = [vp, vp, vp, ci, cd]
+    lib.slim_pack_weights.restype = ci
+    lib.slim_pack_weights.argtypes = [vp, vp, ci, ci, ci]
+    lib.slim_workspace_bytes.restype = ctypes.c_size_t
+    lib.slim_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
+    op = ctypes.POINTER(SlimOpts)
+    lib.slim_decode.restype = ci
+    lib.slim_decode.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, op]
+    lib.vanilla_kv_decode.restype = ci
+    lib.vanilla_kv_decode.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, op]
+    lib.slim_decode_xcache.restype = ci
+    lib.slim_decode_xcache.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, op]
+    _lib = lib
+    return lib
+
+
+def strerror(code: int) -> str:
+    return load().slim_strerror(code).decode()
+
+
+# ---- host side -------------------------------------------------------------------------------
+def slim_prepare_wkv(W_K: np.ndarray, W_V: np.ndarray, allow_illcond: bool = False):
+    """W_KV = W_K^{-1} W_V in fp64 on the host.  Returns (W_KV, rcond)."""
+    W_K = np.ascontiguousarray(W_K, dtype=np.float64)
+    W_V = np.ascontiguousarray(W_V, dtype=np.float64)
+    d = W_K.shape[0]
+    if W_K.shape != (d, d) or W_V.shape != (d, d):
+        raise ValueError("W_K and W_V must be square and of equal size")
+    out = np.empty((d, d), dtype=np.float64)
+    rcond = ctypes.c_double(0.0)
+    rc = load().slim_prepare_wkv(W_K.ctypes.data, W_V.ctypes.data, out.ctypes.data, d, ctypes.byref(rcond))
+    if rc != SLIM_OK and not (allow_illcond and rc == -7):
+        raise SlimError(rc, "slim_prepare_wkv")
+    return out, rcond.value
+
+
+def slim_pack_weights(W: np.ndarray, dtype: str) -> np.ndarray:
+    """fp64 row-major matrix -> device element type (float32 array or uint16 bf16 bits)."""
+    W = np.ascontiguousarray(W, dtype=np.float64)
+    rows, cols = W.shape
+    out = np.empty((rows, cols), dtype=np.float32 if dtype == "f32" else np.uint16)
+    rc = load().slim_pack_weights(W.ctypes.data, out.ctypes.data, rows, cols, DTYPES[dtype])
+    if rc != SLIM_OK:
+        raise SlimError(rc, "slim_pack_weights")
+    return out
+
+
+def slim_workspace_bytes(B, H, T, d, dtype: str) -> int:
+    return int(load().slim_workspace_bytes(B, H, T, d, DTYPES[dtype]))
+
+
+# ---- device side -----------------------------------------------------------------------------
+def _opts(dtype, seq_lens, seq_lens_host, t_stride, workspace, variant):
+    import torch
+    o = SlimOpts()
+    o.dtype = DTYPES[dtype]
+    o.seq_lens = seq_lens.data_ptr() if seq_lens is not None else None
+    keep = None
+    if seq_lens_host is not None:
+        keep = np.ascontiguousarray(seq_lens_host, dtype=np.int32)
+        o.seq_lens_host = keep.ctypes.data
+    o.t_stride = int(t_stride or 0)
+    if workspace is not None:
+        o.workspace = workspace.data_ptr()
+        o.workspace_bytes = workspace.numel() * workspace.element_size()
+    o.stream = torch.cuda.current_stream().cuda_stream
+    o.variant = int(variant)
+    return o, keep
+
+
+def _dev_ptr(t):
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("expected a contiguous device tensor")
+    return t.data_ptr()
+
+
+def slim_decode(q, Kcache, W_KV, out, B, H, T, d, dtype="bf16", seq_lens=None, seq_lens_host=None,
+                t_stride=0, workspace=None, variant=VARIANT_AUTO):
+    o, keep = _opts(dtype, seq_lens, seq_lens_host, t_stride, workspace, variant)
+    rc = load().slim_decode(_dev_ptr(q), _dev_ptr(Kcache), _dev_ptr(W_KV), _dev_ptr(out), B, H, T, d,
+                            ctypes.byref(o))
+    if rc != SLIM_OK:
+        raise SlimError(rc, "slim_decode")
+    return out
+
+
+def vanilla_kv_decode(q, Kcache, Vcache, out, B, H, T, d, dtype="bf16", seq_lens=None,
+                      seq_lens_host=None, t_stride=0, workspace=None, variant=VARIANT_AUTO):
+    o, keep = _opts(dtype, seq_lens, seq_lens_host, t_stride, workspace, variant)
+    rc = load().vanilla_kv_decode(_dev_ptr(q), _dev_ptr(Kcache), _dev_ptr(Vcache), _dev_ptr(out),
+                                  B, H, T, d, ctypes.byref(o))
+    if rc != SLIM_OK:
+        raise SlimError(rc, "vanilla_kv_decode")
+    return out
+
+
+def slim_decode_xcache(q, X, W_K, W_V, out, B, H, T, d_model, d_k, dtype="bf16", seq_lens=None,
+                       seq_lens_host=None, t_stride=0, workspace=None, variant=VARIANT_AUTO):
+    o, keep = _opts(dtype, seq_lens, seq_lens_host, t_stride, workspace, variant)
+    rc = load().slim_decode_xcache(_dev_ptr(q), _dev_ptr(X), _dev_ptr(W_K), _dev_ptr(W_V),
+                                   _dev_ptr(out), B, H, T, d_model, d_k, ctypes.byref(o))
+    if rc != SLIM_OK:
+        raise SlimError(rc, "slim_decode_xcache")
+    return out

@@ -1,0 +1,554 @@
+// Generic vector-ALU kernels of the slim-attention decode step (gfx950).
+//
+// These handle every supported shape in fp32 arithmetic for both cache element types
+// (fp32, bf16) and are the path for fp32 caches; the bf16 fast kernels live in
+// kernels_bf16.hip.  Steps, in the paper's terms:
+//   head_scores   : softmax arguments q_i K_i^T / sqrt(d_k)                 (eq. 2)
+//   weighted_sum  : [softmax(.) K], the full-width weighted sum of K rows   (eq. 7, option 2)
+//                   per split of the context, with a local max (flash-decoding style)
+//   combine       : log-sum-exp merge of the splits and the 1/l normalisation
+//   project       : ... W_KV,i per head                                     (eq. 7, option 2)
+//   vanilla_*     : softmax(.) V_i reading both caches                      (eq. 2; Table 2 "Vanilla")
+//   dense_scores  : (q_i W_K,i^T) X^T for the X-cache scheme                (non-square section, Fig. 4)
+#include "slim_kernels.h"
+
+#include <math.h>
+
+namespace slim {
+namespace {
+
+struct F32 {
+  using elem = float;
+  static constexpr int VEC = 4;
+  static __device__ __forceinline__ void load(const elem* p, float (&v)[4]) {
+    const float4 x = *reinterpret_cast<const float4*>(p);
+    v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
+  }
+  static __device__ __forceinline__ float one(const elem* p) { return *p; }
+  static __device__ __forceinline__ void two(const elem* p, float& a, float& b) {
+    const float2 x = *reinterpret_cast<const float2*>(p);
+    a = x.x; b = x.y;
+  }
+};
+
+struct BF16 {
+  using elem = uint16_t;
+  static constexpr int VEC = 8;
+  static __device__ __forceinline__ void load(const elem* p, float (&v)[8]) {
+    const uint4 x = *reinterpret_cast<const uint4*>(p);
+    v[0] = __uint_as_float(x.x << 16); v[1] = __uint_as_float(x.x & 0xffff0000u);
+    v[2] = __uint_as_float(x.y << 16); v[3] = __uint_as_float(x.y & 0xffff0000u);
+    v[4] = __uint_as_float(x.z << 16); v[5] = __uint_as_float(x.z & 0xffff0000u);
+    v[6] = __uint_as_float(x.w << 16); v[7] = __uint_as_float(x.w & 0xffff0000u);
+  }
+  static __device__ __forceinline__ float one(const elem* p) {
+    return __uint_as_float(((uint32_t)*p) << 16);
+  }
+  static __device__ __forceinline__ void two(const elem* p, float& a, float& b) {
+    const uint32_t x = *reinterpret_cast<const uint32_t*>(p);
+    a = __uint_as_float(x << 16); b = __uint_as_float(x & 0xffff0000u);
+  }
+};
+
+__device__ __forceinline__ int seq_len_of(const int32_t* lens, int b, int T) {
+  if (!lens) return T;
+  int n = lens[b];
+  return n < 0 ? 0 : (n > T ? T : n);
+}
+
+constexpr float NEG_INF = -INFINITY;
+
+// ------------------------------------------------------------------------------------------------
+// head_scores: one wave per row; lanes stride over the row in 16-byte vectors, partial dot
+// products go to LDS and are summed per head (works for any d_k that is a multiple of VEC).
+// ------------------------------------------------------------------------------------------------
+constexpr int HS_ROWS = 32;   // rows per workgroup (4 waves x 8 rows)
+
+template <class ET>
+__global__ __launch_bounds__(256) void head_scores_kernel(
+    const float* __restrict__ q, long q_bstride, const typename ET::elem* __restrict__ M,
+    long m_bstride, long row_pitch, const int32_t* __restrict__ rows_per_b, int rows, int e, int H,
+    int d_k, float scale, float* __restrict__ S, long s_bstride) {
+  extern __shared__ float smem[];
+  constexpr int VEC = ET::VEC;
+  const int nvec = e / VEC;
+  float* q_s = smem;                 // [e]
+  float* part = smem + e;            // [4][nvec]
+  const int b = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int nrows = seq_len_of(rows_per_b, b, rows);
+  const int r0 = blockIdx.x * HS_ROWS;
+  if (r0 >= nrows) return;
+  for (int i = tid; i < e; i += 256) q_s[i] = q[b * q_bstride + i];
+  __syncthreads();
+  const int cpk = d_k / VEC;
+  float* mypart = part + wave * nvec;
+  for (int it = 0; it < HS_ROWS / 4; ++it) {
+    const int r = r0 + it * 4 + wave;
+    const bool valid = r < nrows;
+    if (valid) {
+      const typename ET::elem* row = M + b * m_bstride + (long)r * row_pitch;
+      for (int ci = lane; ci < nvec; ci += 64) {
+        float v[VEC];
+        ET::load(row + ci * VEC, v);
+        float acc = 0.f;
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) acc = fmaf(v[j], q_s[ci * VEC + j], acc);
+        mypart[ci] = acc;
+      }
+    }
+    __syncthreads();
+    if (valid) {
+      for (int h = lane; h < H; h += 64) {
+        float s = 0.f;
+        for (int j = 0; j < cpk; ++j) s += mypart[h * cpk + j];
+        S[b * s_bstride + (long)h * rows + r] = s * scale;
+      }
+    }
+    __syncthreads();
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// dense_scores: S[b][h][t] = scale * sum_c qt[b][h][c] X[b][t][c]; LDS-tiled 64 t x 32 h x 64 c.
+// ------------------------------------------------------------------------------------------------
+constexpr int DS_T = 64, DS_H = 32, DS_C = 64;
+
+template <class ET>
+__global__ __launch_bounds__(256) void dense_scores_kernel(
+    const float* __restrict__ qt, const typename ET::elem* __restrict__ X, long x_bstride,
+    int d_model, const int32_t* __restrict__ seq_lens, int T, int H, float scale,
+    float* __restrict__ S) {
+  __shared__ float Xs[DS_T][DS_C + 1];
+  __shared__ float Qs[DS_H][DS_C + 1];
+  constexpr int VEC = ET::VEC;
+  const int b = blockIdx.z;
+  const int len = seq_len_of(seq_lens, b, T);
+  const int t0 = blockIdx.x * DS_T, h0 = blockIdx.y * DS_H;
+  if (t0 >= len) return;
+  const int tid = threadIdx.x;
+  const int tt = tid & 63, hq = tid >> 6;      // 8 heads per thread
+  float acc[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) acc[j] = 0.f;
+  for (int c0 = 0; c0 < d_model; c0 += DS_C) {
+    // X tile: DS_T rows x DS_C cols in vectors
+    constexpr int VPR = DS_C / VEC;            // vectors per row
+    for (int i = tid; i < DS_T * VPR; i += 256) {
+      const int r = i / VPR, cv = (i % VPR) * VEC;
+      float v[VEC];
+#pragma unroll
+      for (int j = 0; j < VEC; ++j) v[j] = 0.f;
+      const int t = t0 + r;
+      if (t < len && c0 + cv < d_model) ET::load(X + b * x_bstride + (long)t * d_model + c0 + cv, v);
+#pragma unroll
+      for (int j = 0; j < VEC; ++j) Xs[r][cv + j] = v[j];
+    }
+    for (int i = tid; i < DS_H * DS_C; i += 256) {
+      const int hh = i / DS_C, cc = i % DS_C;
+      const int h = h0 + hh, c = c0 + cc;
+      Qs[hh][cc] = (h < H && c < d_model) ? qt[((long)b * H + h) * d_model + c] : 0.f;
+    }
+    __syncthreads();
+#pragma unroll 8
+    for (int cc = 0; cc < DS_C; ++cc) {
+      const float x = Xs[tt][cc];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc[j] = fmaf(x, Qs[hq * 8 + j][cc], acc[j]);
+    }
+    __syncthreads();
+  }
+  const int t = t0 + tt;
+  if (t < len) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int h = h0 + hq * 8 + j;
+      if (h < H) S[((long)b * H + h) * T + t] = acc[j] * scale;
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// weighted_sum: grid (colblocks * headblocks, nsplit, B).  Each workgroup owns 512 columns
+// (2 per thread) and up to 32 heads, walks its split of the context in tiles of 32 rows:
+// P = exp(S - m_local) into LDS, then acc[h][c] += P[t][h] * M[t][c].
+// ------------------------------------------------------------------------------------------------
+constexpr int WS_HB = 32, WS_TT = 32, WS_COLS = 512;
+
+__host__ __device__ inline int split_rows(int T, int nsplit) {
+  int ts = (T + nsplit - 1) / nsplit;
+  return (ts + 31) & ~31;
+}
+
+template <class ET>
+__global__ __launch_bounds__(256) void weighted_sum_kernel(
+    const float* __restrict__ S, const typename ET::elem* __restrict__ M, long m_bstride, int width,
+    const int32_t* __restrict__ seq_lens, int T, int H, int nsplit, int ncolblk,
+    float* __restrict__ Cpart, float* __restrict__ mpart, float* __restrict__ lpart) {
+  __shared__ __attribute__((aligned(16))) float P[WS_TT][WS_HB];
+  __shared__ float m_s[WS_HB];
+  const int b = blockIdx.z, sp = blockIdx.y;
+  const int cb = blockIdx.x % ncolblk, hb = blockIdx.x / ncolblk;
+  const int tid = threadIdx.x;
+  const int len = seq_len_of(seq_lens, b, T);
+  const int ts = split_rows(T, nsplit);
+  const int t0 = sp * ts;
+  const int t1 = min(len, t0 + ts);
+  const int h0 = hb * WS_HB;
+  const int c = cb * WS_COLS + tid * 2;
+  const bool col_ok = c < width;               // width is even (multiple of VEC)
+
+  // phase 0: local max per head
+  const int hh = tid >> 3, sub = tid & 7;
+  const int h = h0 + hh;
+  const float* Srow = S + ((long)b * H + (h < H ? h : 0)) * T;
+  float mx = NEG_INF;
+  if (h < H)
+    for (int t = t0 + sub; t < t1; t += 8) mx = fmaxf(mx, Srow[t]);
+  mx = fmaxf(mx, __shfl_xor(mx, 1));
+  mx = fmaxf(mx, __shfl_xor(mx, 2));
+  mx = fmaxf(mx, __shfl_xor(mx, 4));
+  if (sub == 0) m_s[hh] = mx;
+  __syncthreads();
+
+  float acc[WS_HB][2];
+#pragma unroll
+  for (int i = 0; i < WS_HB; ++i) acc[i][0] = acc[i][1] = 0.f;
+  float lsum = 0.f;
+  const typename ET::elem* Mb = M + b * m_bstride;
+
+  for (int tb = t0; tb < t1; tb += WS_TT) {
+#pragma unroll
+    for (int i = 0; i < WS_TT / 8; ++i) {
+      const int tt = sub + i * 8;
+      const int t = tb + tt;
+      float p = 0.f;
+      if (h < H && t < t1) p = __expf(Srow[t] - mx);
+      P[tt][hh] = p;
+      lsum += p;
+    }
+    __syncthreads();
+    const int nt = min(WS_TT, t1 - tb);
+    if (col_ok) {
+      for (int tt = 0; tt < nt; ++tt) {
+        float k0, k1;
+        ET::two(Mb + (long)(tb + tt) * width + c, k0, k1);
+#pragma unroll
+        for (int g = 0; g < WS_HB; g += 4) {
+          const float4 pv = *reinterpret_cast<const float4*>(&P[tt][g]);
+          acc[g + 0][0] = fmaf(pv.x, k0, acc[g + 0][0]); acc[g + 0][1] = fmaf(pv.x, k1, acc[g + 0][1]);
+          acc[g + 1][0] = fmaf(pv.y, k0, acc[g + 1][0]); acc[g + 1][1] = fmaf(pv.y, k1, acc[g + 1][1]);
+          acc[g + 2][0] = fmaf(pv.z, k0, acc[g + 2][0]); acc[g + 2][1] = fmaf(pv.z, k1, acc[g + 2][1]);
+          acc[g + 3][0] = fmaf(pv.w, k0, acc[g + 3][0]); acc[g + 3][1] = fmaf(pv.w, k1, acc[g + 3][1]);
+        }
+      }
+    }
+    __syncthreads();
+  }
+  lsum += __shfl_xor(lsum, 1);
+  lsum += __shfl_xor(lsum, 2);
+  lsum += __shfl_xor(lsum, 4);
+  const long pbase = ((long)b * nsplit + sp) * H;
+  if (cb == 0 && sub == 0 && h < H) {
+    mpart[pbase + h] = mx;
+    lpart[pbase + h] = lsum;
+  }
+  if (col_ok) {
+#pragma unroll
+    for (int i = 0; i < WS_HB; ++i) {
+      const int hi = h0 + i;
+      if (hi < H)
+        *reinterpret_cast<float2*>(Cpart + (pbase + hi) * width + c) = make_float2(acc[i][0], acc[i][1]);
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// combine: merge the splits (log-sum-exp weights) and normalise.
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ Cpart,
+                                                      const float* __restrict__ mpart,
+                                                      const float* __restrict__ lpart, int nsplit,
+                                                      int H, int width, float* __restrict__ Cn) {
+  const int b = blockIdx.y;
+  const long i = (long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= (long)H * width) return;
+  const int h = (int)(i / width);
+  const int c = (int)(i % width);
+  float m = NEG_INF;
+  for (int s = 0; s < nsplit; ++s) m = fmaxf(m, mpart[((long)b * nsplit + s) * H + h]);
+  float num = 0.f, den = 0.f;
+  for (int s = 0; s < nsplit; ++s) {
+    const long pb = ((long)b * nsplit + s) * H + h;
+    const float ms = mpart[pb];
+    const float w = (ms == NEG_INF) ? 0.f : __expf(ms - m);
+    num = fmaf(w, Cpart[pb * width + c], num);
+    den = fmaf(w, lpart[pb], den);
+  }
+  Cn[((long)b * H + h) * width + c] = num / den;
+}
+
+// ------------------------------------------------------------------------------------------------
+// project: out[b][n] = sum_c Cn[b][n/d_k][c] W[c][n].  Workgroup = 64 output columns x 4 batch
+// rows; its 4 waves interleave over c and are summed through LDS.
+// ------------------------------------------------------------------------------------------------
+template <class ET>
+__global__ __launch_bounds__(256) void project_kernel(const float* __restrict__ Cn,
+                                                      const typename ET::elem* __restrict__ W,
+                                                      int rows, int e, int H, int d_k,
+                                                      float* __restrict__ out, int B) {
+  __shared__ float red[4][4][64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int n = blockIdx.x * 64 + lane;
+  const int b0 = blockIdx.y * 4;
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  if (n < e) {
+    const int h = n / d_k;
+    const float* c0p = Cn + ((long)min(b0 + 0, B - 1) * H + h) * rows;
+    const float* c1p = Cn + ((long)min(b0 + 1, B - 1) * H + h) * rows;
+    const float* c2p = Cn + ((long)min(b0 + 2, B - 1) * H + h) * rows;
+    const float* c3p = Cn + ((long)min(b0 + 3, B - 1) * H + h) * rows;
+    for (int c = wave; c < rows; c += 4) {
+      const float w = ET::one(W + (long)c * e + n);
+      acc[0] = fmaf(c0p[c], w, acc[0]);
+      acc[1] = fmaf(c1p[c], w, acc[1]);
+      acc[2] = fmaf(c2p[c], w, acc[2]);
+      acc[3] = fmaf(c3p[c], w, acc[3]);
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < 4; ++j) red[wave][j][lane] = acc[j];
+  __syncthreads();
+  if (wave == 0 && n < e) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (b0 + j < B)
+        out[(long)(b0 + j) * e + n] = (red[0][j][lane] + red[1][j][lane]) + (red[2][j][lane] + red[3][j][lane]);
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// vanilla K+V decode (flash-decoding layout): one wave per (b, split, head); 16 lanes span the
+// head's d_k columns in 16-byte vectors (NPASS vectors per lane), the 4 lane groups take
+// alternating rows with their own running (m, l, acc), merged at the end.
+// ------------------------------------------------------------------------------------------------
+template <class ET, int NPASS>
+__global__ __launch_bounds__(256) void vanilla_kernel(
+    const float* __restrict__ q, const typename ET::elem* __restrict__ K,
+    const typename ET::elem* __restrict__ V, long bstride, const int32_t* __restrict__ seq_lens,
+    int T, int H, int d_k, int nsplit, float scale, float* __restrict__ accp,
+    float* __restrict__ mpart, float* __restrict__ lpart) {
+  constexpr int VEC = ET::VEC;
+  constexpr int UNR = 4;
+  const int b = blockIdx.z, sp = blockIdx.y;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int h = blockIdx.x * 4 + wave;
+  if (h >= H) return;
+  const int idx = lane & 15, rg = lane >> 4;
+  const int e = H * d_k;
+  const int cph = d_k / VEC;                   // vectors per head row
+  const int len = seq_len_of(seq_lens, b, T);
+  const int ts = split_rows(T, nsplit);
+  const int t0 = sp * ts;
+  const int t1 = min(len, t0 + ts);
+
+  float qv[NPASS][VEC];
+  bool act[NPASS];
+#pragma unroll
+  for (int p = 0; p < NPASS; ++p) {
+    act[p] = (p * 16 + idx) < cph;
+#pragma unroll
+    for (int j = 0; j < VEC; ++j)
+      qv[p][j] = act[p] ? q[(long)b * e + h * d_k + (p * 16 + idx) * VEC + j] * scale : 0.f;
+  }
+  float m = NEG_INF, l = 0.f;
+  float acc[NPASS][VEC];
+#pragma unroll
+  for (int p = 0; p < NPASS; ++p)
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) acc[p][j] = 0.f;
+
+  const typename ET::elem* Kb = K + b * bstride + h * d_k;
+  const typename ET::elem* Vb = V + b * bstride + h * d_k;
+
+  for (int tb = t0 + rg; tb < t1; tb += 4 * UNR) {
+    float kv[UNR][NPASS][VEC], vv[UNR][NPASS][VEC];
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+      const int t = min(tb + u * 4, t1 - 1);
+#pragma unroll
+      for (int p = 0; p < NPASS; ++p) {
+        if (act[p]) {
+          ET::load(Kb + (long)t * e + (p * 16 + idx) * VEC, kv[u][p]);
+          ET::load(Vb + (long)t * e + (p * 16 + idx) * VEC, vv[u][p]);
+        } else {
+#pragma unroll
+          for (int j = 0; j < VEC; ++j) kv[u][p][j] = vv[u][p][j] = 0.f;
+        }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+      float s = 0.f;
+#pragma unroll
+      for (int p = 0; p < NPASS; ++p)
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) s = fmaf(qv[p][j], kv[u][p][j], s);
+      s += __shfl_xor(s, 1);
+      s += __shfl_xor(s, 2);
+      s += __shfl_xor(s, 4);
+      s += __shfl_xor(s, 8);
+      const bool ok = (tb + u * 4) < t1;
+      if (ok) {
+        const float mn = fmaxf(m, s);
+        const float alpha = __expf(m - mn);      // m = -inf first time: exp(-inf) = 0
+        const float pw = __expf(s - mn);
+        l = l * alpha + pw;
+#pragma unroll
+        for (int p = 0; p < NPASS; ++p)
+#pragma unroll
+          for (int j = 0; j < VEC; ++j) acc[p][j] = fmaf(pw, vv[u][p][j], acc[p][j] * alpha);
+        m = mn;
+      }
+    }
+  }
+  // merge the 4 row groups (lanes idx, idx+16, idx+32, idx+48)
+  float mall = fmaxf(m, __shfl_xor(m, 16));
+  mall = fmaxf(mall, __shfl_xor(mall, 32));
+  const float w = (m == NEG_INF) ? 0.f : __expf(m - mall);
+  l *= w;
+  l += __shfl_xor(l, 16);
+  l += __shfl_xor(l, 32);
+#pragma unroll
+  for (int p = 0; p < NPASS; ++p)
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) {
+      float a = acc[p][j] * w;
+      a += __shfl_xor(a, 16);
+      a += __shfl_xor(a, 32);
+      acc[p][j] = a;
+    }
+  const long pb = ((long)b * nsplit + sp) * H + h;
+  if (lane == 0) { mpart[pb] = mall; lpart[pb] = l; }
+  if (rg == 0) {
+#pragma unroll
+    for (int p = 0; p < NPASS; ++p)
+      if (act[p]) {
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) accp[pb * d_k + (p * 16 + idx) * VEC + j] = acc[p][j];
+      }
+  }
+}
+
+__global__ __launch_bounds__(256) void vanilla_combine_kernel(const float* __restrict__ accp,
+                                                              const float* __restrict__ mpart,
+                                                              const float* __restrict__ lpart,
+                                                              int nsplit, int H, int d_k,
+                                                              float* __restrict__ out) {
+  const int b = blockIdx.y;
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= H * d_k) return;
+  const int h = i / d_k, j = i % d_k;
+  float m = NEG_INF;
+  for (int s = 0; s < nsplit; ++s) m = fmaxf(m, mpart[((long)b * nsplit + s) * H + h]);
+  float num = 0.f, den = 0.f;
+  for (int s = 0; s < nsplit; ++s) {
+    const long pb = ((long)b * nsplit + s) * H + h;
+    const float ms = mpart[pb];
+    const float w = (ms == NEG_INF) ? 0.f : __expf(ms - m);
+    num = fmaf(w, accp[pb * d_k + j], num);
+    den = fmaf(w, lpart[pb], den);
+  }
+  out[(long)b * H * d_k + i] = num / den;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------------------
+// launchers
+// ------------------------------------------------------------------------------------------------
+void launch_head_scores(int dtype, const float* q, long q_bstride, const void* M, long m_bstride,
+                        long row_pitch, const int32_t* rows_per_b, int rows, int e, int H, int d_k,
+                        float scale, float* S, long s_bstride, int B, hipStream_t st) {
+  dim3 grid((rows + HS_ROWS - 1) / HS_ROWS, B);
+  const int nvec = e / vec_elems(dtype);
+  const size_t smem = sizeof(float) * ((size_t)e + 4 * (size_t)nvec);
+  if (dtype == DT_BF16) {
+    (void)hipFuncSetAttribute((const void*)head_scores_kernel<BF16>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    hipLaunchKernelGGL(head_scores_kernel<BF16>, grid, dim3(256), smem, st, q, q_bstride,
+                       (const uint16_t*)M, m_bstride, row_pitch, rows_per_b, rows, e, H, d_k, scale, S, s_bstride);
+  } else {
+    (void)hipFuncSetAttribute((const void*)head_scores_kernel<F32>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    hipLaunchKernelGGL(head_scores_kernel<F32>, grid, dim3(256), smem, st, q, q_bstride,
+                       (const float*)M, m_bstride, row_pitch, rows_per_b, rows, e, H, d_k, scale, S, s_bstride);
+  }
+}
+
+void launch_dense_scores(int dtype, const float* qt, const void* X, long x_bstride, int d_model,
+                         const int32_t* seq_lens, int T, int H, float scale, float* S, int B,
+                         hipStream_t st) {
+  dim3 grid((T + DS_T - 1) / DS_T, (H + DS_H - 1) / DS_H, B);
+  if (dtype == DT_BF16)
+    hipLaunchKernelGGL(dense_scores_kernel<BF16>, grid, dim3(256), 0, st, qt, (const uint16_t*)X,
+                       x_bstride, d_model, seq_lens, T, H, scale, S);
+  else
+    hipLaunchKernelGGL(dense_scores_kernel<F32>, grid, dim3(256), 0, st, qt, (const float*)X,
+                       x_bstride, d_model, seq_lens, T, H, scale, S);
+}
+
+void launch_weighted_sum(int dtype, const float* S, const void* M, long m_bstride, int width,
+                         const int32_t* seq_lens, int T, int H, int nsplit, float* Cpart,
+                         float* mpart, float* lpart, int B, hipStream_t st) {
+  const int ncolblk = (width + WS_COLS - 1) / WS_COLS;
+  const int nhb = (H + WS_HB - 1) / WS_HB;
+  dim3 grid(ncolblk * nhb, nsplit, B);
+  if (dtype == DT_BF16)
+    hipLaunchKernelGGL(weighted_sum_kernel<BF16>, grid, dim3(256), 0, st, S, (const uint16_t*)M,
+                       m_bstride, width, seq_lens, T, H, nsplit, ncolblk, Cpart, mpart, lpart);
+  else
+    hipLaunchKernelGGL(weighted_sum_kernel<F32>, grid, dim3(256), 0, st, S, (const float*)M,
+                       m_bstride, width, seq_lens, T, H, nsplit, ncolblk, Cpart, mpart, lpart);
+}
+
+void launch_combine(const float* Cpart, const float* mpart, const float* lpart, int nsplit, int H,
+                    int width, float* Cn, int B, hipStream_t st) {
+  dim3 grid((unsigned)(((long)H * width + 255) / 256), B);
+  hipLaunchKernelGGL(combine_kernel, grid, dim3(256), 0, st, Cpart, mpart, lpart, nsplit, H, width, Cn);
+}
+
+void launch_project(int dtype, const float* Cn, const void* W, int rows, int e, int H, int d_k,
+                    float* out, int B, hipStream_t st) {
+  dim3 grid((e + 63) / 64, (B + 3) / 4);
+  if (dtype == DT_BF16)
+    hipLaunchKernelGGL(project_kernel<BF16>, grid, dim3(256), 0, st, Cn, (const uint16_t*)W, rows, e, H, d_k, out, B);
+  else
+    hipLaunchKernelGGL(project_kernel<F32>, grid, dim3(256), 0, st, Cn, (const float*)W, rows, e, H, d_k, out, B);
+}
+
+void launch_vanilla(int dtype, const float* q, const void* K, const void* V, long bstride,
+                    const int32_t* seq_lens, int T, int H, int d_k, int nsplit, float* acc,
+                    float* mpart, float* lpart, float* out, int B, hipStream_t st) {
+  dim3 grid((H + 3) / 4, nsplit, B);
+  const float scale = 1.0f / sqrtf((float)d_k);
+  const int cph = d_k / vec_elems(dtype);
+  if (dtype == DT_BF16) {
+    if (cph <= 16)
+      hipLaunchKernelGGL((vanilla_kernel<BF16, 1>), grid, dim3(256), 0, st, q, (const uint16_t*)K,
+                         (const uint16_t*)V, bstride, seq_lens, T, H, d_k, nsplit, scale, acc, mpart, lpart);
+    else
+      hipLaunchKernelGGL((vanilla_kernel<BF16, 2>), grid, dim3(256), 0, st, q, (const uint16_t*)K,
+                         (const uint16_t*)V, bstride, seq_lens, T, H, d_k, nsplit, scale, acc, mpart, lpart);
+  } else {
+    if (cph <= 16)
+      hipLaunchKernelGGL((vanilla_kernel<F32, 1>), grid, dim3(256), 0, st, q, (const float*)K,
+                         (const float*)V, bstride, seq_lens, T, H, d_k, nsplit, scale, acc, mpart, lpart);
+    else
+      hipLaunchKernelGGL((vanilla_kernel<F32, 2>), grid, dim3(256), 0, st, q, (const float*)K,
+                         (const float*)V, bstride, seq_lens, T, H, d_k, nsplit, scale, acc, mpart, lpart);
+  }
+  dim3 g2((H * d_k + 255) / 256, B);
+  hipLaunchKernelGGL(vanilla_combine_kernel, g2, dim3(256), 0, st, acc, mpart, lpart, nsplit, H, d_k, out);
+}
+
+}  // namespace slim

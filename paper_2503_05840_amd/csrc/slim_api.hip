@@ -1,0 +1,200 @@
+// C-ABI layer of the slim-attention decode library: argument validation, workspace layout,
+// variant choice and kernel sequencing.  No arithmetic of the method lives here.
+#include "slim_attention.h"
+#include "slim_kernels.h"
+
+#include <math.h>
+#include <mutex>
+
+namespace {
+
+using namespace slim;
+
+constexpr size_t ALIGN = 256;
+inline size_t up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
+
+// Scratch layout shared by the decode entry points.  `width` is the row width of the cached
+// matrix (d for a K-cache, d_model for an X-cache).
+struct Plan {
+  int nsplit = 1;      // context splits of the weighted-sum step
+  int nsplit_v = 1;    // context splits of the vanilla kernel
+  size_t off_S = 0, off_Cpart = 0, off_m = 0, off_l = 0, off_Cn = 0, off_qt = 0;
+  size_t off_vacc = 0, off_vm = 0, off_vl = 0;
+  size_t total = 0;
+};
+
+int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
+
+Plan make_plan(int B, int H, int T, int width, int e) {
+  Plan p;
+  const int ncolblk = (width + 511) / 512, nhb = (H + 31) / 32;
+  const long per_split = (long)B * ncolblk * nhb;
+  p.nsplit = clampi((int)((1024 + per_split - 1) / per_split), 1, clampi((T + 127) / 128, 1, 64));
+  const long per_split_v = (long)B * ((H + 3) / 4);
+  p.nsplit_v = clampi((int)((2048 + per_split_v - 1) / per_split_v), 1, clampi((T + 63) / 64, 1, 256));
+  size_t o = 0;
+  p.off_S = o;      o += up(sizeof(float) * (size_t)B * H * T);
+  p.off_Cpart = o;  o += up(sizeof(float) * (size_t)B * p.nsplit * H * width);
+  p.off_m = o;      o += up(sizeof(float) * (size_t)B * p.nsplit * H);
+  p.off_l = o;      o += up(sizeof(float) * (size_t)B * p.nsplit * H);
+  p.off_Cn = o;     o += up(sizeof(float) * (size_t)B * H * width);
+  p.off_qt = o;     o += up(sizeof(float) * (size_t)B * H * width);
+  p.off_vacc = o;   o += up(sizeof(float) * (size_t)B * p.nsplit_v * e);
+  p.off_vm = o;     o += up(sizeof(float) * (size_t)B * p.nsplit_v * H);
+  p.off_vl = o;     o += up(sizeof(float) * (size_t)B * p.nsplit_v * H);
+  p.total = o;
+  return p;
+}
+
+// Library-owned scratch: one allocation per device, grown on demand, kept until exit.
+struct OwnedScratch { void* ptr = nullptr; size_t bytes = 0; };
+OwnedScratch g_scratch[64];
+std::mutex g_scratch_mu;
+
+int get_workspace(const slim_opts* o, size_t need, char** ws) {
+  if (o && o->workspace) {
+    if (o->workspace_bytes < need) return SLIM_ERR_WORKSPACE;
+    if (((uintptr_t)o->workspace) & 15) return SLIM_ERR_ALIGN;
+    *ws = (char*)o->workspace;
+    return SLIM_OK;
+  }
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return SLIM_ERR_LAUNCH;
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  OwnedScratch& s = g_scratch[dev];
+  if (s.bytes < need) {
+    if (s.ptr) { (void)hipFree(s.ptr); s.ptr = nullptr; s.bytes = 0; }   // hipFree waits for the device
+    if (hipMalloc(&s.ptr, need) != hipSuccess) { s.ptr = nullptr; (void)hipGetLastError(); return SLIM_ERR_LAUNCH; }
+    s.bytes = need;
+  }
+  *ws = (char*)s.ptr;
+  return SLIM_OK;
+}
+
+bool misaligned(const void* p) { return (((uintptr_t)p) & 15) != 0; }
+
+int check_common(int B, int H, int T, int e, int d_k, int width, const slim_opts* o, int* dtype,
+                 long* t_stride) {
+  if (B < 1 || H < 1 || T < 1 || e < 1 || width < 1) return SLIM_ERR_SHAPE;
+  *dtype = o ? o->dtype : SLIM_F32;
+  if (*dtype != SLIM_F32 && *dtype != SLIM_BF16) return SLIM_ERR_DTYPE;
+  const int vec = vec_elems(*dtype);
+  if (d_k < 1 || H * d_k != e) return SLIM_ERR_SHAPE;
+  if (d_k % vec != 0 || width % vec != 0) return SLIM_ERR_SHAPE;
+  *t_stride = (o && o->t_stride) ? (long)o->t_stride : (long)T;
+  if (*t_stride < T) return SLIM_ERR_SHAPE;
+  if (o && o->seq_lens && (((uintptr_t)o->seq_lens) & 3)) return SLIM_ERR_ALIGN;
+  if (o && o->seq_lens_host)
+    for (int b = 0; b < B; ++b)
+      if (o->seq_lens_host[b] < 1 || o->seq_lens_host[b] > T) return SLIM_ERR_SEQLEN;
+  return SLIM_OK;
+}
+
+int launch_status() { return hipGetLastError() == hipSuccess ? SLIM_OK : SLIM_ERR_LAUNCH; }
+
+}  // namespace
+
+extern "C" const char* slim_strerror(int code) {
+  switch (code) {
+    case SLIM_OK: return "ok";
+    case SLIM_ERR_ARG: return "null pointer or negative size";
+    case SLIM_ERR_SHAPE: return "unsupported shape (d % H, d_k vs 16-byte vectors, T, t_stride)";
+    case SLIM_ERR_DTYPE: return "dtype must be SLIM_F32 or SLIM_BF16";
+    case SLIM_ERR_ALIGN: return "device pointer not 16-byte aligned";
+    case SLIM_ERR_WORKSPACE: return "workspace smaller than slim_workspace_bytes()";
+    case SLIM_ERR_SINGULAR: return "W_K singular to working precision or non-finite";
+    case SLIM_ERR_ILLCOND: return "W_K ill-conditioned (rcond < 1e-12); W_KV written but unreliable";
+    case SLIM_ERR_LAUNCH: return "HIP allocation or launch error";
+    case SLIM_ERR_SEQLEN: return "sequence length outside [1, T]";
+    default: return "unknown slim status";
+  }
+}
+
+extern "C" size_t slim_workspace_bytes(int B, int H, int T, int d, int dtype) {
+  if (B < 1 || H < 1 || T < 1 || d < 1) return 0;
+  (void)dtype;
+  // d is the cached row width; the vanilla partials are sized for e = d (K-cache case).
+  return make_plan(B, H, T, d, d).total;
+}
+
+extern "C" int slim_decode(const void* q, const void* Kcache, const void* W_KV, void* out, int B,
+                           int H, int T, int d, const slim_opts* o) {
+  if (!q || !Kcache || !W_KV || !out) return SLIM_ERR_ARG;
+  if (H < 1 || d < 1 || d % H != 0) return SLIM_ERR_SHAPE;
+  const int d_k = d / H;
+  int dtype; long t_stride;
+  if (int rc = check_common(B, H, T, d, d_k, d, o, &dtype, &t_stride)) return rc;
+  if (misaligned(q) || misaligned(Kcache) || misaligned(W_KV) || misaligned(out)) return SLIM_ERR_ALIGN;
+  const Plan p = make_plan(B, H, T, d, d);
+  char* ws;
+  if (int rc = get_workspace(o, p.total, &ws)) return rc;
+  hipStream_t st = o ? (hipStream_t)o->stream : nullptr;
+  const int32_t* lens = o ? o->seq_lens : nullptr;
+  const float scale = 1.0f / sqrtf((float)d_k);
+  float* S = (float*)(ws + p.off_S);
+  float* Cpart = (float*)(ws + p.off_Cpart);
+  float* mpart = (float*)(ws + p.off_m);
+  float* lpart = (float*)(ws + p.off_l);
+  float* Cn = (float*)(ws + p.off_Cn);
+  const long kb = t_stride * d;
+
+  launch_head_scores(dtype, (const float*)q, d, Kcache, kb, d, lens, T, d, H, d_k, scale, S,
+                     (long)H * T, B, st);
+  launch_weighted_sum(dtype, S, Kcache, kb, d, lens, T, H, p.nsplit, Cpart, mpart, lpart, B, st);
+  launch_combine(Cpart, mpart, lpart, p.nsplit, H, d, Cn, B, st);
+  launch_project(dtype, Cn, W_KV, d, d, H, d_k, (float*)out, B, st);
+  return launch_status();
+}
+
+extern "C" int vanilla_kv_decode(const void* q, const void* Kcache, const void* Vcache, void* out,
+                                 int B, int H, int T, int d, const slim_opts* o) {
+  if (!q || !Kcache || !Vcache || !out) return SLIM_ERR_ARG;
+  if (H < 1 || d < 1 || d % H != 0) return SLIM_ERR_SHAPE;
+  const int d_k = d / H;
+  int dtype; long t_stride;
+  if (int rc = check_common(B, H, T, d, d_k, d, o, &dtype, &t_stride)) return rc;
+  if (d_k / vec_elems(dtype) > 32) return SLIM_ERR_SHAPE;
+  if (misaligned(q) || misaligned(Kcache) || misaligned(Vcache) || misaligned(out)) return SLIM_ERR_ALIGN;
+  const Plan p = make_plan(B, H, T, d, d);
+  char* ws;
+  if (int rc = get_workspace(o, p.total, &ws)) return rc;
+  hipStream_t st = o ? (hipStream_t)o->stream : nullptr;
+  launch_vanilla(dtype, (const float*)q, Kcache, Vcache, t_stride * d, o ? o->seq_lens : nullptr, T,
+                 H, d_k, p.nsplit_v, (float*)(ws + p.off_vacc), (float*)(ws + p.off_vm),
+                 (float*)(ws + p.off_vl), (float*)out, B, st);
+  return launch_status();
+}
+
+extern "C" int slim_decode_xcache(const void* q, const void* X, const void* W_K, const void* W_V,
+                                  void* out, int B, int H, int T, int d_model, int d_k,
+                                  const slim_opts* o) {
+  if (!q || !X || !W_K || !W_V || !out) return SLIM_ERR_ARG;
+  if (H < 1 || d_k < 1 || d_model < 1) return SLIM_ERR_SHAPE;
+  const int e = H * d_k;
+  int dtype; long t_stride;
+  if (int rc = check_common(B, H, T, e, d_k, d_model, o, &dtype, &t_stride)) return rc;
+  if (misaligned(q) || misaligned(X) || misaligned(W_K) || misaligned(W_V) || misaligned(out))
+    return SLIM_ERR_ALIGN;
+  const Plan p = make_plan(B, H, T, d_model, d_model);
+  char* ws;
+  if (int rc = get_workspace(o, p.total, &ws)) return rc;
+  hipStream_t st = o ? (hipStream_t)o->stream : nullptr;
+  const int32_t* lens = o ? o->seq_lens : nullptr;
+  const float scale = 1.0f / sqrtf((float)d_k);
+  float* S = (float*)(ws + p.off_S);
+  float* Cpart = (float*)(ws + p.off_Cpart);
+  float* mpart = (float*)(ws + p.off_m);
+  float* lpart = (float*)(ws + p.off_l);
+  float* Cn = (float*)(ws + p.off_Cn);
+  float* qt = (float*)(ws + p.off_qt);
+  const long xb = t_stride * d_model;
+
+  // qt[b][h][c] = sum_j q[b][h d_k + j] W_K[c][h d_k + j]   ("rows" of W_K scored against q)
+  launch_head_scores(dtype, (const float*)q, e, W_K, 0, e, nullptr, d_model, e, H, d_k, 1.0f, qt,
+                     (long)H * d_model, B, st);
+  launch_dense_scores(dtype, qt, X, xb, d_model, lens, T, H, scale, S, B, st);
+  launch_weighted_sum(dtype, S, X, xb, d_model, lens, T, H, p.nsplit, Cpart, mpart, lpart, B, st);
+  launch_combine(Cpart, mpart, lpart, p.nsplit, H, d_model, Cn, B, st);
+  launch_project(dtype, Cn, W_V, d_model, e, H, d_k, (float*)out, B, st);
+  return launch_status();
+}

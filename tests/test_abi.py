@@ -1,0 +1,72 @@
+"""The C-ABI library loads and exports every symbol include/slim_attention.h declares;
+host-side argument validation answers without touching a GPU.  CPU only."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2503_05840_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    src = open(os.path.join(ROOT, "include", "slim_attention.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b((?:slim|vanilla)_[a-z_]+)\s*\(", src)))
+
+
+def test_header_and_binding_name_the_same_entry_points():
+    assert declared_functions() == sorted(binding.EXPORTS)
+
+
+def test_library_exports_every_declared_symbol():
+    lib = binding.load()
+    for name in declared_functions():
+        assert hasattr(lib, name), name
+
+
+def test_strerror_covers_codes():
+    assert binding.strerror(0) == "ok"
+    for code in range(-9, 0):
+        assert "unknown" not in binding.strerror(code)
+    assert "unknown" in binding.strerror(-99)
+
+
+def test_null_and_shape_errors_are_detected_on_the_host():
+    lib = binding.load()
+    o = binding.SlimOpts()
+    o.dtype = binding.SLIM_BF16
+    assert lib.slim_decode(None, None, None, None, 1, 8, 16, 512, ctypes.byref(o)) == -1
+    fake = ctypes.c_void_p(4096)          # never dereferenced: validation fails first
+    assert lib.slim_decode(fake, fake, fake, fake, 1, 7, 16, 512, ctypes.byref(o)) == -2      # d % H
+    assert lib.slim_decode(fake, fake, fake, fake, 1, 128, 16, 512, ctypes.byref(o)) == -2    # d_k=4 < 8
+    assert lib.slim_decode(fake, fake, fake, fake, 1, 8, 0, 512, ctypes.byref(o)) == -2       # T < 1
+    o.dtype = 5
+    assert lib.slim_decode(fake, fake, fake, fake, 1, 8, 16, 512, ctypes.byref(o)) == -3
+    o.dtype = binding.SLIM_BF16
+    odd = ctypes.c_void_p(4100)
+    assert lib.slim_decode(odd, fake, fake, fake, 1, 8, 16, 512, ctypes.byref(o)) == -4
+    assert lib.vanilla_kv_decode(fake, fake, None, fake, 1, 8, 16, 512, ctypes.byref(o)) == -1
+    assert lib.slim_decode_xcache(fake, fake, fake, fake, fake, 1, 8, 16, 60, 16, ctypes.byref(o)) == -2
+
+
+def test_host_sequence_lengths_are_validated():
+    import numpy as np
+    lib = binding.load()
+    o = binding.SlimOpts()
+    o.dtype = binding.SLIM_BF16
+    lens = np.array([5, 0], dtype=np.int32)
+    o.seq_lens_host = lens.ctypes.data
+    fake = ctypes.c_void_p(4096)
+    assert lib.slim_decode(fake, fake, fake, fake, 2, 8, 16, 512, ctypes.byref(o)) == -9
+    lens[1] = 17
+    assert lib.slim_decode(fake, fake, fake, fake, 2, 8, 16, 512, ctypes.byref(o)) == -9
+
+
+def test_workspace_size_is_positive_and_monotone():
+    a = binding.slim_workspace_bytes(1, 8, 256, 512, "f32")
+    b = binding.slim_workspace_bytes(2, 8, 256, 512, "f32")
+    assert 0 < a < b
+    assert binding.slim_workspace_bytes(0, 8, 256, 512, "f32") == 0

@@ -1,0 +1,127 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 CPU oracle on the
+same seeded inputs.  Bars: max norm-wise relative error per head vector <= 1e-4 for fp32
+caches and <= 2e-2 for bf16 caches (fp32 accumulation)."""
+import numpy as np
+import pytest
+
+from paper_2503_05840_amd import binding, synth
+from gpu_harness import KCase, XCase, TOL, say
+
+pytestmark = pytest.mark.gpu
+C = synth.CONFIGS
+
+SMALL = {
+    # several tiles, a ragged tail, every d_k the configs use
+    "cfg0-exact": C[0],
+    "cfg1-like": synth.scaled(C[1], H=8, d=1024, T=1000),
+    "cfg2-like-ragged": synth.scaled(C[2], B=3, H=8, d=768, T=700, len_lo=100),
+    "cfg3-like": synth.scaled(C[3], B=5, T=333),
+    "f32-ragged": synth.scaled(C[0], B=2, H=4, d=256, T=300, len_lo=40),
+    "f32-dk128": synth.scaled(C[0], B=1, H=2, d=256, d_k=128, T=77),
+    "one-head": synth.scaled(C[1], H=1, d=128, T=65),
+}
+VARIANTS = {"auto": binding.VARIANT_AUTO, "generic": binding.VARIANT_GENERIC}
+
+
+@pytest.fixture(scope="module")
+def cases():
+    cache = {}
+
+    def get(name, **kw):
+        key = (name, tuple(sorted(kw.items())))
+        if key not in cache:
+            cache[key] = KCase(SMALL[name], **kw)
+        return cache[key]
+    return get
+
+
+@pytest.mark.parametrize("variant", list(VARIANTS))
+@pytest.mark.parametrize("name", list(SMALL))
+def test_slim_decode_matches_oracle(cases, name, variant):
+    say(f"[case] slim_decode {name} variant={variant}")
+    k = cases(name)
+    e = k.err(k.run_slim(variant=VARIANTS[variant]))
+    say(f"  rel err {e:.3e} (tol {TOL[k.cfg.dtype]})")
+    assert e <= TOL[k.cfg.dtype]
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+def test_vanilla_kv_decode_matches_oracle(cases, name):
+    say(f"[case] vanilla_kv_decode {name}")
+    k = cases(name)
+    e = k.err(k.run_vanilla())
+    say(f"  rel err {e:.3e}")
+    assert e <= TOL[k.cfg.dtype]
+
+
+@pytest.mark.parametrize("factor", [50.0, 2000.0])
+@pytest.mark.parametrize("name", ["cfg1-like", "cfg2-like-ragged", "f32-ragged"])
+def test_peaky_softmax(cases, name, factor):
+    """Scaled queries: running max, rescale and near one-hot weights."""
+    say(f"[case] peaky {name} x{factor}")
+    k = cases(name, q_scale=factor)
+    for variant in VARIANTS.values():
+        e = k.err(k.run_slim(variant=variant))
+        say(f"  slim variant {variant}: {e:.3e}")
+        assert e <= TOL[k.cfg.dtype]
+    e = k.err(k.run_vanilla())
+    assert e <= TOL[k.cfg.dtype]
+
+
+def test_single_row_context_and_length_one_sequences():
+    say("[case] T=1")
+    k = KCase(synth.scaled(C[1], H=4, d=512, T=1))
+    assert k.err(k.run_slim()) <= TOL["bf16"]
+    assert k.err(k.run_vanilla()) <= TOL["bf16"]
+    say("[case] ragged with len 1 and len T")
+    cfg = synth.scaled(C[2], B=4, H=8, d=768, T=130, len_lo=0)
+    k = KCase(cfg, lens=[1, 130, 9, 64])
+    assert k.err(k.run_slim()) <= TOL["bf16"]
+    assert k.err(k.run_vanilla()) <= TOL["bf16"]
+
+
+def test_padded_cache_stride_and_caller_workspace():
+    import torch
+    cfg = synth.scaled(C[2], B=3, H=8, d=768, T=200, len_lo=50)
+    say("[case] t_stride > T, caller workspace")
+    k = KCase(cfg, t_stride=256)
+    need = binding.slim_workspace_bytes(cfg.B, cfg.H, cfg.T, cfg.d, cfg.dtype)
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    a = k.run_slim(workspace=ws)
+    assert k.err(a) <= TOL["bf16"]
+    b = k.run_slim()
+    assert np.array_equal(a, b)
+    small = torch.empty(need // 2, dtype=torch.uint8, device="cuda")
+    with pytest.raises(binding.SlimError) as ei:
+        k.run_slim(workspace=small)
+    assert ei.value.code == -5
+
+
+def test_repeat_calls_are_bitwise_identical(cases):
+    k = cases("cfg2-like-ragged")
+    say("[case] determinism")
+    a, b = k.run_slim(), k.run_slim()
+    assert np.array_equal(a, b)
+    a, b = k.run_vanilla(), k.run_vanilla()
+    assert np.array_equal(a, b)
+
+
+def test_slim_and_vanilla_agree_with_each_other(cases):
+    """Not a parity claim (both are ours): a cross-check that the two kernels see the same data."""
+    k = cases("cfg3-like")
+    a, b = k.run_slim(), k.run_vanilla()
+    from gpu_harness import head_rel_err
+    assert head_rel_err(a, b.astype(np.float64), k.cfg.H) <= 2 * TOL["bf16"]
+
+
+@pytest.mark.parametrize("name,cfg", [
+    ("xcache-bf16", synth.scaled(C[4], B=2, H=16, d=128, d_k=32, T=300)),
+    ("xcache-f32", synth.scaled(C[4], B=1, H=6, d=64, d_k=32, T=70, dtype="f32", x_pre_rounded=False)),
+    ("xcache-wide-heads", synth.scaled(C[4], B=1, H=40, d=256, d_k=128, T=129)),
+])
+def test_xcache_decode_matches_oracle(name, cfg):
+    say(f"[case] slim_decode_xcache {name}")
+    x = XCase(cfg)
+    e = x.err(x.run())
+    say(f"  rel err {e:.3e}")
+    assert e <= TOL[cfg.dtype]
