@@ -82,12 +82,22 @@ typedef struct slim_opts {
   void*          stream;         /* hipStream_t, null => the null stream                          */
   int            variant;        /* 0 = library's choice; other values select an implementation
                                     (see SLIM_VARIANT_*), for tests and tuning                    */
+  float*         stage_ms;       /* host [SLIM_MAX_STAGES], nullable.  Measurement only: when set,
+                                    the call brackets each of its kernels with HIP events on
+                                    `stream`, waits for the stream, and writes each kernel's
+                                    milliseconds in launch order (unused entries = 0)             */
 } slim_opts;
+
+#define SLIM_MAX_STAGES 8
 
 #define SLIM_VARIANT_AUTO      0
 #define SLIM_VARIANT_GENERIC   1   /* plain vector-ALU kernels, any supported shape            */
 #define SLIM_VARIANT_TWOPASS   2   /* bf16: MFMA weighted sum, K read in a score pass and a sum pass */
 #define SLIM_VARIANT_FUSED     3   /* bf16: single pass over K, scores exchanged between workgroups */
+
+/* The implementation SLIM_VARIANT_AUTO resolves to for a K-cache decode of this shape
+ * (one of the SLIM_VARIANT_* values above, never AUTO); 0 on invalid arguments. */
+int slim_variant_for(int B, int H, int T, int d, int dtype);
 
 /* Upper bound of the device scratch any decode call below needs for this shape. */
 size_t slim_workspace_bytes(int B, int H, int T, int d, int dtype);

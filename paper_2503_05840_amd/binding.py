@@ -20,7 +20,8 @@ VARIANT_AUTO, VARIANT_GENERIC, VARIANT_TWOPASS, VARIANT_FUSED = 0, 1, 2, 3
 DTYPES = {"f32": SLIM_F32, "bf16": SLIM_BF16}
 
 EXPORTS = ("slim_strerror", "slim_prepare_wkv", "slim_pack_weights", "slim_workspace_bytes",
-           "slim_decode", "vanilla_kv_decode", "slim_decode_xcache")
+           "slim_variant_for", "slim_decode", "vanilla_kv_decode", "slim_decode_xcache")
+VARIANT_NAMES = {1: "generic", 2: "twopass", 3: "fused"}
 
 
 class SlimOpts(ctypes.Structure):
@@ -33,7 +34,11 @@ class SlimOpts(ctypes.Structure):
         ("workspace_bytes", ctypes.c_size_t),
         ("stream", ctypes.c_void_p),
         ("variant", ctypes.c_int),
+        ("stage_ms", ctypes.POINTER(ctypes.c_float)),
     ]
+
+
+MAX_STAGES = 8
 
 
 class SlimError(RuntimeError):
@@ -65,6 +70,8 @@ def load():
     lib.slim_pack_weights.argtypes = [vp, vp, ci, ci, ci]
     lib.slim_workspace_bytes.restype = ctypes.c_size_t
     lib.slim_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
+    lib.slim_variant_for.restype = ci
+    lib.slim_variant_for.argtypes = [ci, ci, ci, ci, ci]
     op = ctypes.POINTER(SlimOpts)
     lib.slim_decode.restype = ci
     lib.slim_decode.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, op]
@@ -111,8 +118,21 @@ def slim_workspace_bytes(B, H, T, d, dtype: str) -> int:
     return int(load().slim_workspace_bytes(B, H, T, d, DTYPES[dtype]))
 
 
+def auto_variant_name(B, H, T, d, dtype: str) -> str:
+    """Which implementation SLIM_VARIANT_AUTO resolves to for this shape."""
+    return VARIANT_NAMES[int(load().slim_variant_for(B, H, T, d, DTYPES[dtype]))]
+
+
 # ---- device side -----------------------------------------------------------------------------
-def _opts(dtype, seq_lens, seq_lens_host, t_stride, workspace, variant):
+def to_device(a: np.ndarray):
+    """numpy array -> device tensor; uint16 arrays are bf16 bit patterns."""
+    import torch
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def _opts(dtype, seq_lens, seq_lens_host, t_stride, workspace, variant, stage_ms=None):
     import torch
     o = SlimOpts()
     o.dtype = DTYPES[dtype]
@@ -127,7 +147,14 @@ def _opts(dtype, seq_lens, seq_lens_host, t_stride, workspace, variant):
         o.workspace_bytes = workspace.numel() * workspace.element_size()
     o.stream = torch.cuda.current_stream().cuda_stream
     o.variant = int(variant)
+    if stage_ms is not None:      # a ctypes float array of MAX_STAGES entries, filled by the call
+        o.stage_ms = ctypes.cast(stage_ms, ctypes.POINTER(ctypes.c_float))
     return o, keep
+
+
+def new_stage_buffer():
+    """Host buffer for opts.stage_ms (per-kernel milliseconds of one call; measurement only)."""
+    return (ctypes.c_float * MAX_STAGES)()
 
 
 def _dev_ptr(t):
@@ -137,8 +164,8 @@ def _dev_ptr(t):
 
 
 def slim_decode(q, Kcache, W_KV, out, B, H, T, d, dtype="bf16", seq_lens=None, seq_lens_host=None,
-                t_stride=0, workspace=None, variant=VARIANT_AUTO):
-    o, keep = _opts(dtype, seq_lens, seq_lens_host, t_stride, workspace, variant)
+                t_stride=0, workspace=None, variant=VARIANT_AUTO, stage_ms=None):
+    o, keep = _opts(dtype, seq_lens, seq_lens_host, t_stride, workspace, variant, stage_ms)
     rc = load().slim_decode(_dev_ptr(q), _dev_ptr(Kcache), _dev_ptr(W_KV), _dev_ptr(out), B, H, T, d,
                             ctypes.byref(o))
     if rc != SLIM_OK:
@@ -147,8 +174,8 @@ def slim_decode(q, Kcache, W_KV, out, B, H, T, d, dtype="bf16", seq_lens=None, s
 
 
 def vanilla_kv_decode(q, Kcache, Vcache, out, B, H, T, d, dtype="bf16", seq_lens=None,
-                      seq_lens_host=None, t_stride=0, workspace=None, variant=VARIANT_AUTO):
-    o, keep = _opts(dtype, seq_lens, seq_lens_host, t_stride, workspace, variant)
+                      seq_lens_host=None, t_stride=0, workspace=None, variant=VARIANT_AUTO, stage_ms=None):
+    o, keep = _opts(dtype, seq_lens, seq_lens_host, t_stride, workspace, variant, stage_ms)
     rc = load().vanilla_kv_decode(_dev_ptr(q), _dev_ptr(Kcache), _dev_ptr(Vcache), _dev_ptr(out),
                                   B, H, T, d, ctypes.byref(o))
     if rc != SLIM_OK:
@@ -157,8 +184,8 @@ def vanilla_kv_decode(q, Kcache, Vcache, out, B, H, T, d, dtype="bf16", seq_lens
 
 
 def slim_decode_xcache(q, X, W_K, W_V, out, B, H, T, d_model, d_k, dtype="bf16", seq_lens=None,
-                       seq_lens_host=None, t_stride=0, workspace=None, variant=VARIANT_AUTO):
-    o, keep = _opts(dtype, seq_lens, seq_lens_host, t_stride, workspace, variant)
+                       seq_lens_host=None, t_stride=0, workspace=None, variant=VARIANT_AUTO, stage_ms=None):
+    o, keep = _opts(dtype, seq_lens, seq_lens_host, t_stride, workspace, variant, stage_ms)
     rc = load().slim_decode_xcache(_dev_ptr(q), _dev_ptr(X), _dev_ptr(W_K), _dev_ptr(W_V),
                                    _dev_ptr(out), B, H, T, d_model, d_k, ctypes.byref(o))
     if rc != SLIM_OK:

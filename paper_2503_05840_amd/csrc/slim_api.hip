@@ -92,6 +92,33 @@ int check_common(int B, int H, int T, int e, int d_k, int width, const slim_opts
 
 int launch_status() { return hipGetLastError() == hipSuccess ? SLIM_OK : SLIM_ERR_LAUNCH; }
 
+// Optional per-kernel timing (opts->stage_ms): an event before the first kernel and one after
+// each kernel, all on the call's stream; finish() waits for the stream and reads them out.
+class StageTimer {
+ public:
+  StageTimer(const slim_opts* o, hipStream_t st) : out_(o ? o->stage_ms : nullptr), st_(st) {
+    if (!out_) return;
+    for (int i = 0; i < SLIM_MAX_STAGES; ++i) out_[i] = 0.f;
+    for (auto& e : ev_) if (hipEventCreate(&e) != hipSuccess) { out_ = nullptr; return; }
+    (void)hipEventRecord(ev_[0], st_);
+  }
+  void mark() {
+    if (out_ && n_ < SLIM_MAX_STAGES) (void)hipEventRecord(ev_[++n_], st_);
+  }
+  void finish() {
+    if (!out_) return;
+    (void)hipStreamSynchronize(st_);
+    for (int i = 0; i < n_; ++i) (void)hipEventElapsedTime(&out_[i], ev_[i], ev_[i + 1]);
+    for (auto& e : ev_) (void)hipEventDestroy(e);
+    out_ = nullptr;
+  }
+ private:
+  float* out_;
+  hipStream_t st_;
+  hipEvent_t ev_[SLIM_MAX_STAGES + 1];
+  int n_ = 0;
+};
+
 }  // namespace
 
 extern "C" const char* slim_strerror(int code) {
@@ -108,6 +135,19 @@ extern "C" const char* slim_strerror(int code) {
     case SLIM_ERR_SEQLEN: return "sequence length outside [1, T]";
     default: return "unknown slim status";
   }
+}
+
+// Which implementation runs for a K-cache decode of this shape.
+int pick_variant(int requested, int B, int H, int T, int d, int dtype) {
+  (void)B; (void)H; (void)T; (void)d; (void)dtype;
+  if (requested == SLIM_VARIANT_GENERIC) return SLIM_VARIANT_GENERIC;
+  return SLIM_VARIANT_GENERIC;
+}
+
+extern "C" int slim_variant_for(int B, int H, int T, int d, int dtype) {
+  if (B < 1 || H < 1 || T < 1 || d < 1 || d % H != 0) return 0;
+  if (dtype != SLIM_F32 && dtype != SLIM_BF16) return 0;
+  return pick_variant(SLIM_VARIANT_AUTO, B, H, T, d, dtype);
 }
 
 extern "C" size_t slim_workspace_bytes(int B, int H, int T, int d, int dtype) {
@@ -138,11 +178,17 @@ extern "C" int slim_decode(const void* q, const void* Kcache, const void* W_KV, 
   float* Cn = (float*)(ws + p.off_Cn);
   const long kb = t_stride * d;
 
+  StageTimer tm(o, st);
   launch_head_scores(dtype, (const float*)q, d, Kcache, kb, d, lens, T, d, H, d_k, scale, S,
                      (long)H * T, B, st);
+  tm.mark();
   launch_weighted_sum(dtype, S, Kcache, kb, d, lens, T, H, p.nsplit, Cpart, mpart, lpart, B, st);
+  tm.mark();
   launch_combine(Cpart, mpart, lpart, p.nsplit, H, d, Cn, B, st);
+  tm.mark();
   launch_project(dtype, Cn, W_KV, d, d, H, d_k, (float*)out, B, st);
+  tm.mark();
+  tm.finish();
   return launch_status();
 }
 
@@ -159,9 +205,12 @@ extern "C" int vanilla_kv_decode(const void* q, const void* Kcache, const void* 
   char* ws;
   if (int rc = get_workspace(o, p.total, &ws)) return rc;
   hipStream_t st = o ? (hipStream_t)o->stream : nullptr;
+  StageTimer tm(o, st);
   launch_vanilla(dtype, (const float*)q, Kcache, Vcache, t_stride * d, o ? o->seq_lens : nullptr, T,
                  H, d_k, p.nsplit_v, (float*)(ws + p.off_vacc), (float*)(ws + p.off_vm),
                  (float*)(ws + p.off_vl), (float*)out, B, st);
+  tm.mark();
+  tm.finish();
   return launch_status();
 }
 
@@ -190,11 +239,18 @@ extern "C" int slim_decode_xcache(const void* q, const void* X, const void* W_K,
   const long xb = t_stride * d_model;
 
   // qt[b][h][c] = sum_j q[b][h d_k + j] W_K[c][h d_k + j]   ("rows" of W_K scored against q)
+  StageTimer tm(o, st);
   launch_head_scores(dtype, (const float*)q, e, W_K, 0, e, nullptr, d_model, e, H, d_k, 1.0f, qt,
                      (long)H * d_model, B, st);
+  tm.mark();
   launch_dense_scores(dtype, qt, X, xb, d_model, lens, T, H, scale, S, B, st);
+  tm.mark();
   launch_weighted_sum(dtype, S, X, xb, d_model, lens, T, H, p.nsplit, Cpart, mpart, lpart, B, st);
+  tm.mark();
   launch_combine(Cpart, mpart, lpart, p.nsplit, H, d_model, Cn, B, st);
+  tm.mark();
   launch_project(dtype, Cn, W_V, d_model, e, H, d_k, (float*)out, B, st);
+  tm.mark();
+  tm.finish();
   return launch_status();
 }
