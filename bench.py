@@ -30,8 +30,7 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 STAGES = {                      # kernels of one slim_decode call, in launch order, per variant
     "generic": ["head_scores", "weighted_sum", "combine", "project"],
-    "twopass": ["k_scores", "pk_mfma", "combine", "project"],
-    "fused": ["fused_stream", "combine", "project"],
+    "fused": ["fused_stream", "project_mfma"],
 }
 
 
@@ -45,7 +44,7 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=1, choices=[0, 1, 2, 3])
-    ap.add_argument("--variant", default="auto", choices=["auto", "generic", "twopass", "fused"])
+    ap.add_argument("--variant", default="auto", choices=["auto", "generic", "fused"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copies", type=int, default=0, help="K-cache copies to rotate over (0 = enough to exceed 512 MB)")
     args = ap.parse_args()
@@ -97,7 +96,7 @@ def main():
     if ragged:
         kw.update(seq_lens=lens_dev, seq_lens_host=lens)
     variant = {"auto": binding.VARIANT_AUTO, "generic": binding.VARIANT_GENERIC,
-               "twopass": binding.VARIANT_TWOPASS, "fused": binding.VARIANT_FUSED}[args.variant]
+               "fused": binding.VARIANT_FUSED}[args.variant]
 
     def slim(i, **extra):
         binding.slim_decode(q, Ks[i % ncopies], Wkv, out, B, H, T, d, variant=variant, **kw, **extra)
@@ -142,7 +141,7 @@ def main():
     dom = int(np.argmax(acc[:len(names)]))
     k_bytes = float(lens.astype(np.int64).sum()) * d * es            # K-cache rows read once
     w_bytes = float(d) * d * es                                       # W_KV once per step
-    alg_bytes = {"project": w_bytes}.get(names[dom], k_bytes)
+    alg_bytes = {"project": w_bytes, "project_mfma": w_bytes}.get(names[dom], k_bytes)
     kern_s = acc[dom] * 1e-3
     achieved = alg_bytes / kern_s / 1e9
     roofline = {"bound": "hbm", "kernel": names[dom], "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,

@@ -92,8 +92,9 @@ typedef struct slim_opts {
 
 #define SLIM_VARIANT_AUTO      0
 #define SLIM_VARIANT_GENERIC   1   /* plain vector-ALU kernels, any supported shape            */
-#define SLIM_VARIANT_TWOPASS   2   /* bf16: MFMA weighted sum, K read in a score pass and a sum pass */
-#define SLIM_VARIANT_FUSED     3   /* bf16: single pass over K, scores exchanged between workgroups */
+#define SLIM_VARIANT_FUSED     3   /* bf16, H <= 32, d_k <= 128: single pass over K with the weighted
+                                      sum and the projection on MFMA; falls back to GENERIC when
+                                      the shape does not qualify                                */
 
 /* The implementation SLIM_VARIANT_AUTO resolves to for a K-cache decode of this shape
  * (one of the SLIM_VARIANT_* values above, never AUTO); 0 on invalid arguments. */

@@ -1,0 +1,584 @@
+// bf16 fast path of the slim-attention decode step for gfx950 (MI355X).
+//
+//   fused_stream_kernel : one pass over the K-cache.  Softmax arguments (eq. 2), online softmax
+//                         and the full-width weighted sum [softmax(.) K] of eq. 7 option 2, the
+//                         latter as one MFMA contraction for all heads ("all heads in parallel as
+//                         a single matrix-matrix multiplication").  K is read from HBM once.
+//   project_mfma_kernel : log-sum-exp merge of the context splits and the per-head product with
+//                         W_KV,i (eq. 7 option 2, second factor) on MFMA; W_KV is read once.
+//
+// Why workgroups exchange scores.  The weighted sum keeps H x d fp32 accumulators per sequence
+// (512 KB for H=32, d=4096: a whole CU's register file), so the row width has to be split over
+// workgroups; but head h's weights need columns [h d_k, (h+1) d_k) only, which one column owner
+// holds, while every column owner needs every head's weights.  A "group" of G workgroups (one per
+// column unit of <=128 columns) therefore walks the same rows together; each wave computes the
+// scores of the heads inside its unit from the tile it already holds in registers, publishes them
+// to a small ring in global memory as (tag, value) words, prefetches its next tile, then gathers
+// all heads' scores of the tile, and feeds the register-resident tile to the MFMA.  No fences are
+// needed: every 8-byte word carries the tile's tag, so a reader either sees the value of this tile
+// or polls again.  Polling is bounded; a time-out raises an error word instead of hanging.
+//
+// Register tile.  A wave owns 32 rows x 128 columns: lane l loads 16 bytes (8 columns) of 8 rows,
+// column group l%16, row group l/16.  The MFMA (v_mfma_f32_16x16x32_bf16) contracts over rows,
+// so the 8x8 block of each lane is transposed in registers (v_perm_b32) into 8 A-operands, one
+// per column of the lane: A_i[m = l%16][k = (l/16)*8 + j] = K[row (l/16)*8 + j][col (l%16)*8 + i].
+// The B-operand is P^T: lane (n = l%16, l/16) holds the weights of head n for the same 8 rows.
+#include "slim_kernels.h"
+
+#include <math.h>
+
+namespace slim {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr float NEG_INF = -INFINITY;
+constexpr float LOG2E = 1.4426950408889634f;
+
+__device__ __forceinline__ int seq_len_of(const int32_t* lens, int b, int T) {
+  if (!lens) return T;
+  const int n = lens[b];
+  return n < 0 ? 0 : (n > T ? T : n);
+}
+
+__device__ __forceinline__ float bf16_lo(unsigned x) { return __uint_as_float(x << 16); }
+__device__ __forceinline__ float bf16_hi(unsigned x) { return __uint_as_float(x & 0xffff0000u); }
+
+// 8 rows x 8 bf16 columns per lane  ->  8 operands (one per column), each 8 rows of that column.
+__device__ __forceinline__ void transpose8x8(const u32x4 (&kt)[8], u32x4 (&a)[8]) {
+#pragma unroll
+  for (int jp = 0; jp < 4; ++jp) {
+    const u32x4 lo = kt[2 * jp], hi = kt[2 * jp + 1];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      a[2 * c][jp] = __builtin_amdgcn_perm(hi[c], lo[c], 0x05040100u);      // even column: low halves
+      a[2 * c + 1][jp] = __builtin_amdgcn_perm(hi[c], lo[c], 0x07060302u);  // odd column: high halves
+    }
+  }
+}
+
+// Tiles of 32 rows: prefix[b] = number of tiles of sequences 0..b-1.  One thread, B is small.
+__device__ void build_tile_prefix(int* prefix, const int32_t* lens, int B, int T) {
+  if (threadIdx.x == 0) {
+    int acc = 0;
+    prefix[0] = 0;
+    for (int b = 0; b < B; ++b) {
+      acc += (seq_len_of(lens, b, T) + TILE_ROWS - 1) / TILE_ROWS;
+      prefix[b + 1] = acc;
+    }
+  }
+  __syncthreads();
+}
+
+// ------------------------------------------------------------------------------------------------
+// fused stream kernel
+// ------------------------------------------------------------------------------------------------
+template <int NT, int NW>
+__global__ __launch_bounds__(NW * 64) void fused_stream_kernel(const FusedArgs a) {
+  constexpr int NTHR = NW * 64;
+  constexpr int HP = NT * 16;                       // heads padded to the MFMA N tile
+  __shared__ int prefix[FUSED_MAX_B + 1];
+  __shared__ float marr[NW][NT][16];
+  __shared__ float larr[NW][NT][16];
+  __shared__ float buf[NW][NT * 4][64];
+  __shared__ float obuf[HP][128];
+
+  // ---- which group / column unit is this workgroup -------------------------------------------
+  int g, u;
+  {
+    const int i = blockIdx.x;
+    if (a.gpx > 0) {                                // groups packed inside one XCD (WG i -> XCD i % 8)
+      const int x = i & 7, r = i >> 3;
+      const int gx = r / a.G;
+      if (gx >= a.gpx) return;
+      g = x * a.gpx + gx;
+      u = r % a.G;
+    } else {
+      g = i / a.G;
+      u = i % a.G;
+    }
+    if (g >= a.NG) return;
+  }
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int idx = lane & 15, rg = lane >> 4;        // column group / row group of the register tile
+  const int n = idx, kg = rg;                       // head-in-tile / row group of the B operand
+
+  if (blockIdx.x == 0 && a.counters)                // the projection's arrival counters start at 0
+    for (int i = tid; i < a.ncounters; i += NTHR) a.counters[i] = 0;
+
+  build_tile_prefix(prefix, a.seq_lens, a.B, a.T);
+  const int VT = prefix[a.B];
+  const int Qt = (VT + a.NG - 1) / a.NG;            // tiles per group
+  const int v0 = g * Qt, v1 = min(VT, v0 + Qt);
+  if (v0 >= v1) return;
+
+  // ---- lane -> column mapping inside the unit --------------------------------------------------
+  const int hh = idx / a.lphp, li = idx % a.lphp;
+  const int myhead = u * a.hpu + hh;
+  const bool col_active = (li < a.lph) && (hh < a.hpu) && (myhead < a.H);
+  const int mycol = myhead * a.d_k + li * 8;        // first of this lane's 8 columns
+  const bool pub_lane = col_active && (li == 0);    // one lane per head publishes its row group
+  const int ucol0 = u * a.hpu * a.d_k;
+  const int uwc = min(a.hpu * a.d_k, a.d - ucol0);  // columns of this unit
+
+  unsigned it = 0;                                  // tiles this wave's team has processed
+  bool dead = false;                                // a poll timed out: stop waiting, just drain
+  unsigned long long* const team_ring = a.exch + (size_t)(g * NW + w) * EXCH_SLOTS * HP * TILE_ROWS;
+
+  int b = 0;
+  while (prefix[b + 1] <= v0) ++b;
+  for (; b < a.B && prefix[b] < v1; ++b) {
+    const int s0 = max(v0, prefix[b]) - prefix[b];
+    const int s1 = min(v1, prefix[b + 1]) - prefix[b];
+    if (s0 >= s1) continue;
+    const int len = seq_len_of(a.seq_lens, b, a.T);
+    const uint16_t* Kb = a.K + (size_t)b * a.k_bstride;
+
+    float qv[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) qv[j] = col_active ? a.q[(size_t)b * a.d + mycol + j] * a.qscale : 0.f;
+
+    float m[NT], lsum[NT];
+    f32x4 acc[8][NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      m[t] = NEG_INF;
+      lsum[t] = 0.f;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc[i][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    auto load_tile = [&](u32x4 (&kt)[8], int s) {
+      const int r0 = s * TILE_ROWS + rg * 8;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int r = min(r0 + j, len - 1);         // rows past the end re-read the last row; masked later
+        kt[j] = col_active ? *reinterpret_cast<const u32x4*>(Kb + (size_t)r * a.d + mycol) : u32x4{0u, 0u, 0u, 0u};
+      }
+    };
+
+    int s = s0 + w;
+    bool have = s < s1;
+    u32x4 cur[8];
+    if (have) load_tile(cur, s);
+    while (have) {
+      // ---- scores of this unit's heads for the lane's 8 rows (log2 domain) --------------------
+      float sc[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        float d0 = 0.f;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          d0 = fmaf(bf16_lo(cur[j][c]), qv[2 * c], d0);
+          d0 = fmaf(bf16_hi(cur[j][c]), qv[2 * c + 1], d0);
+        }
+        sc[j] = d0;
+      }
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        sc[j] += __shfl_xor(sc[j], 1);
+        sc[j] += __shfl_xor(sc[j], 2);
+        if (a.lphp > 4) sc[j] += __shfl_xor(sc[j], 4);
+        if (a.lphp > 8) sc[j] += __shfl_xor(sc[j], 8);
+      }
+      // ---- publish (tag, score) words -----------------------------------------------------------
+      ++it;
+      const unsigned tag = a.tag_base + it;
+      unsigned long long* ring = team_ring + (size_t)(it & (EXCH_SLOTS - 1)) * HP * TILE_ROWS;
+      if (pub_lane) {
+        unsigned long long* dst = ring + myhead * TILE_ROWS + rg * 8;
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+          __hip_atomic_store(dst + j, ((unsigned long long)tag << 32) | __float_as_uint(sc[j]),
+                             __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+      // ---- prefetch the next tile ---------------------------------------------------------------
+      const int sn = s + NW;
+      const bool haven = sn < s1;
+      u32x4 nxt[8];
+      if (haven) load_tile(nxt, sn);
+
+      // ---- gather every head's scores for my 8 rows --------------------------------------------
+      float sv[NT][8];
+      {
+        int spins = 0;
+        bool ok;
+        do {
+          ok = true;
+#pragma unroll
+          for (int t = 0; t < NT; ++t) {
+            const int h = t * 16 + n;
+            const unsigned long long* src = ring + h * TILE_ROWS + kg * 8;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+              if (h < a.H) {
+                const unsigned long long v = __hip_atomic_load(src + j, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                ok = ok && ((unsigned)(v >> 32) == tag);
+                sv[t][j] = __uint_as_float((unsigned)v);
+              } else {
+                sv[t][j] = NEG_INF;
+              }
+            }
+          }
+          ok = __all(ok) != 0;
+          if (!ok) {
+            if (dead || ++spins > a.spin_limit) {
+              if (!dead && lane == 0) atomicExch(a.err, (int)a.launch_id);
+              dead = true;
+              break;
+            }
+            __builtin_amdgcn_s_sleep(16);
+          }
+        } while (!ok);
+      }
+
+      // ---- online softmax (per wave), weights as the bf16 B operand ----------------------------
+      const int row0 = s * TILE_ROWS + kg * 8;
+      bf16x8 pb[NT];
+#pragma unroll
+      for (int t = 0; t < NT; ++t) {
+        float tmax = NEG_INF;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          if (row0 + j >= len) sv[t][j] = NEG_INF;
+          tmax = fmaxf(tmax, sv[t][j]);
+        }
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+        const float mn = fmaxf(m[t], tmax);
+        float alpha = 1.f, psum = 0.f;
+        if (mn == NEG_INF) {                        // padded head: no weights at all
+#pragma unroll
+          for (int j = 0; j < 8; ++j) pb[t][j] = (__bf16)0.f;
+        } else {
+          alpha = exp2f(m[t] - mn);
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            const __bf16 pr = (__bf16)exp2f(sv[t][j] - mn);
+            pb[t][j] = pr;
+            psum += (float)pr;
+          }
+        }
+        lsum[t] = lsum[t] * alpha + psum;
+        m[t] = mn;
+        if (__any(alpha != 1.f)) {
+#pragma unroll
+          for (int i = 0; i < 8; ++i) acc[i][t] *= alpha;
+        }
+      }
+      // ---- weighted sum of the tile's rows, all heads at once -----------------------------------
+      u32x4 am[8];
+      transpose8x8(cur, am);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const bf16x8 av = __builtin_bit_cast(bf16x8, am[i]);
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+          acc[i][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, pb[t], acc[i][t], 0, 0, 0);
+      }
+      if (haven) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) cur[j] = nxt[j];
+      }
+      s = sn;
+      have = haven;
+    }
+
+    // ---- end of this sequence's share: merge the NW waves and write one partial ------------------
+    const int pid = b + g;
+    __syncthreads();
+    if (kg == 0) {
+#pragma unroll
+      for (int t = 0; t < NT; ++t) marr[w][t][n] = m[t];
+    }
+    __syncthreads();
+    float wsc[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      float mall = NEG_INF;
+#pragma unroll
+      for (int ww = 0; ww < NW; ++ww) mall = fmaxf(mall, marr[ww][t][n]);
+      wsc[t] = (m[t] == NEG_INF) ? 0.f : exp2f(m[t] - mall);
+      float l = lsum[t] * wsc[t];
+      l += __shfl_xor(l, 16);
+      l += __shfl_xor(l, 32);
+      if (kg == 0) larr[w][t][n] = l;
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+#pragma unroll
+      for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) buf[w][t * 4 + r][lane] = acc[i][t][r] * wsc[t];
+      __syncthreads();
+      for (int v = tid; v < NT * 4 * 64; v += NTHR) {
+        const int reg = v >> 6, ln = v & 63;
+        float sum = 0.f;
+#pragma unroll
+        for (int ww = 0; ww < NW; ++ww) sum += buf[ww][reg][ln];
+        const int t = reg >> 2, r = reg & 3;
+        const int h = t * 16 + (ln & 15);
+        const int mi = (ln >> 4) * 4 + r;           // column group (the A operand's M index)
+        const int h2 = mi / a.lphp, l2 = mi % a.lphp;
+        if (l2 < a.lph && h2 < a.hpu) obuf[h][h2 * a.d_k + l2 * 8 + i] = sum;
+      }
+      __syncthreads();
+    }
+    for (int v = tid; v < a.H * uwc; v += NTHR) {
+      const int h = v / uwc, cl = v % uwc;
+      a.Cpart[((size_t)pid * a.H + h) * a.d + ucol0 + cl] = obuf[h][cl];
+    }
+    if (u == 0 && tid < a.H) {
+      const int t = tid >> 4, nn = tid & 15;
+      float mall = NEG_INF, l = 0.f;
+#pragma unroll
+      for (int ww = 0; ww < NW; ++ww) {
+        mall = fmaxf(mall, marr[ww][t][nn]);
+        l += larr[ww][t][nn];
+      }
+      a.mpart[(size_t)pid * a.H + tid] = mall;
+      a.lpart[(size_t)pid * a.H + tid] = l;
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// merge + projection kernel:  out[b][h d_k + j] = sum_c Cn[b][h][c] W[c][h d_k + j]
+// grid (H, CSW, batch chunks of 16*NBT).  Workgroup = 8 waves over its share of the rows of W;
+// the wave tile is the same 32 x 128 register tile as above (rows = c, columns = the head's
+// output columns), A = W tile transposed, B = merged, normalised C^T split in bf16 hi + lo.
+// ------------------------------------------------------------------------------------------------
+template <int NBT>
+__global__ __launch_bounds__(512) void project_mfma_kernel(const ProjArgs a) {
+  constexpr int NW = 8, NTHR = 512;
+  __shared__ int prefix[FUSED_MAX_B + 1];
+  __shared__ int pid0s[16 * NBT], nps[16 * NBT];
+  __shared__ float wpid[16 * NBT][PROJ_MAX_PARTS];
+  __shared__ float buf[NW][NBT * 4][64];
+  __shared__ float obuf[16 * NBT][128];
+  __shared__ int is_last;
+
+  const int h = blockIdx.x, cs = blockIdx.y;
+  const int bbase = blockIdx.z * 16 * NBT;
+  const int nb = min(16 * NBT, a.B - bbase);
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int idx = lane & 15, rg = lane >> 4;
+  const int n = idx, kg = rg;
+
+  // ---- which partials belong to which sequence, and their merge weights for head h ------------
+  if (a.mode == 0) {
+    build_tile_prefix(prefix, a.seq_lens, a.B, a.T);
+  }
+  if (tid < nb) {
+    const int b = bbase + tid;
+    int p0, np;
+    if (a.mode == 0) {
+      const int VT = prefix[a.B];
+      const int Qt = (VT + a.NG - 1) / a.NG;
+      const int gf = prefix[b] / Qt, gl = (prefix[b + 1] - 1) / Qt;
+      p0 = b + gf;
+      np = gl - gf + 1;
+    } else {
+      p0 = b * a.nsplit;
+      np = a.nsplit;
+    }
+    np = min(np, PROJ_MAX_PARTS);
+    float M = NEG_INF;
+    for (int p = 0; p < np; ++p) M = fmaxf(M, a.mpart[(size_t)(p0 + p) * a.H + h]);
+    float L = 0.f;
+    for (int p = 0; p < np; ++p) {
+      const float mp = a.mpart[(size_t)(p0 + p) * a.H + h];
+      const float wgt = (mp == NEG_INF) ? 0.f : exp2f((mp - M) * a.mscale);
+      wpid[tid][p] = wgt;
+      L = fmaf(wgt, a.lpart[(size_t)(p0 + p) * a.H + h], L);
+    }
+    const float inv = 1.f / L;
+    for (int p = 0; p < np; ++p) wpid[tid][p] *= inv;
+    pid0s[tid] = p0;
+    nps[tid] = np;
+  }
+  __syncthreads();
+
+  const int lph = a.d_k / 8;
+  const bool col_active = idx < lph;
+  const uint16_t* Wh = a.W + (size_t)h * a.d_k + idx * 8;
+  const int c_lo = cs * a.crows, c_hi = min(a.rows, c_lo + a.crows);
+  const int ntile = (c_hi - c_lo + TILE_ROWS - 1) / TILE_ROWS;
+
+  f32x4 acc[8][NBT];
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int t = 0; t < NBT; ++t) acc[i][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  for (int ct = w; ct < ntile; ct += NW) {
+    const int c0 = c_lo + ct * TILE_ROWS;
+    u32x4 wt[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int r = min(c0 + rg * 8 + j, a.rows - 1);
+      wt[j] = col_active ? *reinterpret_cast<const u32x4*>(Wh + (size_t)r * a.e) : u32x4{0u, 0u, 0u, 0u};
+    }
+    // B operand: merged C for (b = bt*16 + n, rows c0 + kg*8 .. +8)
+    bf16x8 bhi[NBT], blo[NBT];
+    const int c = c0 + kg * 8;
+#pragma unroll
+    for (int t = 0; t < NBT; ++t) {
+      float cn[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) cn[j] = 0.f;
+      const int bl = t * 16 + n;
+      if (bl < nb && c < c_hi) {
+        const int p0 = pid0s[bl], np = nps[bl];
+        for (int p = 0; p < np; ++p) {
+          const float wgt = wpid[bl][p];
+          const float* src = a.Cpart + ((size_t)(p0 + p) * a.H + h) * a.rows + c;
+          const float4 x0 = *reinterpret_cast<const float4*>(src);
+          const float4 x1 = *reinterpret_cast<const float4*>(src + 4);
+          cn[0] = fmaf(wgt, x0.x, cn[0]); cn[1] = fmaf(wgt, x0.y, cn[1]);
+          cn[2] = fmaf(wgt, x0.z, cn[2]); cn[3] = fmaf(wgt, x0.w, cn[3]);
+          cn[4] = fmaf(wgt, x1.x, cn[4]); cn[5] = fmaf(wgt, x1.y, cn[5]);
+          cn[6] = fmaf(wgt, x1.z, cn[6]); cn[7] = fmaf(wgt, x1.w, cn[7]);
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const __bf16 hi = (__bf16)cn[j];
+        bhi[t][j] = hi;
+        blo[t][j] = (__bf16)(cn[j] - (float)hi);
+      }
+    }
+    u32x4 am[8];
+    transpose8x8(wt, am);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const bf16x8 av = __builtin_bit_cast(bf16x8, am[i]);
+#pragma unroll
+      for (int t = 0; t < NBT; ++t) {
+        acc[i][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bhi[t], acc[i][t], 0, 0, 0);
+        acc[i][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, blo[t], acc[i][t], 0, 0, 0);
+      }
+    }
+  }
+
+  // ---- sum the 8 waves: obuf[b][j] ---------------------------------------------------------------
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+#pragma unroll
+    for (int t = 0; t < NBT; ++t)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) buf[w][t * 4 + r][lane] = acc[i][t][r];
+    __syncthreads();
+    for (int v = tid; v < NBT * 4 * 64; v += NTHR) {
+      const int reg = v >> 6, ln = v & 63;
+      float sum = 0.f;
+#pragma unroll
+      for (int ww = 0; ww < NW; ++ww) sum += buf[ww][reg][ln];
+      const int t = reg >> 2, r = reg & 3;
+      const int bl = t * 16 + (ln & 15);
+      const int mi = (ln >> 4) * 4 + r;
+      if (mi < lph) obuf[bl][mi * 8 + i] = sum;
+    }
+    __syncthreads();
+  }
+
+  if (a.csw == 1) {
+    const bool bad = a.err && *a.err == (int)a.launch_id;      // the stream kernel gave up waiting
+    for (int v = tid; v < nb * a.d_k; v += NTHR) {
+      const int bl = v / a.d_k, j = v % a.d_k;
+      a.out[(size_t)(bbase + bl) * a.e + h * a.d_k + j] = bad ? NAN : obuf[bl][j];
+    }
+    return;
+  }
+  // ---- several workgroups share the rows of W: last one to arrive adds the partial sums ---------
+  for (int v = tid; v < nb * a.d_k; v += NTHR) {
+    const int bl = v / a.d_k, j = v % a.d_k;
+    a.outpart[((size_t)cs * a.B + bbase + bl) * a.e + h * a.d_k + j] = obuf[bl][j];
+  }
+  __threadfence();
+  __syncthreads();
+  if (tid == 0) {
+    const int old = atomicAdd(&a.counters[blockIdx.z * a.H + h], 1);
+    is_last = (old == a.csw - 1);
+  }
+  __syncthreads();
+  if (!is_last) return;
+  __threadfence();
+  for (int v = tid; v < nb * a.d_k; v += NTHR) {
+    const int bl = v / a.d_k, j = v % a.d_k;
+    float sum = 0.f;
+    for (int s = 0; s < a.csw; ++s)
+      sum += __builtin_nontemporal_load(&a.outpart[((size_t)s * a.B + bbase + bl) * a.e + h * a.d_k + j]);
+    if (a.err && *a.err == (int)a.launch_id) sum = NAN;      // the stream kernel gave up waiting
+    a.out[(size_t)(bbase + bl) * a.e + h * a.d_k + j] = sum;
+  }
+  if (tid == 0) a.counters[blockIdx.z * a.H + h] = 0;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------------------
+// host side
+// ------------------------------------------------------------------------------------------------
+bool fused_geometry(int B, int H, int T, int d, FusedGeom* g) {
+  if (H < 1 || d % H != 0) return false;
+  const int d_k = d / H;
+  if (d_k % 8 != 0 || d_k > 128 || H > 32 || B > FUSED_MAX_B) return false;   // H > 32 spills registers
+  g->lph = d_k / 8;
+  int lphp = 1;
+  while (lphp < g->lph) lphp <<= 1;
+  g->lphp = lphp;
+  g->hpu = 16 / lphp;
+  g->G = (H + g->hpu - 1) / g->hpu;
+  g->NT = H <= 16 ? 1 : 2;
+  g->NW = FUSED_WAVES;
+  const int cus = 256;
+  if (g->G > cus) return false;
+  if (g->G <= 32) {
+    g->gpx = 32 / g->G;
+    if (g->gpx > 8) g->gpx = 8;                     // at most PROJ_MAX_PARTS groups
+    g->NG = 8 * g->gpx;
+    g->grid = cus;
+  } else {
+    g->gpx = 0;
+    g->NG = cus / g->G;
+    g->grid = g->NG * g->G;
+  }
+  // no more groups than there is work for: a group needs a few tiles per wave to be worth it
+  const long tiles = (long)B * ((T + TILE_ROWS - 1) / TILE_ROWS);
+  (void)tiles;
+  g->nparts = B + g->NG - 1;
+  return true;
+}
+
+size_t fused_exch_bytes(const FusedGeom& g) {
+  return (size_t)g.NG * g.NW * EXCH_SLOTS * (g.NT * 16) * TILE_ROWS * sizeof(unsigned long long);
+}
+
+void launch_fused_stream(const FusedGeom& g, const FusedArgs& a, hipStream_t st) {
+  dim3 grid(g.grid), block(g.NW * 64);
+  if (g.NT == 1) hipLaunchKernelGGL((fused_stream_kernel<1, FUSED_WAVES>), grid, block, 0, st, a);
+  else hipLaunchKernelGGL((fused_stream_kernel<2, FUSED_WAVES>), grid, block, 0, st, a);
+}
+
+int proj_row_splits(int H, int rows, int B) {
+  const int zb = (B + 63) / 64;
+  int csw = (384 + H * zb - 1) / (H * zb);
+  const int maxs = (rows + 8 * TILE_ROWS - 1) / (8 * TILE_ROWS);   // at least one tile per wave
+  if (csw > maxs) csw = maxs;
+  if (csw < 1) csw = 1;
+  return csw;
+}
+
+void launch_project_mfma(ProjArgs a, hipStream_t st) {
+  const int nbt = a.B <= 16 ? 1 : (a.B <= 32 ? 2 : 4);
+  a.crows = ((a.rows + a.csw - 1) / a.csw + TILE_ROWS - 1) / TILE_ROWS * TILE_ROWS;
+  dim3 grid(a.H, a.csw, (a.B + 16 * nbt - 1) / (16 * nbt)), block(512);
+  if (nbt == 1) hipLaunchKernelGGL(project_mfma_kernel<1>, grid, block, 0, st, a);
+  else if (nbt == 2) hipLaunchKernelGGL(project_mfma_kernel<2>, grid, block, 0, st, a);
+  else hipLaunchKernelGGL(project_mfma_kernel<4>, grid, block, 0, st, a);
+}
+
+}  // namespace slim

@@ -4,6 +4,8 @@
 #include "slim_kernels.h"
 
 #include <math.h>
+#include <atomic>
+#include <chrono>
 #include <mutex>
 
 namespace {
@@ -20,8 +22,14 @@ struct Plan {
   int nsplit_v = 1;    // context splits of the vanilla kernel
   size_t off_S = 0, off_Cpart = 0, off_m = 0, off_l = 0, off_Cn = 0, off_qt = 0;
   size_t off_vacc = 0, off_vm = 0, off_vl = 0;
+  size_t off_exch = 0, off_outpart = 0, off_ctrl = 0;   // bf16 fast path
+  bool fused_ok = false;
+  FusedGeom geom{};
+  int csw = 1;         // row splits of W_KV in the MFMA projection
   size_t total = 0;
 };
+
+constexpr int CTRL_INTS = 4096;   // arrival counters + the error word (last int)
 
 int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
 
@@ -33,15 +41,22 @@ Plan make_plan(int B, int H, int T, int width, int e) {
   const long per_split_v = (long)B * ((H + 3) / 4);
   p.nsplit_v = clampi((int)((2048 + per_split_v - 1) / per_split_v), 1, clampi((T + 63) / 64, 1, 256));
   size_t o = 0;
+  p.fused_ok = (width == e) && fused_geometry(B, H, T, width, &p.geom);
+  size_t nparts = (size_t)B * p.nsplit;
+  if (p.fused_ok && (size_t)p.geom.nparts > nparts) nparts = p.geom.nparts;
+  p.csw = proj_row_splits(H, width, B);
   p.off_S = o;      o += up(sizeof(float) * (size_t)B * H * T);
-  p.off_Cpart = o;  o += up(sizeof(float) * (size_t)B * p.nsplit * H * width);
-  p.off_m = o;      o += up(sizeof(float) * (size_t)B * p.nsplit * H);
-  p.off_l = o;      o += up(sizeof(float) * (size_t)B * p.nsplit * H);
+  p.off_Cpart = o;  o += up(sizeof(float) * nparts * H * width);
+  p.off_m = o;      o += up(sizeof(float) * nparts * H);
+  p.off_l = o;      o += up(sizeof(float) * nparts * H);
   p.off_Cn = o;     o += up(sizeof(float) * (size_t)B * H * width);
   p.off_qt = o;     o += up(sizeof(float) * (size_t)B * H * width);
   p.off_vacc = o;   o += up(sizeof(float) * (size_t)B * p.nsplit_v * e);
   p.off_vm = o;     o += up(sizeof(float) * (size_t)B * p.nsplit_v * H);
   p.off_vl = o;     o += up(sizeof(float) * (size_t)B * p.nsplit_v * H);
+  if (p.fused_ok) { p.off_exch = o; o += up(fused_exch_bytes(p.geom)); }
+  p.off_outpart = o; o += up(sizeof(float) * (size_t)p.csw * B * e);
+  p.off_ctrl = o;    o += up(sizeof(int) * CTRL_INTS);
   p.total = o;
   return p;
 }
@@ -139,10 +154,17 @@ extern "C" const char* slim_strerror(int code) {
 
 // Which implementation runs for a K-cache decode of this shape.
 int pick_variant(int requested, int B, int H, int T, int d, int dtype) {
-  (void)B; (void)H; (void)T; (void)d; (void)dtype;
   if (requested == SLIM_VARIANT_GENERIC) return SLIM_VARIANT_GENERIC;
+  FusedGeom g;
+  const int zb = (B + 63) / 64;
+  if (dtype == SLIM_BF16 && fused_geometry(B, H, T, d, &g) && H * zb < CTRL_INTS) return SLIM_VARIANT_FUSED;
   return SLIM_VARIANT_GENERIC;
 }
+
+// Tags of the score exchange are unique per launch within the process and start at a random
+// point, so words left in a workspace by earlier launches (or an earlier process) never match.
+std::atomic<unsigned> g_tag{(unsigned)std::chrono::steady_clock::now().time_since_epoch().count() * 2654435761u};
+std::atomic<unsigned> g_launch{1};
 
 extern "C" int slim_variant_for(int B, int H, int T, int d, int dtype) {
   if (B < 1 || H < 1 || T < 1 || d < 1 || d % H != 0) return 0;
@@ -179,6 +201,38 @@ extern "C" int slim_decode(const void* q, const void* Kcache, const void* W_KV, 
   const long kb = t_stride * d;
 
   StageTimer tm(o, st);
+  const int variant = pick_variant(o ? o->variant : SLIM_VARIANT_AUTO, B, H, T, d, dtype);
+  if (variant == SLIM_VARIANT_FUSED) {
+    const FusedGeom& g = p.geom;
+    int* ctrl = (int*)(ws + p.off_ctrl);
+    const int zb = (B + 63) / 64;
+    FusedArgs fa{};
+    fa.q = (const float*)q; fa.K = (const uint16_t*)Kcache; fa.k_bstride = kb; fa.seq_lens = lens;
+    fa.T = T; fa.B = B; fa.H = H; fa.d = d; fa.d_k = d_k;
+    fa.G = g.G; fa.NG = g.NG; fa.gpx = g.gpx; fa.lph = g.lph; fa.lphp = g.lphp; fa.hpu = g.hpu;
+    fa.qscale = scale * 1.4426950408889634f;
+    fa.exch = (unsigned long long*)(ws + p.off_exch);
+    const unsigned tiles = (unsigned)B * (unsigned)((T + TILE_ROWS - 1) / TILE_ROWS) + (unsigned)B + 64u;
+    fa.tag_base = g_tag.fetch_add(tiles);
+    unsigned lid = g_launch.fetch_add(1);
+    if (lid == 0) lid = g_launch.fetch_add(1);
+    fa.launch_id = lid;
+    fa.spin_limit = 1 << 15;
+    fa.Cpart = Cpart; fa.mpart = mpart; fa.lpart = lpart;
+    fa.err = ctrl + CTRL_INTS - 1; fa.counters = ctrl; fa.ncounters = H * zb;
+    launch_fused_stream(g, fa, st);
+    tm.mark();
+    ProjArgs pa{};
+    pa.Cpart = Cpart; pa.mpart = mpart; pa.lpart = lpart; pa.W = (const uint16_t*)W_KV;
+    pa.out = (float*)out; pa.outpart = (float*)(ws + p.off_outpart); pa.counters = ctrl;
+    pa.err = ctrl + CTRL_INTS - 1; pa.launch_id = lid; pa.seq_lens = lens;
+    pa.B = B; pa.T = T; pa.H = H; pa.d_k = d_k; pa.rows = d; pa.e = d;
+    pa.NG = g.NG; pa.nsplit = 0; pa.mode = 0; pa.mscale = 1.0f; pa.csw = p.csw;
+    launch_project_mfma(pa, st);
+    tm.mark();
+    tm.finish();
+    return launch_status();
+  }
   launch_head_scores(dtype, (const float*)q, d, Kcache, kb, d, lens, T, d, H, d_k, scale, S,
                      (long)H * T, B, st);
   tm.mark();

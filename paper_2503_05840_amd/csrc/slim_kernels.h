@@ -44,4 +44,54 @@ void launch_vanilla(int dtype, const float* q, const void* K, const void* V, lon
                     const int32_t* seq_lens, int T, int H, int d_k, int nsplit, float* acc,
                     float* mpart, float* lpart, float* out, int B, hipStream_t st);
 
+// ---- bf16 fast path (kernels_bf16.hip) -----------------------------------------------------------
+constexpr int TILE_ROWS = 32;        // cache rows per wave tile
+constexpr int EXCH_SLOTS = 4;        // ring depth of the score exchange (>= 2 is required)
+constexpr int FUSED_MAX_B = 1024;    // sequences per call the fast path handles
+constexpr int FUSED_WAVES = 8;       // waves per workgroup of the stream kernel
+constexpr int PROJ_MAX_PARTS = 64;   // partials per sequence the projection merges
+
+struct FusedGeom {
+  int lph, lphp, hpu;   // active lanes per head (d_k/8), lanes reserved per head, heads per unit
+  int G, NG, gpx;       // column units per group, groups, groups per XCD (0 = not packed)
+  int NT, NW, grid, nparts;
+};
+
+struct FusedArgs {
+  const float* q;
+  const uint16_t* K;
+  long k_bstride;
+  const int32_t* seq_lens;
+  int T, B, H, d, d_k;
+  int G, NG, gpx, lph, lphp, hpu;
+  float qscale;                       // log2(e) / sqrt(d_k): scores live in the log2 domain
+  unsigned long long* exch;           // [NG][NW][EXCH_SLOTS][16*NT][TILE_ROWS] (tag, score) words
+  unsigned tag_base, launch_id;
+  int spin_limit;
+  float* Cpart;                       // [nparts][H][d]
+  float* mpart;                       // [nparts][H]  running max, log2 domain
+  float* lpart;                       // [nparts][H]
+  int* err;                           // set to launch_id when a wait timed out
+  int* counters;                      // arrival counters of the projection, zeroed here
+  int ncounters;
+};
+
+struct ProjArgs {
+  const float* Cpart; const float* mpart; const float* lpart;
+  const uint16_t* W;                  // [rows][e] bf16
+  float* out; float* outpart;         // [B][e], [csw][B][e]
+  int* counters; const int* err; unsigned launch_id;
+  const int32_t* seq_lens;
+  int B, T, H, d_k, rows, e;
+  int NG, nsplit, mode;               // mode 0: partials laid out by the stream kernel; 1: [b][nsplit]
+  float mscale;                       // 1 for log2-domain maxima, log2(e) for natural-log ones
+  int csw, crows;                     // row splits of W across workgroups, rows per split
+};
+
+bool fused_geometry(int B, int H, int T, int d, FusedGeom* g);
+size_t fused_exch_bytes(const FusedGeom& g);
+void launch_fused_stream(const FusedGeom& g, const FusedArgs& a, hipStream_t st);
+int proj_row_splits(int H, int rows, int B);
+void launch_project_mfma(ProjArgs a, hipStream_t st);
+
 }  // namespace slim

@@ -20,7 +20,7 @@ SMALL = {
     "f32-dk128": synth.scaled(C[0], B=1, H=2, d=256, d_k=128, T=77),
     "one-head": synth.scaled(C[1], H=1, d=128, T=65),
 }
-VARIANTS = {"auto": binding.VARIANT_AUTO, "generic": binding.VARIANT_GENERIC}
+VARIANTS = {"auto": binding.VARIANT_AUTO, "generic": binding.VARIANT_GENERIC, "fused": binding.VARIANT_FUSED}
 
 
 @pytest.fixture(scope="module")
