@@ -4,6 +4,7 @@
 #include "slim_kernels.h"
 
 #include <math.h>
+#include <stdlib.h>
 #include <atomic>
 #include <chrono>
 #include <mutex>
@@ -218,6 +219,8 @@ extern "C" int slim_decode(const void* q, const void* Kcache, const void* W_KV, 
     if (lid == 0) lid = g_launch.fetch_add(1);
     fa.launch_id = lid;
     fa.spin_limit = 1 << 15;
+    { int dev = 0; (void)hipGetDevice(&dev); (void)dev; fa.xcd_local = 0; }
+    { static const int dbg = getenv("SLIM_DEBUG") ? atoi(getenv("SLIM_DEBUG")) : 0; fa.debug = dbg; static const int em = getenv("SLIM_EXCH_MODE") ? atoi(getenv("SLIM_EXCH_MODE")) : -1; if (em >= 0) fa.xcd_local = em; }
     fa.Cpart = Cpart; fa.mpart = mpart; fa.lpart = lpart;
     fa.err = ctrl + CTRL_INTS - 1; fa.counters = ctrl; fa.ncounters = H * zb;
     launch_fused_stream(g, fa, st);

@@ -46,7 +46,7 @@ void launch_vanilla(int dtype, const float* q, const void* K, const void* V, lon
 
 // ---- bf16 fast path (kernels_bf16.hip) -----------------------------------------------------------
 constexpr int TILE_ROWS = 32;        // cache rows per wave tile
-constexpr int EXCH_SLOTS = 4;        // ring depth of the score exchange (>= 2 is required)
+constexpr int EXCH_SLOTS = 8;        // ring depth of the score exchange (a power of two >= 4)
 constexpr int FUSED_MAX_B = 1024;    // sequences per call the fast path handles
 constexpr int FUSED_WAVES = 8;       // waves per workgroup of the stream kernel
 constexpr int PROJ_MAX_PARTS = 64;   // partials per sequence the projection merges
@@ -74,6 +74,8 @@ struct FusedArgs {
   int* err;                           // set to launch_id when a wait timed out
   int* counters;                      // arrival counters of the projection, zeroed here
   int ncounters;
+  int xcd_local;                      // 1: a group's workgroups share an XCD, exchange through its L2
+  int debug;                          // timing experiments only (0 in normal use)
 };
 
 struct ProjArgs {
@@ -90,6 +92,7 @@ struct ProjArgs {
 
 bool fused_geometry(int B, int H, int T, int d, FusedGeom* g);
 size_t fused_exch_bytes(const FusedGeom& g);
+bool xcd_round_robin(int device);
 void launch_fused_stream(const FusedGeom& g, const FusedArgs& a, hipStream_t st);
 int proj_row_splits(int H, int rows, int B);
 void launch_project_mfma(ProjArgs a, hipStream_t st);
