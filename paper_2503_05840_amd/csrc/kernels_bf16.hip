@@ -119,8 +119,8 @@ __global__ __launch_bounds__(NW * 64) void fused_stream_kernel(const FusedArgs a
   __shared__ float larr[NW][NT][16];
   __shared__ u32x4 tiles[NW][2][512];              // per wave: two 8 KB landing slots for K tiles
   // the end-of-segment reduction reuses the (then idle) landing slots
-  float (*buf)[NT * 4][64] = reinterpret_cast<float (*)[NT * 4][64]>(&tiles[0][0][0]);
-  float (*obuf)[128] = reinterpret_cast<float (*)[128]>(reinterpret_cast<float*>(&tiles[0][0][0]) + NW * NT * 4 * 64);
+  float* const sbuf = reinterpret_cast<float*>(&tiles[0][0][0]);   // [4][HP][129] floats <= 66 KB
+  static_assert(NW == 8, "the end-of-segment reduction assumes 8 waves (two halves of 4)");
 
   // ---- which group / column unit is this workgroup -------------------------------------------
   int g, u;
@@ -221,6 +221,7 @@ __global__ __launch_bounds__(NW * 64) void fused_stream_kernel(const FusedArgs a
           sv[t][2 * i + 1] = hv ? __uint_as_float(pr[t * 4 + i][2]) : NEG_INF;
         }
       }
+      if (a.debug & 32) return;
       const int row0 = s * TILE_ROWS + kg * 8;
       bf16x8 pb[NT];
 #pragma unroll
@@ -271,7 +272,7 @@ __global__ __launch_bounds__(NW * 64) void fused_stream_kernel(const FusedArgs a
     // score and publish tile k, refill the slot with tile k+2, then sum tile k-1 (kept in
     // registers) once its gather is back.  All vector-memory waits are explicit: operations
     // return in issue order, so "at most N younger ones outstanding" identifies what has landed.
-    const int ntl = (s1 - s0 - w + NW - 1) / NW;
+    const int ntl = (a.debug & 256) ? 0 : (s1 - s0 - w + NW - 1) / NW;
     const int wu = __builtin_amdgcn_readfirstlane(w);
     auto dma_tile = [&](int k) {                      // tile k of this wave -> slot k & 1
       const int r0 = (s0 + w + k * NW) * TILE_ROWS + rg * 8;
@@ -306,10 +307,14 @@ __global__ __launch_bounds__(NW * 64) void fused_stream_kernel(const FusedArgs a
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                  // slot is free again
       }
       u32x4 pr[NT * 4];
-      if (k >= 1) poll_issue<NT>(pr, ring_prev + (n * 4 + kg), HP, xl);
+      if (k >= 1 && !(a.debug & 64)) poll_issue<NT>(pr, ring_prev + (n * 4 + kg), HP, xl);
       if (k < ntl) {
         // ---- scores of this unit's heads for the lane's 8 rows (log2 domain) ------------------
         float sc[8];
+        if (a.debug & 16) {
+#pragma unroll
+          for (int j = 0; j < 8; ++j) sc[j] = __uint_as_float(cur[j][0]);
+        } else {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
           float d0 = 0.f;
@@ -326,6 +331,7 @@ __global__ __launch_bounds__(NW * 64) void fused_stream_kernel(const FusedArgs a
           sc[j] += __shfl_xor(sc[j], 2);
           if (a.lphp > 4) sc[j] += __shfl_xor(sc[j], 4);
           if (a.lphp > 8) sc[j] += __shfl_xor(sc[j], 8);
+        }
         }
         // ---- publish {score, tag, score, tag} words (write-through) ------------------------------
         ++it;
@@ -353,6 +359,7 @@ __global__ __launch_bounds__(NW * 64) void fused_stream_kernel(const FusedArgs a
 
     // ---- end of this sequence's share: merge the NW waves and write one partial ------------------
     const int pid = b + g;
+    if (a.debug & 128) continue;
     __syncthreads();
     if (kg == 0) {
 #pragma unroll
@@ -371,29 +378,45 @@ __global__ __launch_bounds__(NW * 64) void fused_stream_kernel(const FusedArgs a
       l += __shfl_xor(l, 32);
       if (kg == 0) larr[w][t][n] = l;
     }
+    // Sum the waves' accumulators through LDS, half of the waves at a time: sbuf[wave][head][col]
+    // (row pitch 129 floats), written in MFMA layout, read back with one thread per column.
+    float osum[HP / 4];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int jj = 0; jj < HP / 4; ++jj) osum[jj] = 0.f;
+    const int ocl = tid & 127, ohq = tid >> 7;       // this thread's column and first head (then +4, +8, ...)
 #pragma unroll
-      for (int t = 0; t < NT; ++t)
+    for (int half = 0; half < 2; ++half) {
+      if ((w >> 2) == half) {
+        float* mine = sbuf + (size_t)(w & 3) * HP * 129;
 #pragma unroll
-        for (int r = 0; r < 4; ++r) buf[w][t * 4 + r][lane] = acc[i][t][r] * wsc[t];
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+          for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              const int mi = rg * 4 + r;              // column group (the A operand's M index)
+              const int h2 = mi / a.lphp, l2 = mi % a.lphp;
+              if (l2 < a.lph && h2 < a.hpu)
+                mine[(t * 16 + n) * 129 + h2 * a.d_k + l2 * 8 + i] = acc[i][t][r] * wsc[t];
+            }
+      }
       __syncthreads();
-      for (int v = tid; v < NT * 4 * 64; v += NTHR) {
-        const int reg = v >> 6, ln = v & 63;
-        float sum = 0.f;
+      if (ocl < uwc) {
 #pragma unroll
-        for (int ww = 0; ww < NW; ++ww) sum += buf[ww][reg][ln];
-        const int t = reg >> 2, r = reg & 3;
-        const int h = t * 16 + (ln & 15);
-        const int mi = (ln >> 4) * 4 + r;           // column group (the A operand's M index)
-        const int h2 = mi / a.lphp, l2 = mi % a.lphp;
-        if (l2 < a.lph && h2 < a.hpu) obuf[h][h2 * a.d_k + l2 * 8 + i] = sum;
+        for (int jj = 0; jj < HP / 4; ++jj) {
+          const int h = ohq + 4 * jj;
+#pragma unroll
+          for (int ww = 0; ww < 4; ++ww) osum[jj] += sbuf[((size_t)ww * HP + h) * 129 + ocl];
+        }
       }
       __syncthreads();
     }
-    for (int v = tid; v < a.H * uwc; v += NTHR) {
-      const int h = v / uwc, cl = v % uwc;
-      a.Cpart[((size_t)pid * a.H + h) * a.d + ucol0 + cl] = obuf[h][cl];
+    if (ocl < uwc) {
+#pragma unroll
+      for (int jj = 0; jj < HP / 4; ++jj) {
+        const int h = ohq + 4 * jj;
+        if (h < a.H) a.Cpart[((size_t)pid * a.H + h) * a.d + ucol0 + ocl] = osum[jj];
+      }
     }
     if (u == 0 && tid < a.H) {
       const int t = tid >> 4, nn = tid & 15;
@@ -432,12 +455,26 @@ __global__ __launch_bounds__(512) void project_mfma_kernel(const ProjArgs a) {
   const int idx = lane & 15, rg = lane >> 4;
   const int n = idx, kg = rg;
 
+  const int lph = a.d_k / 8;
+  const bool col_active = idx < lph;
+  const uint16_t* Wh = a.W + (size_t)h * a.d_k + idx * 8;
+  const int c_lo = cs * a.crows, c_hi = min(a.rows, c_lo + a.crows);
+  const int ntile = (c_hi - c_lo + TILE_ROWS - 1) / TILE_ROWS;
+  auto load_w = [&](u32x4 (&wt)[8], int ct) {
+    const int c0 = c_lo + ct * TILE_ROWS;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int r = min(c0 + rg * 8 + j, a.rows - 1);
+      wt[j] = col_active ? *reinterpret_cast<const u32x4*>(Wh + (size_t)r * a.e) : u32x4{0u, 0u, 0u, 0u};
+    }
+  };
+  u32x4 wt[8], wn[8];
+  if (w < ntile) load_w(wt, w);                      // in flight while the merge weights are built
+
   // ---- which partials belong to which sequence, and their merge weights for head h ------------
-  if (a.mode == 0) {
-    build_tile_prefix(prefix, a.seq_lens, a.B, a.T);
-  }
-  if (tid < nb) {
-    const int b = bbase + tid;
+  if (a.mode == 0) build_tile_prefix(prefix, a.seq_lens, a.B, a.T);
+  for (int bl = w; bl < nb; bl += NW) {              // one wave per sequence, one lane per partial
+    const int b = bbase + bl;
     int p0, np;
     if (a.mode == 0) {
       const int VT = prefix[a.B];
@@ -450,27 +487,22 @@ __global__ __launch_bounds__(512) void project_mfma_kernel(const ProjArgs a) {
       np = a.nsplit;
     }
     np = min(np, PROJ_MAX_PARTS);
-    float M = NEG_INF;
-    for (int p = 0; p < np; ++p) M = fmaxf(M, a.mpart[(size_t)(p0 + p) * a.H + h]);
-    float L = 0.f;
-    for (int p = 0; p < np; ++p) {
-      const float mp = a.mpart[(size_t)(p0 + p) * a.H + h];
-      const float wgt = (mp == NEG_INF) ? 0.f : exp2f((mp - M) * a.mscale);
-      wpid[tid][p] = wgt;
-      L = fmaf(wgt, a.lpart[(size_t)(p0 + p) * a.H + h], L);
+    float mp = NEG_INF, lp = 0.f;
+    if (lane < np) {
+      mp = a.mpart[(size_t)(p0 + lane) * a.H + h];
+      lp = a.lpart[(size_t)(p0 + lane) * a.H + h];
     }
-    const float inv = 1.f / L;
-    for (int p = 0; p < np; ++p) wpid[tid][p] *= inv;
-    pid0s[tid] = p0;
-    nps[tid] = np;
+    float M = mp;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) M = fmaxf(M, __shfl_xor(M, o));
+    const float wgt = (mp == NEG_INF) ? 0.f : exp2f((mp - M) * a.mscale);
+    float L = wgt * lp;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) L += __shfl_xor(L, o);
+    if (lane < np) wpid[bl][lane] = wgt / L;
+    if (lane == 0) { pid0s[bl] = p0; nps[bl] = np; }
   }
   __syncthreads();
-
-  const int lph = a.d_k / 8;
-  const bool col_active = idx < lph;
-  const uint16_t* Wh = a.W + (size_t)h * a.d_k + idx * 8;
-  const int c_lo = cs * a.crows, c_hi = min(a.rows, c_lo + a.crows);
-  const int ntile = (c_hi - c_lo + TILE_ROWS - 1) / TILE_ROWS;
 
   f32x4 acc[8][NBT];
 #pragma unroll
@@ -480,12 +512,8 @@ __global__ __launch_bounds__(512) void project_mfma_kernel(const ProjArgs a) {
 
   for (int ct = w; ct < ntile; ct += NW) {
     const int c0 = c_lo + ct * TILE_ROWS;
-    u32x4 wt[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const int r = min(c0 + rg * 8 + j, a.rows - 1);
-      wt[j] = col_active ? *reinterpret_cast<const u32x4*>(Wh + (size_t)r * a.e) : u32x4{0u, 0u, 0u, 0u};
-    }
+    const bool more = ct + NW < ntile;
+    if (more) load_w(wn, ct + NW);
     // B operand: merged C for (b = bt*16 + n, rows c0 + kg*8 .. +8)
     bf16x8 bhi[NBT], blo[NBT];
     const int c = c0 + kg * 8;
@@ -526,6 +554,10 @@ __global__ __launch_bounds__(512) void project_mfma_kernel(const ProjArgs a) {
         acc[i][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, blo[t], acc[i][t], 0, 0, 0);
       }
     }
+    if (more) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) wt[j] = wn[j];
+    }
   }
 
   // ---- sum the 8 waves: obuf[b][j] ---------------------------------------------------------------
@@ -558,26 +590,40 @@ __global__ __launch_bounds__(512) void project_mfma_kernel(const ProjArgs a) {
     return;
   }
   // ---- several workgroups share the rows of W: last one to arrive adds the partial sums ---------
+  // No cache-wide fences: the partial sums are stored write-through and waited for (so they are
+  // visible device-wide) before this workgroup's arrival is counted, and the last workgroup reads
+  // them with device-coherent loads.
   for (int v = tid; v < nb * a.d_k; v += NTHR) {
     const int bl = v / a.d_k, j = v % a.d_k;
-    a.outpart[((size_t)cs * a.B + bbase + bl) * a.e + h * a.d_k + j] = obuf[bl][j];
+    float* dst = &a.outpart[((size_t)cs * a.B + bbase + bl) * a.e + h * a.d_k + j];
+    asm volatile("global_store_dword %0, %1, off sc0 sc1" : : "v"(dst), "v"(obuf[bl][j]) : "memory");
   }
-  __threadfence();
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
   if (tid == 0) {
-    const int old = atomicAdd(&a.counters[blockIdx.z * a.H + h], 1);
+    const int old = __hip_atomic_fetch_add(&a.counters[blockIdx.z * a.H + h], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     is_last = (old == a.csw - 1);
   }
   __syncthreads();
   if (!is_last) return;
-  __threadfence();
+  const bool bad = a.err && __hip_atomic_load(a.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (int)a.launch_id;
   for (int v = tid; v < nb * a.d_k; v += NTHR) {
     const int bl = v / a.d_k, j = v % a.d_k;
     float sum = 0.f;
-    for (int s = 0; s < a.csw; ++s)
-      sum += __builtin_nontemporal_load(&a.outpart[((size_t)s * a.B + bbase + bl) * a.e + h * a.d_k + j]);
-    if (a.err && *a.err == (int)a.launch_id) sum = NAN;      // the stream kernel gave up waiting
-    a.out[(size_t)(bbase + bl) * a.e + h * a.d_k + j] = sum;
+    for (int s0 = 0; s0 < a.csw; s0 += 8) {
+      float part[8];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        const int sp = min(s0 + q, a.csw - 1);
+        const float* src = &a.outpart[((size_t)sp * a.B + bbase + bl) * a.e + h * a.d_k + j];
+        asm volatile("global_load_dword %0, %1, off sc1" : "=v"(part[q]) : "v"(src) : "memory");
+      }
+      asm volatile("s_waitcnt vmcnt(0)" : "+v"(part[0]), "+v"(part[1]), "+v"(part[2]), "+v"(part[3]),
+                   "+v"(part[4]), "+v"(part[5]), "+v"(part[6]), "+v"(part[7]) : : "memory");
+#pragma unroll
+      for (int q = 0; q < 8; ++q) if (s0 + q < a.csw) sum += part[q];
+    }
+    a.out[(size_t)(bbase + bl) * a.e + h * a.d_k + j] = bad ? NAN : sum;    // NaN: the stream kernel gave up waiting
   }
   if (tid == 0) a.counters[blockIdx.z * a.H + h] = 0;
 }
@@ -660,10 +706,12 @@ void launch_fused_stream(const FusedGeom& g, const FusedArgs& a, hipStream_t st)
 }
 
 int proj_row_splits(int H, int rows, int B) {
+  // one 32-row tile of W per wave (8 waves = 256 rows per workgroup) unless that makes too many
+  // workgroups; everything a wave needs is then in flight from its first instruction
   const int zb = (B + 63) / 64;
-  int csw = (384 + H * zb - 1) / (H * zb);
-  const int maxs = (rows + 8 * TILE_ROWS - 1) / (8 * TILE_ROWS);   // at least one tile per wave
-  if (csw > maxs) csw = maxs;
+  int csw = (rows + 8 * TILE_ROWS - 1) / (8 * TILE_ROWS);
+  const int cap = (1024 + H * zb - 1) / (H * zb);
+  if (csw > cap) csw = cap;
   if (csw < 1) csw = 1;
   return csw;
 }
