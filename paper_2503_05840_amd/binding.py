@@ -12,7 +12,7 @@ import os
 import numpy as np
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libslim_attention.so")
+LIB_PATH = os.environ.get("SLIM_ATTENTION_LIB") or os.path.join(_PKG, "libslim_attention.so")
 
 SLIM_OK = 0
 SLIM_F32, SLIM_BF16 = 0, 1

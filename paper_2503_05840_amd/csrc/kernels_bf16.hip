@@ -384,21 +384,25 @@ __global__ __launch_bounds__(NW * 64) void fused_stream_kernel(const FusedArgs a
 #pragma unroll
     for (int jj = 0; jj < HP / 4; ++jj) osum[jj] = 0.f;
     const int ocl = tid & 127, ohq = tid >> 7;       // this thread's column and first head (then +4, +8, ...)
+    int ocol[4];                                     // first unit-local column of accumulator row r, or -1
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int mi = rg * 4 + r;                     // column group (the A operand's M index)
+      const int h2 = mi / a.lphp, l2 = mi % a.lphp;
+      ocol[r] = (l2 < a.lph && h2 < a.hpu) ? h2 * a.d_k + l2 * 8 : -1;
+    }
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
       if ((w >> 2) == half) {
-        float* mine = sbuf + (size_t)(w & 3) * HP * 129;
+        float* mine = sbuf + (size_t)(w & 3) * HP * 129 + n * 129;
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
+        for (int r = 0; r < 4; ++r) {
+          if (ocol[r] < 0) continue;
 #pragma unroll
           for (int t = 0; t < NT; ++t)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-              const int mi = rg * 4 + r;              // column group (the A operand's M index)
-              const int h2 = mi / a.lphp, l2 = mi % a.lphp;
-              if (l2 < a.lph && h2 < a.hpu)
-                mine[(t * 16 + n) * 129 + h2 * a.d_k + l2 * 8 + i] = acc[i][t][r] * wsc[t];
-            }
+            for (int i = 0; i < 8; ++i) mine[t * 16 * 129 + ocol[r] + i] = acc[i][t][r] * wsc[t];
+        }
       }
       __syncthreads();
       if (ocl < uwc) {
