@@ -33,6 +33,7 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 constexpr float NEG_INF = -INFINITY;
 constexpr float LOG2E = 1.4426950408889634f;
@@ -45,6 +46,12 @@ __device__ __forceinline__ int seq_len_of(const int32_t* lens, int b, int T) {
 
 __device__ __forceinline__ float bf16_lo(unsigned x) { return __uint_as_float(x << 16); }
 __device__ __forceinline__ float bf16_hi(unsigned x) { return __uint_as_float(x & 0xffff0000u); }
+
+// v + (v of the lane selected by a DPP control inside the 16-lane row); one v_add_f32_dpp
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float v) {
+  return v + __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
 
 // 8 rows x 8 bf16 columns per lane  ->  8 operands (one per column), each 8 rows of that column.
 __device__ __forceinline__ void transpose8x8(const u32x4 (&kt)[8], u32x4 (&a)[8]) {
@@ -161,6 +168,10 @@ __global__ __launch_bounds__(NW * 64) void fused_stream_kernel(const FusedArgs a
   const int uwc = min(a.hpu * a.d_k, a.d - ucol0);  // columns of this unit
 
   const int xl = a.xcd_local;
+  const bool all_active = __all(col_active) != 0;    // every lane of the wave owns live columns
+  const bool heads_full = (a.H == HP);               // no padded heads in the MFMA N tiles
+  const unsigned pitchB = (unsigned)a.d * 2u;        // bytes per cache row
+  const int wu = __builtin_amdgcn_readfirstlane(w);
   unsigned it = 0;                                  // tiles this wave's team has processed
   bool dead = false;                                // a poll timed out: stop waiting, just drain
   u32x4* const team_ring = reinterpret_cast<u32x4*>(a.exch) + (size_t)(g * NW + w) * EXCH_SLOTS * (HP * 16);
@@ -174,34 +185,45 @@ __global__ __launch_bounds__(NW * 64) void fused_stream_kernel(const FusedArgs a
     const int len = seq_len_of(a.seq_lens, b, a.T);
     const uint16_t* Kb = a.K + (size_t)b * a.k_bstride;
 
-    float qv[8];
+    // query for this lane's 8 columns, pre-scaled (log2 domain), split into bf16 hi + lo pairs so
+    // that the score dot products run on v_dot2c_f32_bf16 without losing the fp32 query
+    unsigned qh[4], ql[4];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) qv[j] = col_active ? a.q[(size_t)b * a.d + mycol + j] * a.qscale : 0.f;
+    for (int c = 0; c < 4; ++c) {
+      const float f0 = col_active ? a.q[(size_t)b * a.d + mycol + 2 * c] * a.qscale : 0.f;
+      const float f1 = col_active ? a.q[(size_t)b * a.d + mycol + 2 * c + 1] * a.qscale : 0.f;
+      const __bf16 h0 = (__bf16)f0, h1 = (__bf16)f1;
+      const bf16x2 hi = {h0, h1};
+      const bf16x2 lo = {(__bf16)(f0 - (float)h0), (__bf16)(f1 - (float)h1)};
+      qh[c] = __builtin_bit_cast(unsigned, hi);
+      ql[c] = __builtin_bit_cast(unsigned, lo);
+    }
 
-    float m[NT], lsum[NT];
-    f32x4 acc[8][NT];
+    float m[NT];
+    f32x4 acc[8][NT], accl[NT];                      // accl: sum of the weights (an all-ones A operand)
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
       m[t] = NEG_INF;
-      lsum[t] = 0.f;
+      accl[t] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int i = 0; i < 8; ++i) acc[i][t] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
-
+    const unsigned lane_off = (unsigned)(rg * 8) * pitchB + (unsigned)mycol * 2u;
 
     // Sum one tile: check the gathered words' tags (re-polling while any is missing), online
     // softmax per wave, weights as the bf16 B operand, MFMA over the tile held in `kt`.
     auto consume = [&](u32x4 (&pr)[NT * 4], const u32x4 (&kt)[8], int s, unsigned tag, u32x4* ring) {
       int spins = 0;
       for (;;) {
-        bool ok = true;
+        unsigned bad = 0;
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
-          const bool hv = (t * 16 + n) < a.H;
+          unsigned bt = 0;
 #pragma unroll
-          for (int i = 0; i < 4; ++i) ok = ok && (!hv || (pr[t * 4 + i][1] == tag && pr[t * 4 + i][3] == tag));
+          for (int i = 0; i < 4; ++i) bt |= (pr[t * 4 + i][1] ^ tag) | (pr[t * 4 + i][3] ^ tag);
+          bad |= (heads_full || (t * 16 + n) < a.H) ? bt : 0u;
         }
-        if ((a.debug & 4) || __all(ok)) break;
+        if (__all(bad == 0)) break;
         if (dead || ++spins > a.spin_limit) {
           if (!dead && lane == 0) atomicExch(a.err, (int)a.launch_id);
           dead = true;
@@ -211,52 +233,46 @@ __global__ __launch_bounds__(NW * 64) void fused_stream_kernel(const FusedArgs a
         poll_issue<NT>(pr, ring + (n * 4 + kg), HP, xl);
         poll_wait<NT, 0>(pr);
       }
-      float sv[NT][8];
-#pragma unroll
-      for (int t = 0; t < NT; ++t) {
-        const bool hv = (t * 16 + n) < a.H;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          sv[t][2 * i] = hv ? __uint_as_float(pr[t * 4 + i][0]) : NEG_INF;
-          sv[t][2 * i + 1] = hv ? __uint_as_float(pr[t * 4 + i][2]) : NEG_INF;
-        }
-      }
-      if (a.debug & 32) return;
+      const bool partial = (s + 1) * TILE_ROWS > len;            // wave-uniform
       const int row0 = s * TILE_ROWS + kg * 8;
       bf16x8 pb[NT];
 #pragma unroll
       for (int t = 0; t < NT; ++t) {
-        float tmax = NEG_INF;
+        float x[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          if (row0 + j >= len) sv[t][j] = NEG_INF;
-          tmax = fmaxf(tmax, sv[t][j]);
+        for (int i = 0; i < 4; ++i) {
+          x[2 * i] = __uint_as_float(pr[t * 4 + i][0]);
+          x[2 * i + 1] = __uint_as_float(pr[t * 4 + i][2]);
         }
+        if (partial) {
+#pragma unroll
+          for (int j = 0; j < 8; ++j) x[j] = (row0 + j < len) ? x[j] : NEG_INF;
+        }
+        if (!heads_full && (t * 16 + n) >= a.H) {                // padded head: no weights at all
+#pragma unroll
+          for (int j = 0; j < 8; ++j) x[j] = NEG_INF;
+        }
+        float tmax = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
         tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
         tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
         const float mn = fmaxf(m[t], tmax);
-        float alpha = 1.f, psum = 0.f;
-        if (mn == NEG_INF) {                        // padded head: no weights at all
+        const float ref = (mn == NEG_INF) ? 0.f : mn;            // all -inf so far: exp2(-inf - 0) = 0
+        const float alpha = __builtin_amdgcn_exp2f(m[t] - ref);
 #pragma unroll
-          for (int j = 0; j < 8; ++j) pb[t][j] = (__bf16)0.f;
-        } else {
-          alpha = exp2f(m[t] - mn);
-#pragma unroll
-          for (int j = 0; j < 8; ++j) {
-            const __bf16 pw = (__bf16)exp2f(sv[t][j] - mn);
-            pb[t][j] = pw;
-            psum += (float)pw;
-          }
-        }
-        lsum[t] = lsum[t] * alpha + psum;
+        for (int j = 0; j < 8; ++j) pb[t][j] = (__bf16)__builtin_amdgcn_exp2f(x[j] - ref);
         m[t] = mn;
         if (__any(alpha != 1.f)) {
+          accl[t] *= alpha;
 #pragma unroll
           for (int i = 0; i < 8; ++i) acc[i][t] *= alpha;
         }
       }
       u32x4 am[8];
       transpose8x8(kt, am);
+      const u32x4 ones_bits = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
+      const bf16x8 ones = __builtin_bit_cast(bf16x8, ones_bits);
+#pragma unroll
+      for (int t = 0; t < NT; ++t) accl[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pb[t], accl[t], 0, 0, 0);
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         const bf16x8 av = __builtin_bit_cast(bf16x8, am[i]);
@@ -272,18 +288,28 @@ __global__ __launch_bounds__(NW * 64) void fused_stream_kernel(const FusedArgs a
     // score and publish tile k, refill the slot with tile k+2, then sum tile k-1 (kept in
     // registers) once its gather is back.  All vector-memory waits are explicit: operations
     // return in issue order, so "at most N younger ones outstanding" identifies what has landed.
-    const int ntl = (a.debug & 256) ? 0 : (s1 - s0 - w + NW - 1) / NW;
-    const int wu = __builtin_amdgcn_readfirstlane(w);
+    const int ntl = (s1 - s0 - w + NW - 1) / NW;
     auto dma_tile = [&](int k) {                      // tile k of this wave -> slot k & 1
-      const int r0 = (s0 + w + k * NW) * TILE_ROWS + rg * 8;
+      const int st = __builtin_amdgcn_readfirstlane(s0 + w + k * NW);
       u32x4* slot = &tiles[wu][k & 1][0];
+      if ((st + 1) * TILE_ROWS <= len && all_active) {
+        // full tile, every lane loads: uniform row base + per-lane 32-bit offset
+        const char* tb = reinterpret_cast<const char*>(Kb) + (size_t)st * TILE_ROWS * pitchB;
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const int r = min(r0 + j, len - 1);           // rows past the end re-read the last row; masked later
-        if (col_active)
+        for (int j = 0; j < 8; ++j)
           __builtin_amdgcn_global_load_lds(
-              (const __attribute__((address_space(1))) void*)(Kb + (size_t)r * a.d + mycol),
+              (const __attribute__((address_space(1))) void*)(tb + (size_t)j * pitchB + lane_off),
               (__attribute__((address_space(3))) void*)(slot + j * 64), 16, 0, 0);
+      } else {
+        const int r0 = st * TILE_ROWS + rg * 8;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const int r = min(r0 + j, len - 1);         // rows past the end re-read the last row; masked later
+          if (col_active)
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void*)(Kb + (size_t)r * a.d + mycol),
+                (__attribute__((address_space(3))) void*)(slot + j * 64), 16, 0, 0);
+        }
       }
     };
     u32x4 cur[8], prev[8];
@@ -300,44 +326,42 @@ __global__ __launch_bounds__(NW * 64) void fused_stream_kernel(const FusedArgs a
         if (k + 1 < ntl) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");   // tile k landed, k+1 may be in flight
         else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          const u32x4 v = tiles[wu][k & 1][j * 64 + lane];
-          cur[j] = col_active ? v : u32x4{0u, 0u, 0u, 0u};
+        for (int j = 0; j < 8; ++j) cur[j] = tiles[wu][k & 1][j * 64 + lane];
+        if (!all_active) {
+#pragma unroll
+          for (int j = 0; j < 8; ++j) cur[j] = col_active ? cur[j] : u32x4{0u, 0u, 0u, 0u};
         }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                  // slot is free again
       }
       u32x4 pr[NT * 4];
-      if (k >= 1 && !(a.debug & 64)) poll_issue<NT>(pr, ring_prev + (n * 4 + kg), HP, xl);
+      if (k >= 1) poll_issue<NT>(pr, ring_prev + (n * 4 + kg), HP, xl);
       if (k < ntl) {
         // ---- scores of this unit's heads for the lane's 8 rows (log2 domain) ------------------
         float sc[8];
-        if (a.debug & 16) {
-#pragma unroll
-          for (int j = 0; j < 8; ++j) sc[j] = __uint_as_float(cur[j][0]);
-        } else {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-          float d0 = 0.f;
+          float d0 = 0.f, d1 = 0.f;
 #pragma unroll
           for (int c = 0; c < 4; ++c) {
-            d0 = fmaf(bf16_lo(cur[j][c]), qv[2 * c], d0);
-            d0 = fmaf(bf16_hi(cur[j][c]), qv[2 * c + 1], d0);
+            const unsigned kw = cur[j][c];             // (a scalar copy: bit_cast of a vector element picks lane 0)
+            const bf16x2 kv = __builtin_bit_cast(bf16x2, kw);
+            d0 = __builtin_amdgcn_fdot2_f32_bf16(kv, __builtin_bit_cast(bf16x2, qh[c]), d0, false);
+            d1 = __builtin_amdgcn_fdot2_f32_bf16(kv, __builtin_bit_cast(bf16x2, ql[c]), d1, false);
           }
-          sc[j] = d0;
+          sc[j] = d0 + d1;
         }
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          sc[j] += __shfl_xor(sc[j], 1);
-          sc[j] += __shfl_xor(sc[j], 2);
-          if (a.lphp > 4) sc[j] += __shfl_xor(sc[j], 4);
-          if (a.lphp > 8) sc[j] += __shfl_xor(sc[j], 8);
-        }
+        for (int j = 0; j < 8; ++j) {                 // sum over the head's lanes, all inside a 16-lane row
+          sc[j] = dpp_add<0xB1>(sc[j]);               // lane ^ 1
+          sc[j] = dpp_add<0x4E>(sc[j]);               // lane ^ 2
+          if (a.lphp > 4) sc[j] = dpp_add<0x141>(sc[j]);   // other quad of the 8-lane half
+          if (a.lphp > 8) sc[j] = dpp_add<0x140>(sc[j]);   // other half of the row
         }
         // ---- publish {score, tag, score, tag} words (write-through) ------------------------------
         ++it;
         tag = a.tag_base + it;
         ring = team_ring + (size_t)(it & (EXCH_SLOTS - 1)) * (HP * 16);
-        if (pub_lane && !(a.debug & 1)) {
+        if (pub_lane) {
 #pragma unroll
           for (int i = 0; i < 4; ++i)
             st_exch(ring + ((i * HP + myhead) * 4 + rg),
@@ -359,7 +383,6 @@ __global__ __launch_bounds__(NW * 64) void fused_stream_kernel(const FusedArgs a
 
     // ---- end of this sequence's share: merge the NW waves and write one partial ------------------
     const int pid = b + g;
-    if (a.debug & 128) continue;
     __syncthreads();
     if (kg == 0) {
 #pragma unroll
@@ -373,10 +396,7 @@ __global__ __launch_bounds__(NW * 64) void fused_stream_kernel(const FusedArgs a
 #pragma unroll
       for (int ww = 0; ww < NW; ++ww) mall = fmaxf(mall, marr[ww][t][n]);
       wsc[t] = (m[t] == NEG_INF) ? 0.f : exp2f(m[t] - mall);
-      float l = lsum[t] * wsc[t];
-      l += __shfl_xor(l, 16);
-      l += __shfl_xor(l, 32);
-      if (kg == 0) larr[w][t][n] = l;
+      if (kg == 0) larr[w][t][n] = accl[t][0] * wsc[t];   // every accumulator row holds the same sum
     }
     // Sum the waves' accumulators through LDS, half of the waves at a time: sbuf[wave][head][col]
     // (row pitch 129 floats), written in MFMA layout, read back with one thread per column.

@@ -446,21 +446,43 @@ __global__ __launch_bounds__(256) void vanilla_combine_kernel(const float* __res
                                                               const float* __restrict__ lpart,
                                                               int nsplit, int H, int d_k,
                                                               float* __restrict__ out) {
-  const int b = blockIdx.y;
-  const int i = blockIdx.x * 256 + threadIdx.x;
-  if (i >= H * d_k) return;
-  const int h = i / d_k, j = i % d_k;
-  float m = NEG_INF;
-  for (int s = 0; s < nsplit; ++s) m = fmaxf(m, mpart[((long)b * nsplit + s) * H + h]);
-  float num = 0.f, den = 0.f;
-  for (int s = 0; s < nsplit; ++s) {
-    const long pb = ((long)b * nsplit + s) * H + h;
-    const float ms = mpart[pb];
-    const float w = (ms == NEG_INF) ? 0.f : __expf(ms - m);
-    num = fmaf(w, accp[pb * d_k + j], num);
-    den = fmaf(w, lpart[pb], den);
+  // one workgroup per (b, h): merge weights of the (<= 256) splits in LDS, then one thread per
+  // output column sums the weighted partial accumulators with independent loads
+  __shared__ float wgt[256];
+  __shared__ float red[256];
+  const int b = blockIdx.y, h = blockIdx.x, tid = threadIdx.x;
+  const long pb0 = ((long)b * nsplit) * H + h;
+  const float ms = tid < nsplit ? mpart[pb0 + (long)tid * H] : NEG_INF;
+  red[tid] = ms;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if (tid < o) red[tid] = fmaxf(red[tid], red[tid + o]);
+    __syncthreads();
   }
-  out[(long)b * H * d_k + i] = num / den;
+  const float m = red[0];
+  __syncthreads();
+  const float w = (ms == NEG_INF) ? 0.f : __expf(ms - m);
+  wgt[tid] = w;
+  red[tid] = tid < nsplit ? w * lpart[pb0 + (long)tid * H] : 0.f;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if (tid < o) red[tid] += red[tid + o];
+    __syncthreads();
+  }
+  const float inv = 1.f / red[0];
+  for (int j = tid; j < d_k; j += 256) {
+    float num = 0.f;
+    int s = 0;
+    for (; s + 8 <= nsplit; s += 8) {
+      float v[8];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) v[q] = accp[(pb0 + (long)(s + q) * H) * d_k + j];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) num = fmaf(wgt[s + q], v[q], num);
+    }
+    for (; s < nsplit; ++s) num = fmaf(wgt[s], accp[(pb0 + (long)s * H) * d_k + j], num);
+    out[((long)b * H + h) * d_k + j] = num * inv;
+  }
 }
 
 }  // namespace
@@ -547,7 +569,7 @@ void launch_vanilla(int dtype, const float* q, const void* K, const void* V, lon
       hipLaunchKernelGGL((vanilla_kernel<F32, 2>), grid, dim3(256), 0, st, q, (const float*)K,
                          (const float*)V, bstride, seq_lens, T, H, d_k, nsplit, scale, acc, mpart, lpart);
   }
-  dim3 g2((H * d_k + 255) / 256, B);
+  dim3 g2(H, B);
   hipLaunchKernelGGL(vanilla_combine_kernel, g2, dim3(256), 0, st, acc, mpart, lpart, nsplit, H, d_k, out);
 }
 

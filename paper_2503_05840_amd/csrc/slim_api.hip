@@ -4,7 +4,6 @@
 #include "slim_kernels.h"
 
 #include <math.h>
-#include <stdlib.h>
 #include <atomic>
 #include <chrono>
 #include <mutex>
@@ -40,7 +39,7 @@ Plan make_plan(int B, int H, int T, int width, int e) {
   const long per_split = (long)B * ncolblk * nhb;
   p.nsplit = clampi((int)((1024 + per_split - 1) / per_split), 1, clampi((T + 127) / 128, 1, 64));
   const long per_split_v = (long)B * ((H + 3) / 4);
-  p.nsplit_v = clampi((int)((2048 + per_split_v - 1) / per_split_v), 1, clampi((T + 63) / 64, 1, 256));
+  p.nsplit_v = clampi((int)((1024 + per_split_v - 1) / per_split_v), 1, clampi((T + 127) / 128, 1, 256));
   size_t o = 0;
   p.fused_ok = (width == e) && fused_geometry(B, H, T, width, &p.geom);
   size_t nparts = (size_t)B * p.nsplit;
@@ -220,7 +219,6 @@ extern "C" int slim_decode(const void* q, const void* Kcache, const void* W_KV, 
     fa.launch_id = lid;
     fa.spin_limit = 1 << 15;
     { int dev = 0; (void)hipGetDevice(&dev); (void)dev; fa.xcd_local = 0; }
-    { static const int dbg = getenv("SLIM_DEBUG") ? atoi(getenv("SLIM_DEBUG")) : 0; fa.debug = dbg; static const int em = getenv("SLIM_EXCH_MODE") ? atoi(getenv("SLIM_EXCH_MODE")) : -1; if (em >= 0) fa.xcd_local = em; }
     fa.Cpart = Cpart; fa.mpart = mpart; fa.lpart = lpart;
     fa.err = ctrl + CTRL_INTS - 1; fa.counters = ctrl; fa.ncounters = H * zb;
     launch_fused_stream(g, fa, st);

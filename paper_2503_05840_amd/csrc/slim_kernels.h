@@ -75,7 +75,6 @@ struct FusedArgs {
   int* counters;                      // arrival counters of the projection, zeroed here
   int ncounters;
   int xcd_local;                      // 1: a group's workgroups share an XCD, exchange through its L2
-  int debug;                          // timing experiments only (0 in normal use)
 };
 
 struct ProjArgs {
