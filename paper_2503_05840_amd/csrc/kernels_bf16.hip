@@ -82,7 +82,10 @@ __device__ __forceinline__ u32x4 ld_exch(const u32x4* p, int mode) {
   return v;
 }
 __device__ __forceinline__ void st_exch(u32x4* p, u32x4 v, int mode) {
-  asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" : : "v"(p), "v"(v) : "memory");
+  // The trailing s_nop matters: a store of more than 64 bits still reads its data registers in
+  // the wait states after it issues, and the compiler (which pads its own stores) is free to
+  // overwrite the inputs of an asm statement with the very next VALU instruction.
+  asm volatile("s_nop 1\n\tglobal_store_dwordx4 %0, %1, off sc0 sc1\n\ts_nop 1" : : "v"(p), "v"(v) : "memory");
 }
 template <int NT>
 __device__ __forceinline__ void poll_issue(u32x4 (&pr)[NT * 4], const u32x4* lane_base, int HP, int mode) {

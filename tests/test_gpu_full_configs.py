@@ -1,0 +1,75 @@
+"""GPU parity at the full sizes of the five configs, in the launch configuration bench.py
+times (library-chosen variant, ragged lengths where the config has them).  Where the fp64
+oracle for the whole batch would take too long, a fixed sample of sequences is compared
+(shortest, longest and two seeded picks for config 2; two sequences for config 4) and the
+rest of the batch is checked for finiteness and against the vanilla K+V kernel."""
+import numpy as np
+import pytest
+
+from paper_2503_05840_amd import binding, synth
+from gpu_harness import KCase, XCase, TOL, head_rel_err, say
+
+pytestmark = pytest.mark.gpu
+C = synth.CONFIGS
+
+
+def test_config1_codellama_16k_full():
+    say("[case] config 1 full size (B=1 H=32 d=4096 T=16384 bf16)")
+    k = KCase(C[1])
+    assert binding.auto_variant_name(1, 32, 16384, 4096, "bf16") == "fused"
+    a = k.run_slim()
+    e = k.err(a)
+    say(f"  slim rel err {e:.3e}")
+    assert e <= TOL["bf16"]
+    assert np.array_equal(a, k.run_slim())                       # bitwise repeatable
+    ev = k.err(k.run_vanilla())
+    say(f"  vanilla rel err {ev:.3e}")
+    assert ev <= TOL["bf16"]
+    eg = k.err(k.run_slim(variant=binding.VARIANT_GENERIC))
+    say(f"  slim (generic kernels) rel err {eg:.3e}")
+    assert eg <= TOL["bf16"]
+    k.set_query_scale(50.0)                                      # peaky softmax at full length
+    e50 = k.err(k.run_slim())
+    say(f"  slim rel err with q x50: {e50:.3e}")
+    assert e50 <= TOL["bf16"]
+
+
+def test_config3_whisper_cross_attention_full():
+    say("[case] config 3 full size (B=64 H=20 d=1280 T=1500 bf16)")
+    k = KCase(C[3])
+    e = k.err(k.run_slim())
+    say(f"  slim rel err {e:.3e} over all 64 sequences")
+    assert e <= TOL["bf16"]
+    ev = k.err(k.run_vanilla())
+    say(f"  vanilla rel err {ev:.3e}")
+    assert ev <= TOL["bf16"]
+
+
+def test_config2_phi3_ragged_batch_sampled():
+    cfg = C[2]
+    lens = synth.make_problem(synth.scaled(cfg, T=cfg.T), keep=set()).lengths
+    rng = np.random.default_rng(7)
+    picks = {int(np.argmin(lens)), int(np.argmax(lens))}
+    while len(picks) < 4:
+        picks.add(int(rng.integers(0, cfg.B)))
+    say(f"[case] config 2 full size (B=16 H=32 d=3072 ragged {lens.min()}..{lens.max()}); oracle on sequences {sorted(picks)}")
+    k = KCase(cfg, oracle_seqs=picks)
+    a = k.run_slim()
+    e = k.err(a)
+    say(f"  slim rel err {e:.3e} on the sampled sequences")
+    assert e <= TOL["bf16"]
+    v = k.run_vanilla()
+    assert np.isfinite(a).all() and np.isfinite(v).all()
+    cross = head_rel_err(a, v.astype(np.float64), cfg.H)          # all 16 sequences, kernel vs kernel
+    say(f"  slim vs vanilla over the whole batch: {cross:.3e}")
+    assert cross <= 2 * TOL["bf16"]
+
+
+def test_config4_t5_xcache_sampled():
+    cfg = C[4]
+    say("[case] config 4 full size (B=8 H=128 d_model=1024 d_k=128 T=4096); oracle on sequences 0 and 5")
+    x = XCase(cfg, oracle_seqs={0, 5})
+    out = x.run()
+    e = x.err(out)
+    say(f"  xcache rel err {e:.3e}")
+    assert e <= TOL["bf16"]

@@ -19,6 +19,11 @@ SMALL = {
     "f32-ragged": synth.scaled(C[0], B=2, H=4, d=256, T=300, len_lo=40),
     "f32-dk128": synth.scaled(C[0], B=1, H=2, d=256, d_k=128, T=77),
     "one-head": synth.scaled(C[1], H=1, d=128, T=65),
+    # every wave of the stream kernel's workgroups busy, two heads per column unit, several tiles
+    # per wave and several sequences per group
+    "whisper-width-all-waves": synth.scaled(C[3], B=1, T=6144),
+    "two-heads-per-unit-multi-tile": synth.scaled(C[3], B=3, H=32, d=2048, T=5000, len_lo=3000),
+    "dk96-multi-tile": synth.scaled(C[2], B=2, T=9000, len_lo=4000),
 }
 VARIANTS = {"auto": binding.VARIANT_AUTO, "generic": binding.VARIANT_GENERIC, "fused": binding.VARIANT_FUSED}
 
@@ -59,12 +64,13 @@ def test_vanilla_kv_decode_matches_oracle(cases, name):
 def test_peaky_softmax(cases, name, factor):
     """Scaled queries: running max, rescale and near one-hot weights."""
     say(f"[case] peaky {name} x{factor}")
-    k = cases(name, q_scale=factor)
+    k = cases(name).set_query_scale(factor)
     for variant in VARIANTS.values():
         e = k.err(k.run_slim(variant=variant))
         say(f"  slim variant {variant}: {e:.3e}")
         assert e <= TOL[k.cfg.dtype]
     e = k.err(k.run_vanilla())
+    k.set_query_scale(1.0)
     assert e <= TOL[k.cfg.dtype]
 
 
