@@ -11,12 +11,13 @@
 // (512 KB for H=32, d=4096: a whole CU's register file), so the row width has to be split over
 // workgroups; but head h's weights need columns [h d_k, (h+1) d_k) only, which one column owner
 // holds, while every column owner needs every head's weights.  A "group" of G workgroups (one per
-// column unit of <=128 columns) therefore walks the same rows together; each wave computes the
-// scores of the heads inside its unit from the tile it already holds in registers, publishes them
-// to a small ring in global memory as (tag, value) words, prefetches its next tile, then gathers
-// all heads' scores of the tile, and feeds the register-resident tile to the MFMA.  No fences are
-// needed: every 8-byte word carries the tile's tag, so a reader either sees the value of this tile
-// or polls again.  Polling is bounded; a time-out raises an error word instead of hanging.
+// column unit of <=128 columns) therefore walks the same rows together; a scoring wave computes
+// the scores of the heads inside its unit from the 32-row tile it has just moved into LDS and
+// publishes them to a small ring in global memory as (score, tag) words; a summing wave gathers all
+// heads' scores of the tile, takes the tile out of LDS and feeds it to the MFMA.  No fences are
+// needed: every 8-byte half of a word carries the tile's tag, so a reader either sees the value of
+// this tile or gathers again.  Every wait is bounded; a time-out raises an error word instead of
+// hanging.
 //
 // Register tile.  A wave owns 32 rows x 128 columns: lane l loads 16 bytes (8 columns) of 8 rows,
 // column group l%16, row group l/16.  The MFMA (v_mfma_f32_16x16x32_bf16) contracts over rows,
@@ -66,35 +67,33 @@ __device__ __forceinline__ void transpose8x8(const u32x4 (&kt)[8], u32x4 (&a)[8]
   }
 }
 
-// Score exchange accesses.  Two flavours, chosen per launch:
+// Score exchange accesses.  Readers load at agent scope (never served by the CU's own vector L1).
+// Writers have two flavours, chosen per launch:
 //  * XCD-local (the normal case): all workgroups of a group run on one XCD (workgroup i is
 //    dispatched to XCD i % 8, which the host verifies once per device), so that XCD's L2 is their
-//    coherence point.  Readers invalidate the CU's vector L1 (buffer_inv sc0) and load; writers
-//    store through the write-through L1 into the L2.  The gather never leaves the XCD.
-//  * agent scope (fallback): loads with sc1 and write-through stores, coherent across XCDs but
-//    every gather goes out to the memory-side cache.
-// 16-byte accesses, so that a wave's gather of one tile is 8 fully coalesced 1 KB loads.
-__device__ __forceinline__ u32x4 ld_exch(const u32x4* p, int mode) {
+//    meeting point: a plain store (the vector L1 is write-through) is enough and the words never
+//    leave the L2.
+//  * system scope (fallback): write-through stores that also reach the memory side, for groups
+//    whose workgroups may sit on different XCDs.
+// 16-byte accesses: a wave's gather of one tile is a handful of fully coalesced 1 KB loads.
+__device__ __forceinline__ u32x4 ld_exch(const u32x4* p) {
   u32x4 v;
-  if (mode == 1) asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(v) : "v"(p) : "memory");
-  else if (mode == 2 || mode == 3) asm volatile("global_load_dwordx4 %0, %1, off sc0" : "=v"(v) : "v"(p) : "memory");
-  else asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v) : "v"(p) : "memory");
+  asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v) : "v"(p) : "memory");
   return v;
 }
-__device__ __forceinline__ void st_exch(u32x4* p, u32x4 v, int mode) {
-  // The trailing s_nop matters: a store of more than 64 bits still reads its data registers in
-  // the wait states after it issues, and the compiler (which pads its own stores) is free to
-  // overwrite the inputs of an asm statement with the very next VALU instruction.
-  asm volatile("s_nop 1\n\tglobal_store_dwordx4 %0, %1, off sc0 sc1\n\ts_nop 1" : : "v"(p), "v"(v) : "memory");
+__device__ __forceinline__ void st_exch(u32x4* p, u32x4 v, bool xcd_local) {
+  // The s_nops matter: a store of more than 64 bits still reads its data registers in the wait
+  // states after it issues, and the compiler (which pads its own stores) is free to overwrite
+  // the inputs of an asm statement with the very next VALU instruction.
+  if (xcd_local) asm volatile("s_nop 1\n\tglobal_store_dwordx4 %0, %1, off\n\ts_nop 1" : : "v"(p), "v"(v) : "memory");
+  else asm volatile("s_nop 1\n\tglobal_store_dwordx4 %0, %1, off sc0 sc1\n\ts_nop 1" : : "v"(p), "v"(v) : "memory");
 }
 template <int NT>
-__device__ __forceinline__ void poll_issue(u32x4 (&pr)[NT * 4], const u32x4* lane_base, int HP, int mode) {
-  if (mode == 2) asm volatile("buffer_inv sc0" : : : "memory");
-  if (mode == 1 || mode == 3) asm volatile("buffer_inv sc1" : : : "memory");
+__device__ __forceinline__ void poll_issue(u32x4 (&pr)[NT * 4], const u32x4* lane_base, int HP) {
 #pragma unroll
   for (int t = 0; t < NT; ++t)
 #pragma unroll
-    for (int i = 0; i < 4; ++i) pr[t * 4 + i] = ld_exch(lane_base + (i * HP + t * 16) * 4, mode);
+    for (int i = 0; i < 4; ++i) pr[t * 4 + i] = ld_exch(lane_base + (i * HP + t * 16) * 4);
 }
 // Waits until at most YOUNGER vector-memory operations issued after the poll loads are still
 // outstanding (they return in order), and ties the polled registers to the wait.
@@ -102,6 +101,20 @@ template <int NT, int YOUNGER>
 __device__ __forceinline__ void poll_wait(u32x4 (&pr)[NT * 4]) {
   asm volatile("s_waitcnt vmcnt(%4)" : "+v"(pr[0]), "+v"(pr[1]), "+v"(pr[2]), "+v"(pr[3]) : "n"(YOUNGER) : "memory");
   if constexpr (NT > 1) asm volatile("" : "+v"(pr[4]), "+v"(pr[5]), "+v"(pr[6]), "+v"(pr[7]) : : "memory");
+}
+
+// s_waitcnt vmcnt(n) for a run-time n (a multiple of 4 up to 28; the instruction wants a constant).
+__device__ __forceinline__ void wait_vm_outstanding(int n) {
+  switch (n >> 2) {
+    case 0: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
+    case 1: asm volatile("s_waitcnt vmcnt(4)" ::: "memory"); break;
+    case 2: asm volatile("s_waitcnt vmcnt(8)" ::: "memory"); break;
+    case 3: asm volatile("s_waitcnt vmcnt(12)" ::: "memory"); break;
+    case 4: asm volatile("s_waitcnt vmcnt(16)" ::: "memory"); break;
+    case 5: asm volatile("s_waitcnt vmcnt(20)" ::: "memory"); break;
+    case 6: asm volatile("s_waitcnt vmcnt(24)" ::: "memory"); break;
+    default: asm volatile("s_waitcnt vmcnt(28)" ::: "memory"); break;
+  }
 }
 
 // Tiles of 32 rows: prefix[b] = number of tiles of sequences 0..b-1.  One thread, B is small.
@@ -119,18 +132,33 @@ __device__ void build_tile_prefix(int* prefix, const int32_t* lens, int B, int T
 
 // ------------------------------------------------------------------------------------------------
 // fused stream kernel
+//
+// A workgroup is FUSED_PAIRS pairs of waves.  The first wave of a pair (the "scoring" wave) moves
+// its K tiles HBM -> LDS with direct-to-LDS loads issued FUSED_SLOTS-1 tiles ahead, computes the
+// scores of its unit's heads and publishes them; it never waits for another workgroup, so the
+// stream from HBM runs at its own pace.  The second wave (the "summing" wave) gathers all heads'
+// scores of a tile, takes the tile out of the same LDS slot, and does the online softmax and the
+// MFMA contraction; it runs up to FUSED_SLOTS-1 tiles behind its partner, which hides the
+// latency of the exchange.  The two roles sit in different waves because vector-memory
+// operations of one wave complete in issue order: a wave that mixed the long-latency tile loads
+// with the gathers could not wait for a gather without also waiting for every tile load issued
+// before it.  A slot goes back to the scoring wave through a counter in LDS.
 // ------------------------------------------------------------------------------------------------
-template <int NT, int NW>
-__global__ __launch_bounds__(NW * 64) void fused_stream_kernel(const FusedArgs a) {
-  constexpr int NTHR = NW * 64;
+template <int NT>
+__global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const FusedArgs a) {
+  constexpr int NP = FUSED_PAIRS, NS = FUSED_SLOTS, PD = FUSED_AHEAD;
+  constexpr int NTHR = NP * 128;
   constexpr int HP = NT * 16;                       // heads padded to the MFMA N tile
   __shared__ int prefix[FUSED_MAX_B + 1];
-  __shared__ float marr[NW][NT][16];
-  __shared__ float larr[NW][NT][16];
-  __shared__ u32x4 tiles[NW][2][512];              // per wave: two 8 KB landing slots for K tiles
+  __shared__ float marr[NP][NT][16];
+  __shared__ float larr[NP][NT][16];
+  __shared__ int consumed[NP];                      // tiles of this segment the summing wave has taken
+  __shared__ int published[NP];                     // tiles of this segment the scoring wave has published
+  __shared__ u32x4 tiles[NP][NS][512];              // per pair: 8 KB landing slots for K tiles
   // the end-of-segment reduction reuses the (then idle) landing slots
-  float* const sbuf = reinterpret_cast<float*>(&tiles[0][0][0]);   // [4][HP][129] floats <= 66 KB
-  static_assert(NW == 8, "the end-of-segment reduction assumes 8 waves (two halves of 4)");
+  float* const sbuf = reinterpret_cast<float*>(&tiles[0][0][0]);   // [NP][HP][129] floats
+  static_assert(sizeof(float) * NP * HP * 129 <= sizeof(u32x4) * NP * NS * 512, "reduction buffer must fit the slots");
+  static_assert(NP == 4 && NS >= 3 && NS <= 5, "the thread mappings below assume 4 pairs");
 
   // ---- which group / column unit is this workgroup -------------------------------------------
   int g, u;
@@ -151,6 +179,9 @@ __global__ __launch_bounds__(NW * 64) void fused_stream_kernel(const FusedArgs a
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int idx = lane & 15, rg = lane >> 4;        // column group / row group of the register tile
   const int n = idx, kg = rg;                       // head-in-tile / row group of the B operand
+  const int wu = __builtin_amdgcn_readfirstlane(w);
+  const bool scoring = wu < NP;                     // wave role
+  const int p = wu & (NP - 1);                      // pair
 
   if (blockIdx.x == 0 && a.counters)                // the projection's arrival counters start at 0
     for (int i = tid; i < a.ncounters; i += NTHR) a.counters[i] = 0;
@@ -170,14 +201,13 @@ __global__ __launch_bounds__(NW * 64) void fused_stream_kernel(const FusedArgs a
   const int ucol0 = u * a.hpu * a.d_k;
   const int uwc = min(a.hpu * a.d_k, a.d - ucol0);  // columns of this unit
 
-  const int xl = a.xcd_local;
+  const bool xl = a.xcd_local != 0;
   const bool all_active = __all(col_active) != 0;    // every lane of the wave owns live columns
   const bool heads_full = (a.H == HP);               // no padded heads in the MFMA N tiles
   const unsigned pitchB = (unsigned)a.d * 2u;        // bytes per cache row
-  const int wu = __builtin_amdgcn_readfirstlane(w);
-  unsigned it = 0;                                  // tiles this wave's team has processed
-  bool dead = false;                                // a poll timed out: stop waiting, just drain
-  u32x4* const team_ring = reinterpret_cast<u32x4*>(a.exch) + (size_t)(g * NW + w) * EXCH_SLOTS * (HP * 16);
+  unsigned it = 0;                                  // tiles this pair has been through so far
+  bool dead = false;                                // a wait timed out: stop waiting, just drain
+  u32x4* const team_ring = reinterpret_cast<u32x4*>(a.exch) + (size_t)(g * NP + p) * EXCH_SLOTS * (HP * 16);
 
   int b = 0;
   while (prefix[b + 1] <= v0) ++b;
@@ -187,20 +217,10 @@ __global__ __launch_bounds__(NW * 64) void fused_stream_kernel(const FusedArgs a
     if (s0 >= s1) continue;
     const int len = seq_len_of(a.seq_lens, b, a.T);
     const uint16_t* Kb = a.K + (size_t)b * a.k_bstride;
-
-    // query for this lane's 8 columns, pre-scaled (log2 domain), split into bf16 hi + lo pairs so
-    // that the score dot products run on v_dot2c_f32_bf16 without losing the fp32 query
-    unsigned qh[4], ql[4];
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      const float f0 = col_active ? a.q[(size_t)b * a.d + mycol + 2 * c] * a.qscale : 0.f;
-      const float f1 = col_active ? a.q[(size_t)b * a.d + mycol + 2 * c + 1] * a.qscale : 0.f;
-      const __bf16 h0 = (__bf16)f0, h1 = (__bf16)f1;
-      const bf16x2 hi = {h0, h1};
-      const bf16x2 lo = {(__bf16)(f0 - (float)h0), (__bf16)(f1 - (float)h1)};
-      qh[c] = __builtin_bit_cast(unsigned, hi);
-      ql[c] = __builtin_bit_cast(unsigned, lo);
-    }
+    // this pair's tiles are s0+p, s0+p+NP, ...; tile k carries tag tag_base + it0 + k + 1
+    const int ntl = max(0, (s1 - s0 - p + NP - 1) / NP);
+    const unsigned it0 = it;
+    it += (unsigned)ntl;
 
     float m[NT];
     f32x4 acc[8][NT], accl[NT];                      // accl: sum of the weights (an all-ones A operand)
@@ -211,135 +231,77 @@ __global__ __launch_bounds__(NW * 64) void fused_stream_kernel(const FusedArgs a
 #pragma unroll
       for (int i = 0; i < 8; ++i) acc[i][t] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
-    const unsigned lane_off = (unsigned)(rg * 8) * pitchB + (unsigned)mycol * 2u;
 
-    // Sum one tile: check the gathered words' tags (re-polling while any is missing), online
-    // softmax per wave, weights as the bf16 B operand, MFMA over the tile held in `kt`.
-    auto consume = [&](u32x4 (&pr)[NT * 4], const u32x4 (&kt)[8], int s, unsigned tag, u32x4* ring) {
-      int spins = 0;
-      for (;;) {
-        unsigned bad = 0;
-#pragma unroll
-        for (int t = 0; t < NT; ++t) {
-          unsigned bt = 0;
-#pragma unroll
-          for (int i = 0; i < 4; ++i) bt |= (pr[t * 4 + i][1] ^ tag) | (pr[t * 4 + i][3] ^ tag);
-          bad |= (heads_full || (t * 16 + n) < a.H) ? bt : 0u;
-        }
-        if (__all(bad == 0)) break;
-        if (dead || ++spins > a.spin_limit) {
-          if (!dead && lane == 0) atomicExch(a.err, (int)a.launch_id);
-          dead = true;
-          break;
-        }
-        __builtin_amdgcn_s_sleep(8);
-        poll_issue<NT>(pr, ring + (n * 4 + kg), HP, xl);
-        poll_wait<NT, 0>(pr);
-      }
-      const bool partial = (s + 1) * TILE_ROWS > len;            // wave-uniform
-      const int row0 = s * TILE_ROWS + kg * 8;
-      bf16x8 pb[NT];
-#pragma unroll
-      for (int t = 0; t < NT; ++t) {
-        float x[8];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          x[2 * i] = __uint_as_float(pr[t * 4 + i][0]);
-          x[2 * i + 1] = __uint_as_float(pr[t * 4 + i][2]);
-        }
-        if (partial) {
-#pragma unroll
-          for (int j = 0; j < 8; ++j) x[j] = (row0 + j < len) ? x[j] : NEG_INF;
-        }
-        if (!heads_full && (t * 16 + n) >= a.H) {                // padded head: no weights at all
-#pragma unroll
-          for (int j = 0; j < 8; ++j) x[j] = NEG_INF;
-        }
-        float tmax = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-        const float mn = fmaxf(m[t], tmax);
-        const float ref = (mn == NEG_INF) ? 0.f : mn;            // all -inf so far: exp2(-inf - 0) = 0
-        const float alpha = __builtin_amdgcn_exp2f(m[t] - ref);
-#pragma unroll
-        for (int j = 0; j < 8; ++j) pb[t][j] = (__bf16)__builtin_amdgcn_exp2f(x[j] - ref);
-        m[t] = mn;
-        if (__any(alpha != 1.f)) {
-          accl[t] *= alpha;
-#pragma unroll
-          for (int i = 0; i < 8; ++i) acc[i][t] *= alpha;
-        }
-      }
-      u32x4 am[8];
-      transpose8x8(kt, am);
-      const u32x4 ones_bits = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
-      const bf16x8 ones = __builtin_bit_cast(bf16x8, ones_bits);
-#pragma unroll
-      for (int t = 0; t < NT; ++t) accl[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pb[t], accl[t], 0, 0, 0);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const bf16x8 av = __builtin_bit_cast(bf16x8, am[i]);
-#pragma unroll
-        for (int t = 0; t < NT; ++t)
-          acc[i][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, pb[t], acc[i][t], 0, 0, 0);
-      }
-    };
+    if (tid < NP) { consumed[tid] = 0; published[tid] = 0; }
+    __syncthreads();
 
-    // This wave's tiles are s0+w, s0+w+NW, ...  K tiles travel HBM -> LDS by direct-to-LDS loads
-    // issued two tiles ahead (no registers held while in flight); each wave owns two 8 KB landing
-    // slots.  Iteration k: take tile k out of its slot, issue the gather of tile k-1's scores,
-    // score and publish tile k, refill the slot with tile k+2, then sum tile k-1 (kept in
-    // registers) once its gather is back.  All vector-memory waits are explicit: operations
-    // return in issue order, so "at most N younger ones outstanding" identifies what has landed.
-    const int ntl = (s1 - s0 - w + NW - 1) / NW;
-    auto dma_tile = [&](int k) {                      // tile k of this wave -> slot k & 1
-      const int st = __builtin_amdgcn_readfirstlane(s0 + w + k * NW);
-      u32x4* slot = &tiles[wu][k & 1][0];
-      if ((st + 1) * TILE_ROWS <= len && all_active) {
-        // full tile, every lane loads: uniform row base + per-lane 32-bit offset
-        const char* tb = reinterpret_cast<const char*>(Kb) + (size_t)st * TILE_ROWS * pitchB;
+    if (scoring) {
+      // ======================= scoring wave: HBM -> LDS, scores, publish ========================
+      // query for this lane's 8 columns, pre-scaled (log2 domain), split into bf16 hi + lo pairs
+      // so that the dot products run on v_dot2c_f32_bf16 without losing the fp32 query
+      unsigned qh[4], ql[4];
 #pragma unroll
-        for (int j = 0; j < 8; ++j)
-          __builtin_amdgcn_global_load_lds(
-              (const __attribute__((address_space(1))) void*)(tb + (size_t)j * pitchB + lane_off),
-              (__attribute__((address_space(3))) void*)(slot + j * 64), 16, 0, 0);
-      } else {
-        const int r0 = st * TILE_ROWS + rg * 8;
+      for (int c = 0; c < 4; ++c) {
+        const float f0 = col_active ? a.q[(size_t)b * a.d + mycol + 2 * c] * a.qscale : 0.f;
+        const float f1 = col_active ? a.q[(size_t)b * a.d + mycol + 2 * c + 1] * a.qscale : 0.f;
+        const __bf16 h0 = (__bf16)f0, h1 = (__bf16)f1;
+        const bf16x2 hi = {h0, h1};
+        const bf16x2 lo = {(__bf16)(f0 - (float)h0), (__bf16)(f1 - (float)h1)};
+        qh[c] = __builtin_bit_cast(unsigned, hi);
+        ql[c] = __builtin_bit_cast(unsigned, lo);
+      }
+      const unsigned lane_off = (unsigned)(rg * 8) * pitchB + (unsigned)mycol * 2u;
+      auto dma_tile = [&](int k) {                    // tile k of this pair -> slot k % NS
+        const int st = __builtin_amdgcn_readfirstlane(s0 + p + k * NP);
+        u32x4* slot = &tiles[p][k % NS][0];
+        if ((st + 1) * TILE_ROWS <= len && all_active) {
+          // full tile, every lane loads: uniform row base + per-lane 32-bit offset
+          const char* tb = reinterpret_cast<const char*>(Kb) + (size_t)st * TILE_ROWS * pitchB;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          const int r = min(r0 + j, len - 1);         // rows past the end re-read the last row; masked later
-          if (col_active)
+          for (int j = 0; j < 8; ++j)
             __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void*)(Kb + (size_t)r * a.d + mycol),
+                (const __attribute__((address_space(1))) void*)(tb + (size_t)j * pitchB + lane_off),
                 (__attribute__((address_space(3))) void*)(slot + j * 64), 16, 0, 0);
-        }
-      }
-    };
-    u32x4 cur[8], prev[8];
-    int s_prev = 0;
-    unsigned tag_prev = 0;
-    u32x4* ring_prev = team_ring;
-    if (ntl > 0) dma_tile(0);
-    if (ntl > 1) dma_tile(1);
-    for (int k = 0; k <= ntl && ntl > 0; ++k) {
-      const int s = s0 + w + k * NW;
-      unsigned tag = 0;
-      u32x4* ring = team_ring;
-      if (k < ntl) {
-        if (k + 1 < ntl) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");   // tile k landed, k+1 may be in flight
-        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        } else {
+          const int r0 = st * TILE_ROWS + rg * 8;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) cur[j] = tiles[wu][k & 1][j * 64 + lane];
-        if (!all_active) {
-#pragma unroll
-          for (int j = 0; j < 8; ++j) cur[j] = col_active ? cur[j] : u32x4{0u, 0u, 0u, 0u};
+          for (int j = 0; j < 8; ++j) {
+            const int r = min(r0 + j, len - 1);       // rows past the end re-read the last row; masked later
+            if (col_active)
+              __builtin_amdgcn_global_load_lds(
+                  (const __attribute__((address_space(1))) void*)(Kb + (size_t)r * a.d + mycol),
+                  (__attribute__((address_space(3))) void*)(slot + j * 64), 16, 0, 0);
+          }
         }
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                  // slot is free again
-      }
-      u32x4 pr[NT * 4];
-      if (k >= 1) poll_issue<NT>(pr, ring_prev + (n * 4 + kg), HP, xl);
-      if (k < ntl) {
-        // ---- scores of this unit's heads for the lane's 8 rows (log2 domain) ------------------
+      };
+#pragma unroll
+      for (int k = 0; k < PD; ++k)
+        if (k < ntl) dma_tile(k);
+      for (int k = 0; k < ntl; ++k) {
+        // Tile k has landed once only what was issued after its loads is still outstanding
+        // (operations complete in issue order): 8 loads for each of the tiles k+1 .. k+PD-1 and
+        // 4 publishing stores for each step since tile k was requested.  Every scoring wave has
+        // a publishing lane (each unit owns at least one head), so the stores always issue.
+        wait_vm_outstanding(8 * min(ntl - 1 - k, PD - 1) + 4 * min(k, PD));
+        // ---- keep PD tiles in flight: tile k+PD goes where tile k+PD-NS was, once the summing
+        //      wave has taken that one out
+        if (k + PD < ntl) {
+          int spins = 0;
+          while (!dead && __hip_atomic_load(&consumed[p], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) < k + PD - NS + 1) {
+            if (++spins > a.spin_limit) {
+              if (lane == 0) atomicExch(a.err, (int)a.launch_id);
+              dead = true;
+              break;
+            }
+            __builtin_amdgcn_s_sleep(2);
+          }
+          asm volatile("" ::: "memory");
+          dma_tile(k + PD);
+        }
+        u32x4 cur[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) cur[j] = tiles[p][k % NS][j * 64 + lane];
+        // ---- scores of this unit's heads for the lane's 8 rows (log2 domain) --------------------
         float sc[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
@@ -351,7 +313,7 @@ __global__ __launch_bounds__(NW * 64) void fused_stream_kernel(const FusedArgs a
             d0 = __builtin_amdgcn_fdot2_f32_bf16(kv, __builtin_bit_cast(bf16x2, qh[c]), d0, false);
             d1 = __builtin_amdgcn_fdot2_f32_bf16(kv, __builtin_bit_cast(bf16x2, ql[c]), d1, false);
           }
-          sc[j] = d0 + d1;
+          sc[j] = col_active ? d0 + d1 : 0.f;          // idle lanes hold whatever the slot held before
         }
 #pragma unroll
         for (int j = 0; j < 8; ++j) {                 // sum over the head's lanes, all inside a 16-lane row
@@ -361,35 +323,149 @@ __global__ __launch_bounds__(NW * 64) void fused_stream_kernel(const FusedArgs a
           if (a.lphp > 8) sc[j] = dpp_add<0x140>(sc[j]);   // other half of the row
         }
         // ---- publish {score, tag, score, tag} words (write-through) ------------------------------
-        ++it;
-        tag = a.tag_base + it;
-        ring = team_ring + (size_t)(it & (EXCH_SLOTS - 1)) * (HP * 16);
+        const unsigned itk = it0 + (unsigned)k + 1u;
+        const unsigned tag = a.tag_base + itk;
+        u32x4* ring = team_ring + (size_t)(itk & (EXCH_SLOTS - 1)) * (HP * 16);
         if (pub_lane) {
 #pragma unroll
           for (int i = 0; i < 4; ++i)
             st_exch(ring + ((i * HP + myhead) * 4 + rg),
                     u32x4{__float_as_uint(sc[2 * i]), tag, __float_as_uint(sc[2 * i + 1]), tag}, xl);
         }
+        // a hint for the summing wave (the words themselves carry the proof)
+        if (lane == 0) __hip_atomic_store(&published[p], k + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
       }
-      const bool refill = k + 2 < ntl;
-      if (refill) dma_tile(k + 2);
-      if (k >= 1) {
-        if (refill) poll_wait<NT, 8>(pr); else poll_wait<NT, 0>(pr);
-        consume(pr, prev, s_prev, tag_prev, ring_prev);
-      }
+      // nothing of this wave may still be in flight towards LDS when the slots change hands
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    } else {
+      // ======================= summing wave: gather, softmax, MFMA =============================
+      auto ring_of = [&](int k) {
+        return team_ring + (size_t)((it0 + (unsigned)k + 1u) & (EXCH_SLOTS - 1)) * (HP * 16) + (n * 4 + kg);
+      };
+      // A gather is only worth issuing once the words are probably there: the partner's own
+      // progress is the hint (the workgroups of a group move at about the same pace).
+      auto partner_at = [&]() {
+        return __builtin_amdgcn_readfirstlane(
+            __hip_atomic_load(&published[p], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
+      };
+      u32x4 pr[NT * 4], pn[NT * 4];
+      bool have = false;                              // pr already holds an issued gather of tile k
+      for (int k = 0; k < ntl; ++k) {
+        const int s = s0 + p + k * NP;
+        const unsigned tag = a.tag_base + it0 + (unsigned)k + 1u;
+        if (!have) {
+          int hs = 0;
+          while (!dead && partner_at() < k + 1) {
+            if (++hs > a.spin_limit) {
+              if (lane == 0) atomicExch(a.err, (int)a.launch_id);
+              dead = true;
+              break;
+            }
+            __builtin_amdgcn_s_sleep(1);
+          }
+          poll_issue<NT>(pr, ring_of(k), HP);
+        }
+        have = (k + 1 < ntl) && (partner_at() >= k + 2);
+        if (have) {
+          poll_issue<NT>(pn, ring_of(k + 1), HP);     // the next tile's words, in flight during this tile's sums
+          poll_wait<NT, NT * 4>(pr);
+        } else {
+          poll_wait<NT, 0>(pr);
+        }
+        // every word of tile k must carry its tag; gather again while any is missing
+        int spins = 0;
+        for (;;) {
+          unsigned bad = 0;
 #pragma unroll
-      for (int j = 0; j < 8; ++j) prev[j] = cur[j];
-      ring_prev = ring;
-      tag_prev = tag;
-      s_prev = s;
+          for (int t = 0; t < NT; ++t) {
+            unsigned bt = 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) bt |= (pr[t * 4 + i][1] ^ tag) | (pr[t * 4 + i][3] ^ tag);
+            bad |= (heads_full || (t * 16 + n) < a.H) ? bt : 0u;
+          }
+          if (__all(bad == 0)) break;
+          if (dead || ++spins > a.spin_limit) {
+            if (!dead && lane == 0) atomicExch(a.err, (int)a.launch_id);
+            dead = true;
+            break;
+          }
+          __builtin_amdgcn_s_sleep(8);
+          poll_issue<NT>(pr, ring_of(k), HP);
+          poll_wait<NT, 0>(pr);
+        }
+        if (!have && k + 1 < ntl && partner_at() >= k + 2) {
+          poll_issue<NT>(pn, ring_of(k + 1), HP);     // second chance: in flight during this tile's sums
+          have = true;
+        }
+        // the scoring wave published after it had read the tile, so the tile is in its slot
+        u32x4 kt[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) kt[j] = tiles[p][k % NS][j * 64 + lane];
+        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(kt[0]), "+v"(kt[1]), "+v"(kt[2]), "+v"(kt[3]),
+                     "+v"(kt[4]), "+v"(kt[5]), "+v"(kt[6]), "+v"(kt[7]) : : "memory");
+        if (lane == 0) __hip_atomic_store(&consumed[p], k + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        if (!all_active) {
+#pragma unroll
+          for (int j = 0; j < 8; ++j) kt[j] = col_active ? kt[j] : u32x4{0u, 0u, 0u, 0u};
+        }
+        const bool partial = (s + 1) * TILE_ROWS > len;            // wave-uniform
+        const int row0 = s * TILE_ROWS + kg * 8;
+        bf16x8 pb[NT];
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+          float x[8];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            x[2 * i] = __uint_as_float(pr[t * 4 + i][0]);
+            x[2 * i + 1] = __uint_as_float(pr[t * 4 + i][2]);
+          }
+          if (partial) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) x[j] = (row0 + j < len) ? x[j] : NEG_INF;
+          }
+          if (!heads_full && (t * 16 + n) >= a.H) {                // padded head: no weights at all
+#pragma unroll
+            for (int j = 0; j < 8; ++j) x[j] = NEG_INF;
+          }
+          float tmax = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+          tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
+          tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+          const float mn = fmaxf(m[t], tmax);
+          const float ref = (mn == NEG_INF) ? 0.f : mn;            // all -inf so far: exp2(-inf - 0) = 0
+          const float alpha = __builtin_amdgcn_exp2f(m[t] - ref);
+#pragma unroll
+          for (int j = 0; j < 8; ++j) pb[t][j] = (__bf16)__builtin_amdgcn_exp2f(x[j] - ref);
+          m[t] = mn;
+          if (__any(alpha != 1.f)) {
+            accl[t] *= alpha;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[i][t] *= alpha;
+          }
+        }
+        u32x4 am[8];
+        transpose8x8(kt, am);
+        const u32x4 ones_bits = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
+        const bf16x8 ones = __builtin_bit_cast(bf16x8, ones_bits);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) accl[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pb[t], accl[t], 0, 0, 0);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const bf16x8 av = __builtin_bit_cast(bf16x8, am[i]);
+#pragma unroll
+          for (int t = 0; t < NT; ++t)
+            acc[i][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, pb[t], acc[i][t], 0, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < NT * 4; ++i) pr[i] = pn[i];
+      }
     }
 
-    // ---- end of this sequence's share: merge the NW waves and write one partial ------------------
+    // ---- end of this sequence's share: merge the summing waves and write one partial -------------
     const int pid = b + g;
-    __syncthreads();
-    if (kg == 0) {
+    __syncthreads();                                  // every slot is idle from here on
+    if (!scoring && kg == 0) {
 #pragma unroll
-      for (int t = 0; t < NT; ++t) marr[w][t][n] = m[t];
+      for (int t = 0; t < NT; ++t) marr[p][t][n] = m[t];
     }
     __syncthreads();
     float wsc[NT];
@@ -397,65 +473,50 @@ __global__ __launch_bounds__(NW * 64) void fused_stream_kernel(const FusedArgs a
     for (int t = 0; t < NT; ++t) {
       float mall = NEG_INF;
 #pragma unroll
-      for (int ww = 0; ww < NW; ++ww) mall = fmaxf(mall, marr[ww][t][n]);
+      for (int ww = 0; ww < NP; ++ww) mall = fmaxf(mall, marr[ww][t][n]);
       wsc[t] = (m[t] == NEG_INF) ? 0.f : exp2f(m[t] - mall);
-      if (kg == 0) larr[w][t][n] = accl[t][0] * wsc[t];   // every accumulator row holds the same sum
+      if (!scoring && kg == 0) larr[p][t][n] = accl[t][0] * wsc[t];   // every accumulator row holds the same sum
     }
-    // Sum the waves' accumulators through LDS, half of the waves at a time: sbuf[wave][head][col]
-    // (row pitch 129 floats), written in MFMA layout, read back with one thread per column.
-    float osum[HP / 4];
+    // Sum the summing waves' accumulators through LDS: sbuf[pair][head][col] (row pitch 129
+    // floats), written in MFMA layout, read back with one thread per (column, head quarter).
+    if (!scoring) {
+      float* mine = sbuf + (size_t)p * HP * 129 + n * 129;
 #pragma unroll
-    for (int jj = 0; jj < HP / 4; ++jj) osum[jj] = 0.f;
+      for (int r = 0; r < 4; ++r) {
+        const int mi = rg * 4 + r;                     // column group (the A operand's M index)
+        const int h2 = mi / a.lphp, l2 = mi % a.lphp;
+        if (!(l2 < a.lph && h2 < a.hpu)) continue;
+        const int oc = h2 * a.d_k + l2 * 8;            // first unit-local column of accumulator row r
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+          for (int i = 0; i < 8; ++i) mine[t * 16 * 129 + oc + i] = acc[i][t][r] * wsc[t];
+      }
+    }
+    __syncthreads();
     const int ocl = tid & 127, ohq = tid >> 7;       // this thread's column and first head (then +4, +8, ...)
-    int ocol[4];                                     // first unit-local column of accumulator row r, or -1
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const int mi = rg * 4 + r;                     // column group (the A operand's M index)
-      const int h2 = mi / a.lphp, l2 = mi % a.lphp;
-      ocol[r] = (l2 < a.lph && h2 < a.hpu) ? h2 * a.d_k + l2 * 8 : -1;
-    }
-#pragma unroll
-    for (int half = 0; half < 2; ++half) {
-      if ((w >> 2) == half) {
-        float* mine = sbuf + (size_t)(w & 3) * HP * 129 + n * 129;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          if (ocol[r] < 0) continue;
-#pragma unroll
-          for (int t = 0; t < NT; ++t)
-#pragma unroll
-            for (int i = 0; i < 8; ++i) mine[t * 16 * 129 + ocol[r] + i] = acc[i][t][r] * wsc[t];
-        }
-      }
-      __syncthreads();
-      if (ocl < uwc) {
-#pragma unroll
-        for (int jj = 0; jj < HP / 4; ++jj) {
-          const int h = ohq + 4 * jj;
-#pragma unroll
-          for (int ww = 0; ww < 4; ++ww) osum[jj] += sbuf[((size_t)ww * HP + h) * 129 + ocl];
-        }
-      }
-      __syncthreads();
-    }
     if (ocl < uwc) {
 #pragma unroll
       for (int jj = 0; jj < HP / 4; ++jj) {
         const int h = ohq + 4 * jj;
-        if (h < a.H) a.Cpart[((size_t)pid * a.H + h) * a.d + ucol0 + ocl] = osum[jj];
+        float osum = 0.f;
+#pragma unroll
+        for (int ww = 0; ww < NP; ++ww) osum += sbuf[((size_t)ww * HP + h) * 129 + ocl];
+        if (h < a.H) a.Cpart[((size_t)pid * a.H + h) * a.d + ucol0 + ocl] = osum;
       }
     }
     if (u == 0 && tid < a.H) {
       const int t = tid >> 4, nn = tid & 15;
       float mall = NEG_INF, l = 0.f;
 #pragma unroll
-      for (int ww = 0; ww < NW; ++ww) {
+      for (int ww = 0; ww < NP; ++ww) {
         mall = fmaxf(mall, marr[ww][t][nn]);
         l += larr[ww][t][nn];
       }
       a.mpart[(size_t)pid * a.H + tid] = mall;
       a.lpart[(size_t)pid * a.H + tid] = l;
     }
+    __syncthreads();                                  // the slots are reused by the next segment
   }
 }
 
@@ -678,7 +739,7 @@ bool fused_geometry(int B, int H, int T, int d, FusedGeom* g) {
   g->hpu = 16 / lphp;
   g->G = (H + g->hpu - 1) / g->hpu;
   g->NT = H <= 16 ? 1 : 2;
-  g->NW = FUSED_WAVES;
+  g->NP = FUSED_PAIRS;
   const int cus = 256;
   if (g->G > cus) return false;
   if (g->G <= 32) {
@@ -691,9 +752,6 @@ bool fused_geometry(int B, int H, int T, int d, FusedGeom* g) {
     g->NG = cus / g->G;
     g->grid = g->NG * g->G;
   }
-  // no more groups than there is work for: a group needs a few tiles per wave to be worth it
-  const long tiles = (long)B * ((T + TILE_ROWS - 1) / TILE_ROWS);
-  (void)tiles;
   g->nparts = B + g->NG - 1;
   return true;
 }
@@ -723,13 +781,13 @@ bool xcd_round_robin(int device) {
 }
 
 size_t fused_exch_bytes(const FusedGeom& g) {
-  return (size_t)g.NG * g.NW * EXCH_SLOTS * (g.NT * 16) * TILE_ROWS * sizeof(unsigned long long);
+  return (size_t)g.NG * g.NP * EXCH_SLOTS * (g.NT * 16) * TILE_ROWS * sizeof(unsigned long long);
 }
 
 void launch_fused_stream(const FusedGeom& g, const FusedArgs& a, hipStream_t st) {
-  dim3 grid(g.grid), block(g.NW * 64);
-  if (g.NT == 1) hipLaunchKernelGGL((fused_stream_kernel<1, FUSED_WAVES>), grid, block, 0, st, a);
-  else hipLaunchKernelGGL((fused_stream_kernel<2, FUSED_WAVES>), grid, block, 0, st, a);
+  dim3 grid(g.grid), block(g.NP * 128);
+  if (g.NT == 1) hipLaunchKernelGGL(fused_stream_kernel<1>, grid, block, 0, st, a);
+  else hipLaunchKernelGGL(fused_stream_kernel<2>, grid, block, 0, st, a);
 }
 
 int proj_row_splits(int H, int rows, int B) {

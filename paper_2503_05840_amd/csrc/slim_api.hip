@@ -218,7 +218,11 @@ extern "C" int slim_decode(const void* q, const void* Kcache, const void* W_KV, 
     if (lid == 0) lid = g_launch.fetch_add(1);
     fa.launch_id = lid;
     fa.spin_limit = 1 << 15;
-    { int dev = 0; (void)hipGetDevice(&dev); (void)dev; fa.xcd_local = 0; }
+    {
+      int dev = 0;
+      (void)hipGetDevice(&dev);
+      fa.xcd_local = (g.gpx > 0 && xcd_round_robin(dev)) ? 1 : 0;
+    }
     fa.Cpart = Cpart; fa.mpart = mpart; fa.lpart = lpart;
     fa.err = ctrl + CTRL_INTS - 1; fa.counters = ctrl; fa.ncounters = H * zb;
     launch_fused_stream(g, fa, st);

@@ -46,15 +46,17 @@ void launch_vanilla(int dtype, const float* q, const void* K, const void* V, lon
 
 // ---- bf16 fast path (kernels_bf16.hip) -----------------------------------------------------------
 constexpr int TILE_ROWS = 32;        // cache rows per wave tile
-constexpr int EXCH_SLOTS = 8;        // ring depth of the score exchange (a power of two >= 4)
+constexpr int EXCH_SLOTS = 16;       // ring depth of the score exchange (a power of two >= 2 * FUSED_SLOTS)
 constexpr int FUSED_MAX_B = 1024;    // sequences per call the fast path handles
-constexpr int FUSED_WAVES = 8;       // waves per workgroup of the stream kernel
+constexpr int FUSED_PAIRS = 4;       // (scoring wave, summing wave) pairs per workgroup of the stream kernel
+constexpr int FUSED_SLOTS = 4;       // LDS landing slots (8 KB tiles) per pair
+constexpr int FUSED_AHEAD = 1;       // tiles a scoring wave keeps in flight (1..3, < FUSED_SLOTS)
 constexpr int PROJ_MAX_PARTS = 64;   // partials per sequence the projection merges
 
 struct FusedGeom {
   int lph, lphp, hpu;   // active lanes per head (d_k/8), lanes reserved per head, heads per unit
   int G, NG, gpx;       // column units per group, groups, groups per XCD (0 = not packed)
-  int NT, NW, grid, nparts;
+  int NT, NP, grid, nparts;   // MFMA head tiles, wave pairs per workgroup
 };
 
 struct FusedArgs {
@@ -65,7 +67,7 @@ struct FusedArgs {
   int T, B, H, d, d_k;
   int G, NG, gpx, lph, lphp, hpu;
   float qscale;                       // log2(e) / sqrt(d_k): scores live in the log2 domain
-  unsigned long long* exch;           // [NG][NW][EXCH_SLOTS][16*NT][TILE_ROWS] (tag, score) words
+  unsigned long long* exch;           // [NG][NP][EXCH_SLOTS][16*NT][TILE_ROWS] (tag, score) words
   unsigned tag_base, launch_id;
   int spin_limit;
   float* Cpart;                       // [nparts][H][d]
@@ -74,7 +76,7 @@ struct FusedArgs {
   int* err;                           // set to launch_id when a wait timed out
   int* counters;                      // arrival counters of the projection, zeroed here
   int ncounters;
-  int xcd_local;                      // 1: a group's workgroups share an XCD, exchange through its L2
+  int xcd_local;                      // 1: a group's workgroups share an XCD, the exchange stays in its L2
 };
 
 struct ProjArgs {
