@@ -27,6 +27,7 @@
 #include "slim_kernels.h"
 
 #include <math.h>
+#include <type_traits>
 
 namespace slim {
 namespace {
@@ -52,6 +53,18 @@ __device__ __forceinline__ float bf16_hi(unsigned x) { return __uint_as_float(x 
 template <int CTRL>
 __device__ __forceinline__ float dpp_add(float v) {
   return v + __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+
+// max over the four lanes l, l^16, l^32, l^48 (the same column group in the four row groups).
+// Register swaps (v_permlane32_swap / v_permlane16_swap), no LDS traffic: a wave's LDS operations
+// queue behind its direct-to-LDS loads.
+__device__ __forceinline__ float max_over_row_groups(float v) {
+  const unsigned u = __float_as_uint(v);
+  const auto a = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  const float h = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+  const unsigned w = __float_as_uint(h);
+  const auto b = __builtin_amdgcn_permlane16_swap(w, w, false, false);
+  return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
 }
 
 // 8 rows x 8 bf16 columns per lane  ->  8 operands (one per column), each 8 rows of that column.
@@ -88,32 +101,25 @@ __device__ __forceinline__ void st_exch(u32x4* p, u32x4 v, bool xcd_local) {
   if (xcd_local) asm volatile("s_nop 1\n\tglobal_store_dwordx4 %0, %1, off\n\ts_nop 1" : : "v"(p), "v"(v) : "memory");
   else asm volatile("s_nop 1\n\tglobal_store_dwordx4 %0, %1, off sc0 sc1\n\ts_nop 1" : : "v"(p), "v"(v) : "memory");
 }
-template <int NT>
-__device__ __forceinline__ void poll_issue(u32x4 (&pr)[NT * 4], const u32x4* lane_base, int HP) {
-#pragma unroll
-  for (int t = 0; t < NT; ++t)
-#pragma unroll
-    for (int i = 0; i < 4; ++i) pr[t * 4 + i] = ld_exch(lane_base + (i * HP + t * 16) * 4);
-}
-// Waits until at most YOUNGER vector-memory operations issued after the poll loads are still
-// outstanding (they return in order), and ties the polled registers to the wait.
-template <int NT, int YOUNGER>
-__device__ __forceinline__ void poll_wait(u32x4 (&pr)[NT * 4]) {
-  asm volatile("s_waitcnt vmcnt(%4)" : "+v"(pr[0]), "+v"(pr[1]), "+v"(pr[2]), "+v"(pr[3]) : "n"(YOUNGER) : "memory");
-  if constexpr (NT > 1) asm volatile("" : "+v"(pr[4]), "+v"(pr[5]), "+v"(pr[6]), "+v"(pr[7]) : : "memory");
+// s_waitcnt vmcnt(n) for a run-time even n <= 30 (the instruction wants a constant).
+__device__ __forceinline__ void wait_vm_outstanding(int n) {
+  switch (n >> 1) {
+#define SLIM_VM_CASE(N) case N / 2: asm volatile("s_waitcnt vmcnt(" #N ")" ::: "memory"); break;
+    SLIM_VM_CASE(0) SLIM_VM_CASE(2) SLIM_VM_CASE(4) SLIM_VM_CASE(6) SLIM_VM_CASE(8) SLIM_VM_CASE(10)
+    SLIM_VM_CASE(12) SLIM_VM_CASE(14) SLIM_VM_CASE(16) SLIM_VM_CASE(18) SLIM_VM_CASE(20) SLIM_VM_CASE(22)
+    SLIM_VM_CASE(24) SLIM_VM_CASE(26) SLIM_VM_CASE(28)
+#undef SLIM_VM_CASE
+    default: asm volatile("s_waitcnt vmcnt(30)" ::: "memory"); break;
+  }
 }
 
-// s_waitcnt vmcnt(n) for a run-time n (a multiple of 4 up to 28; the instruction wants a constant).
-__device__ __forceinline__ void wait_vm_outstanding(int n) {
-  switch (n >> 2) {
-    case 0: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
-    case 1: asm volatile("s_waitcnt vmcnt(4)" ::: "memory"); break;
-    case 2: asm volatile("s_waitcnt vmcnt(8)" ::: "memory"); break;
-    case 3: asm volatile("s_waitcnt vmcnt(12)" ::: "memory"); break;
-    case 4: asm volatile("s_waitcnt vmcnt(16)" ::: "memory"); break;
-    case 5: asm volatile("s_waitcnt vmcnt(20)" ::: "memory"); break;
-    case 6: asm volatile("s_waitcnt vmcnt(24)" ::: "memory"); break;
-    default: asm volatile("s_waitcnt vmcnt(28)" ::: "memory"); break;
+// f(k + I, integral_constant<I>) for I = 0 .. N-1 while k + I < end: loop bodies whose register
+// buffers are chosen by a compile-time index.
+template <int I, int N, class F>
+__device__ __forceinline__ void unrolled_steps(int k, int end, F& f) {
+  if constexpr (I < N) {
+    if (k + I < end) f(k + I, std::integral_constant<int, I>{});
+    unrolled_steps<I + 1, N>(k, end, f);
   }
 }
 
@@ -133,16 +139,19 @@ __device__ void build_tile_prefix(int* prefix, const int32_t* lens, int B, int T
 // ------------------------------------------------------------------------------------------------
 // fused stream kernel
 //
-// A workgroup is FUSED_PAIRS pairs of waves.  The first wave of a pair (the "scoring" wave) moves
-// its K tiles HBM -> LDS with direct-to-LDS loads issued FUSED_SLOTS-1 tiles ahead, computes the
-// scores of its unit's heads and publishes them; it never waits for another workgroup, so the
-// stream from HBM runs at its own pace.  The second wave (the "summing" wave) gathers all heads'
-// scores of a tile, takes the tile out of the same LDS slot, and does the online softmax and the
-// MFMA contraction; it runs up to FUSED_SLOTS-1 tiles behind its partner, which hides the
-// latency of the exchange.  The two roles sit in different waves because vector-memory
-// operations of one wave complete in issue order: a wave that mixed the long-latency tile loads
-// with the gathers could not wait for a gather without also waiting for every tile load issued
-// before it.  A slot goes back to the scoring wave through a counter in LDS.
+// A workgroup is FUSED_PAIRS pairs of waves.  The first wave of a pair (the "scoring" wave) streams
+// its K tiles from HBM into registers (FUSED_AHEAD register sets, so the next tile is in flight
+// while one is being scored), computes the scores of its unit's heads, turns them into softmax
+// numerators against the head's running maximum (bf16, the precision the MFMA consumes anyway),
+// parks the tile in an LDS slot and publishes {tag, running max, 4 numerators} words; it never
+// waits for another workgroup, so the stream from HBM runs at its own pace.  The second wave (the
+// "summing" wave) gathers all heads' words of a tile (up to FUSED_GATHERS tiles ahead), takes the
+// tile out of the LDS slot, rescales its accumulators when a maximum moved and does the MFMA
+// contraction; it may run FUSED_SLOTS-1 tiles behind its partner, which hides the latency of the
+// exchange.  The two roles sit in different waves because vector-memory operations of one wave
+// complete in issue order: a wave that mixed the long-latency tile loads with the gathers could
+// not wait for a gather without also waiting for every tile load issued before it.  A slot goes
+// back to the scoring wave through a counter in LDS.
 // ------------------------------------------------------------------------------------------------
 template <int NT>
 __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const FusedArgs a) {
@@ -205,296 +214,42 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
   const bool all_active = __all(col_active) != 0;    // every lane of the wave owns live columns
   const bool heads_full = (a.H == HP);               // no padded heads in the MFMA N tiles
   const unsigned pitchB = (unsigned)a.d * 2u;        // bytes per cache row
-  unsigned it = 0;                                  // tiles this pair has been through so far
+  u32x4* const team_ring = reinterpret_cast<u32x4*>(a.exch) + (size_t)(g * NP + p) * EXCH_SLOTS * (HP * 8);
   bool dead = false;                                // a wait timed out: stop waiting, just drain
-  u32x4* const team_ring = reinterpret_cast<u32x4*>(a.exch) + (size_t)(g * NP + p) * EXCH_SLOTS * (HP * 16);
+  auto give_up = [&]() {
+    if (!dead && lane == 0) atomicExch(a.err, (int)a.launch_id);
+    dead = true;
+  };
 
-  int b = 0;
-  while (prefix[b + 1] <= v0) ++b;
-  for (; b < a.B && prefix[b] < v1; ++b) {
-    const int s0 = max(v0, prefix[b]) - prefix[b];
-    const int s1 = min(v1, prefix[b + 1]) - prefix[b];
-    if (s0 >= s1) continue;
-    const int len = seq_len_of(a.seq_lens, b, a.T);
-    const uint16_t* Kb = a.K + (size_t)b * a.k_bstride;
-    // this pair's tiles are s0+p, s0+p+NP, ...; tile k carries tag tag_base + it0 + k + 1
-    const int ntl = max(0, (s1 - s0 - p + NP - 1) / NP);
-    const unsigned it0 = it;
-    it += (unsigned)ntl;
-
-    float m[NT];
-    f32x4 acc[8][NT], accl[NT];                      // accl: sum of the weights (an all-ones A operand)
-#pragma unroll
-    for (int t = 0; t < NT; ++t) {
-      m[t] = NEG_INF;
-      accl[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int i = 0; i < 8; ++i) acc[i][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+  // The segments (sequence shares) of this group, the same walk for both roles.  Both roles run
+  // the same sequence of workgroup barriers per segment.
+  struct Seg { int b, s0, ntl, len; unsigned it0; const uint16_t* Kb; };
+  int seg_b = 0;
+  unsigned seg_it = 0;                              // tiles this pair has been through so far
+  while (prefix[seg_b + 1] <= v0) ++seg_b;
+  auto next_segment = [&](Seg& sg) -> bool {
+    for (; seg_b < a.B && prefix[seg_b] < v1; ++seg_b) {
+      const int b = seg_b;
+      const int s0 = max(v0, prefix[b]) - prefix[b];
+      const int s1 = min(v1, prefix[b + 1]) - prefix[b];
+      if (s0 >= s1) continue;
+      sg.b = b;
+      sg.s0 = s0;
+      sg.len = seq_len_of(a.seq_lens, b, a.T);
+      sg.Kb = a.K + (size_t)b * a.k_bstride;
+      // this pair's tiles are s0+p, s0+p+NP, ...; tile k carries tag tag_base + it0 + k + 1
+      sg.ntl = max(0, (s1 - s0 - p + NP - 1) / NP);
+      sg.it0 = seg_it;
+      seg_it += (unsigned)sg.ntl;
+      ++seg_b;
+      return true;
     }
-
-    if (tid < NP) { consumed[tid] = 0; published[tid] = 0; }
-    __syncthreads();
-
-    if (scoring) {
-      // ======================= scoring wave: HBM -> LDS, scores, publish ========================
-      // query for this lane's 8 columns, pre-scaled (log2 domain), split into bf16 hi + lo pairs
-      // so that the dot products run on v_dot2c_f32_bf16 without losing the fp32 query
-      unsigned qh[4], ql[4];
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const float f0 = col_active ? a.q[(size_t)b * a.d + mycol + 2 * c] * a.qscale : 0.f;
-        const float f1 = col_active ? a.q[(size_t)b * a.d + mycol + 2 * c + 1] * a.qscale : 0.f;
-        const __bf16 h0 = (__bf16)f0, h1 = (__bf16)f1;
-        const bf16x2 hi = {h0, h1};
-        const bf16x2 lo = {(__bf16)(f0 - (float)h0), (__bf16)(f1 - (float)h1)};
-        qh[c] = __builtin_bit_cast(unsigned, hi);
-        ql[c] = __builtin_bit_cast(unsigned, lo);
-      }
-      const unsigned lane_off = (unsigned)(rg * 8) * pitchB + (unsigned)mycol * 2u;
-      auto dma_tile = [&](int k) {                    // tile k of this pair -> slot k % NS
-        const int st = __builtin_amdgcn_readfirstlane(s0 + p + k * NP);
-        u32x4* slot = &tiles[p][k % NS][0];
-        if ((st + 1) * TILE_ROWS <= len && all_active) {
-          // full tile, every lane loads: uniform row base + per-lane 32-bit offset
-          const char* tb = reinterpret_cast<const char*>(Kb) + (size_t)st * TILE_ROWS * pitchB;
-#pragma unroll
-          for (int j = 0; j < 8; ++j)
-            __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void*)(tb + (size_t)j * pitchB + lane_off),
-                (__attribute__((address_space(3))) void*)(slot + j * 64), 16, 0, 0);
-        } else {
-          const int r0 = st * TILE_ROWS + rg * 8;
-#pragma unroll
-          for (int j = 0; j < 8; ++j) {
-            const int r = min(r0 + j, len - 1);       // rows past the end re-read the last row; masked later
-            if (col_active)
-              __builtin_amdgcn_global_load_lds(
-                  (const __attribute__((address_space(1))) void*)(Kb + (size_t)r * a.d + mycol),
-                  (__attribute__((address_space(3))) void*)(slot + j * 64), 16, 0, 0);
-          }
-        }
-      };
-#pragma unroll
-      for (int k = 0; k < PD; ++k)
-        if (k < ntl) dma_tile(k);
-      for (int k = 0; k < ntl; ++k) {
-        // Tile k has landed once only what was issued after its loads is still outstanding
-        // (operations complete in issue order): 8 loads for each of the tiles k+1 .. k+PD-1 and
-        // 4 publishing stores for each step since tile k was requested.  Every scoring wave has
-        // a publishing lane (each unit owns at least one head), so the stores always issue.
-        wait_vm_outstanding(8 * min(ntl - 1 - k, PD - 1) + 4 * min(k, PD));
-        // ---- keep PD tiles in flight: tile k+PD goes where tile k+PD-NS was, once the summing
-        //      wave has taken that one out
-        if (k + PD < ntl) {
-          int spins = 0;
-          while (!dead && __hip_atomic_load(&consumed[p], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) < k + PD - NS + 1) {
-            if (++spins > a.spin_limit) {
-              if (lane == 0) atomicExch(a.err, (int)a.launch_id);
-              dead = true;
-              break;
-            }
-            __builtin_amdgcn_s_sleep(2);
-          }
-          asm volatile("" ::: "memory");
-          dma_tile(k + PD);
-        }
-        u32x4 cur[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) cur[j] = tiles[p][k % NS][j * 64 + lane];
-        // ---- scores of this unit's heads for the lane's 8 rows (log2 domain) --------------------
-        float sc[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          float d0 = 0.f, d1 = 0.f;
-#pragma unroll
-          for (int c = 0; c < 4; ++c) {
-            const unsigned kw = cur[j][c];             // (a scalar copy: bit_cast of a vector element picks lane 0)
-            const bf16x2 kv = __builtin_bit_cast(bf16x2, kw);
-            d0 = __builtin_amdgcn_fdot2_f32_bf16(kv, __builtin_bit_cast(bf16x2, qh[c]), d0, false);
-            d1 = __builtin_amdgcn_fdot2_f32_bf16(kv, __builtin_bit_cast(bf16x2, ql[c]), d1, false);
-          }
-          sc[j] = col_active ? d0 + d1 : 0.f;          // idle lanes hold whatever the slot held before
-        }
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {                 // sum over the head's lanes, all inside a 16-lane row
-          sc[j] = dpp_add<0xB1>(sc[j]);               // lane ^ 1
-          sc[j] = dpp_add<0x4E>(sc[j]);               // lane ^ 2
-          if (a.lphp > 4) sc[j] = dpp_add<0x141>(sc[j]);   // other quad of the 8-lane half
-          if (a.lphp > 8) sc[j] = dpp_add<0x140>(sc[j]);   // other half of the row
-        }
-        // ---- publish {score, tag, score, tag} words (write-through) ------------------------------
-        const unsigned itk = it0 + (unsigned)k + 1u;
-        const unsigned tag = a.tag_base + itk;
-        u32x4* ring = team_ring + (size_t)(itk & (EXCH_SLOTS - 1)) * (HP * 16);
-        if (pub_lane) {
-#pragma unroll
-          for (int i = 0; i < 4; ++i)
-            st_exch(ring + ((i * HP + myhead) * 4 + rg),
-                    u32x4{__float_as_uint(sc[2 * i]), tag, __float_as_uint(sc[2 * i + 1]), tag}, xl);
-        }
-        // a hint for the summing wave (the words themselves carry the proof)
-        if (lane == 0) __hip_atomic_store(&published[p], k + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-      }
-      // nothing of this wave may still be in flight towards LDS when the slots change hands
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    } else {
-      // ======================= summing wave: gather, softmax, MFMA =============================
-      auto ring_of = [&](int k) {
-        return team_ring + (size_t)((it0 + (unsigned)k + 1u) & (EXCH_SLOTS - 1)) * (HP * 16) + (n * 4 + kg);
-      };
-      // A gather is only worth issuing once the words are probably there: the partner's own
-      // progress is the hint (the workgroups of a group move at about the same pace).
-      auto partner_at = [&]() {
-        return __builtin_amdgcn_readfirstlane(
-            __hip_atomic_load(&published[p], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
-      };
-      u32x4 pr[NT * 4], pn[NT * 4];
-      bool have = false;                              // pr already holds an issued gather of tile k
-      for (int k = 0; k < ntl; ++k) {
-        const int s = s0 + p + k * NP;
-        const unsigned tag = a.tag_base + it0 + (unsigned)k + 1u;
-        if (!have) {
-          int hs = 0;
-          while (!dead && partner_at() < k + 1) {
-            if (++hs > a.spin_limit) {
-              if (lane == 0) atomicExch(a.err, (int)a.launch_id);
-              dead = true;
-              break;
-            }
-            __builtin_amdgcn_s_sleep(1);
-          }
-          poll_issue<NT>(pr, ring_of(k), HP);
-        }
-        have = (k + 1 < ntl) && (partner_at() >= k + 2);
-        if (have) {
-          poll_issue<NT>(pn, ring_of(k + 1), HP);     // the next tile's words, in flight during this tile's sums
-          poll_wait<NT, NT * 4>(pr);
-        } else {
-          poll_wait<NT, 0>(pr);
-        }
-        // every word of tile k must carry its tag; gather again while any is missing
-        int spins = 0;
-        for (;;) {
-          unsigned bad = 0;
-#pragma unroll
-          for (int t = 0; t < NT; ++t) {
-            unsigned bt = 0;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) bt |= (pr[t * 4 + i][1] ^ tag) | (pr[t * 4 + i][3] ^ tag);
-            bad |= (heads_full || (t * 16 + n) < a.H) ? bt : 0u;
-          }
-          if (__all(bad == 0)) break;
-          if (dead || ++spins > a.spin_limit) {
-            if (!dead && lane == 0) atomicExch(a.err, (int)a.launch_id);
-            dead = true;
-            break;
-          }
-          __builtin_amdgcn_s_sleep(8);
-          poll_issue<NT>(pr, ring_of(k), HP);
-          poll_wait<NT, 0>(pr);
-        }
-        if (!have && k + 1 < ntl && partner_at() >= k + 2) {
-          poll_issue<NT>(pn, ring_of(k + 1), HP);     // second chance: in flight during this tile's sums
-          have = true;
-        }
-        // the scoring wave published after it had read the tile, so the tile is in its slot
-        u32x4 kt[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) kt[j] = tiles[p][k % NS][j * 64 + lane];
-        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(kt[0]), "+v"(kt[1]), "+v"(kt[2]), "+v"(kt[3]),
-                     "+v"(kt[4]), "+v"(kt[5]), "+v"(kt[6]), "+v"(kt[7]) : : "memory");
-        if (lane == 0) __hip_atomic_store(&consumed[p], k + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        if (!all_active) {
-#pragma unroll
-          for (int j = 0; j < 8; ++j) kt[j] = col_active ? kt[j] : u32x4{0u, 0u, 0u, 0u};
-        }
-        const bool partial = (s + 1) * TILE_ROWS > len;            // wave-uniform
-        const int row0 = s * TILE_ROWS + kg * 8;
-        bf16x8 pb[NT];
-#pragma unroll
-        for (int t = 0; t < NT; ++t) {
-          float x[8];
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            x[2 * i] = __uint_as_float(pr[t * 4 + i][0]);
-            x[2 * i + 1] = __uint_as_float(pr[t * 4 + i][2]);
-          }
-          if (partial) {
-#pragma unroll
-            for (int j = 0; j < 8; ++j) x[j] = (row0 + j < len) ? x[j] : NEG_INF;
-          }
-          if (!heads_full && (t * 16 + n) >= a.H) {                // padded head: no weights at all
-#pragma unroll
-            for (int j = 0; j < 8; ++j) x[j] = NEG_INF;
-          }
-          float tmax = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
-          tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
-          tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-          const float mn = fmaxf(m[t], tmax);
-          const float ref = (mn == NEG_INF) ? 0.f : mn;            // all -inf so far: exp2(-inf - 0) = 0
-          const float alpha = __builtin_amdgcn_exp2f(m[t] - ref);
-#pragma unroll
-          for (int j = 0; j < 8; ++j) pb[t][j] = (__bf16)__builtin_amdgcn_exp2f(x[j] - ref);
-          m[t] = mn;
-          if (__any(alpha != 1.f)) {
-            accl[t] *= alpha;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) acc[i][t] *= alpha;
-          }
-        }
-        u32x4 am[8];
-        transpose8x8(kt, am);
-        const u32x4 ones_bits = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
-        const bf16x8 ones = __builtin_bit_cast(bf16x8, ones_bits);
-#pragma unroll
-        for (int t = 0; t < NT; ++t) accl[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pb[t], accl[t], 0, 0, 0);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          const bf16x8 av = __builtin_bit_cast(bf16x8, am[i]);
-#pragma unroll
-          for (int t = 0; t < NT; ++t)
-            acc[i][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, pb[t], acc[i][t], 0, 0, 0);
-        }
-#pragma unroll
-        for (int i = 0; i < NT * 4; ++i) pr[i] = pn[i];
-      }
-    }
-
-    // ---- end of this sequence's share: merge the summing waves and write one partial -------------
-    const int pid = b + g;
-    __syncthreads();                                  // every slot is idle from here on
-    if (!scoring && kg == 0) {
-#pragma unroll
-      for (int t = 0; t < NT; ++t) marr[p][t][n] = m[t];
-    }
-    __syncthreads();
-    float wsc[NT];
-#pragma unroll
-    for (int t = 0; t < NT; ++t) {
-      float mall = NEG_INF;
-#pragma unroll
-      for (int ww = 0; ww < NP; ++ww) mall = fmaxf(mall, marr[ww][t][n]);
-      wsc[t] = (m[t] == NEG_INF) ? 0.f : exp2f(m[t] - mall);
-      if (!scoring && kg == 0) larr[p][t][n] = accl[t][0] * wsc[t];   // every accumulator row holds the same sum
-    }
-    // Sum the summing waves' accumulators through LDS: sbuf[pair][head][col] (row pitch 129
-    // floats), written in MFMA layout, read back with one thread per (column, head quarter).
-    if (!scoring) {
-      float* mine = sbuf + (size_t)p * HP * 129 + n * 129;
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int mi = rg * 4 + r;                     // column group (the A operand's M index)
-        const int h2 = mi / a.lphp, l2 = mi % a.lphp;
-        if (!(l2 < a.lph && h2 < a.hpu)) continue;
-        const int oc = h2 * a.d_k + l2 * 8;            // first unit-local column of accumulator row r
-#pragma unroll
-        for (int t = 0; t < NT; ++t)
-#pragma unroll
-          for (int i = 0; i < 8; ++i) mine[t * 16 * 129 + oc + i] = acc[i][t][r] * wsc[t];
-      }
-    }
-    __syncthreads();
-    const int ocl = tid & 127, ohq = tid >> 7;       // this thread's column and first head (then +4, +8, ...)
+    return false;
+  };
+  // End of a segment, all threads: sum the summing waves' accumulators out of sbuf[pair][head][col]
+  // (one thread per column and head quarter) and write the group's partial for this sequence.
+  auto write_partial = [&](int pid) {
+    const int ocl = tid & 127, ohq = tid >> 7;
     if (ocl < uwc) {
 #pragma unroll
       for (int jj = 0; jj < HP / 4; ++jj) {
@@ -516,7 +271,284 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
       a.mpart[(size_t)pid * a.H + tid] = mall;
       a.lpart[(size_t)pid * a.H + tid] = l;
     }
-    __syncthreads();                                  // the slots are reused by the next segment
+  };
+
+  if (scoring) {
+    // ========================= scoring waves: HBM -> registers -> LDS, scores, publish ===========
+    Seg sg;
+    while (next_segment(sg)) {
+      const int ntl = sg.ntl, len = sg.len, s0 = sg.s0;
+      const uint16_t* Kb = sg.Kb;
+      if (tid < NP) { consumed[tid] = 0; published[tid] = 0; }
+      __syncthreads();
+      // query for this lane's 8 columns, pre-scaled (log2 domain), split into bf16 hi + lo pairs
+      // so that the dot products run on v_dot2c_f32_bf16 without losing the fp32 query
+      unsigned qh[4], ql[4];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const float f0 = col_active ? a.q[(size_t)sg.b * a.d + mycol + 2 * c] * a.qscale : 0.f;
+        const float f1 = col_active ? a.q[(size_t)sg.b * a.d + mycol + 2 * c + 1] * a.qscale : 0.f;
+        const __bf16 h0 = (__bf16)f0, h1 = (__bf16)f1;
+        const bf16x2 hi = {h0, h1};
+        const bf16x2 lo = {(__bf16)(f0 - (float)h0), (__bf16)(f1 - (float)h1)};
+        qh[c] = __builtin_bit_cast(unsigned, hi);
+        ql[c] = __builtin_bit_cast(unsigned, lo);
+      }
+      const unsigned lane_off = (unsigned)(rg * 8) * pitchB + (unsigned)mycol * 2u;
+      float mrun = NEG_INF;                           // running maximum of this lane's head (log2 domain)
+      // Tiles travel HBM -> registers (PD register sets: PD-1 tiles in flight while one is being
+      // scored) -> LDS slot, where the summing wave picks them up.  Direct-to-LDS loads are slower
+      // to issue here, and a wave's LDS operations queue behind those it has in flight.
+      u32x4 ts[PD][8];
+      auto load_tile = [&](u32x4 (&t)[8], int k) {
+        const int st = __builtin_amdgcn_readfirstlane(s0 + p + k * NP);
+        if ((st + 1) * TILE_ROWS <= len && all_active) {
+          // full tile, every lane loads: uniform row base + per-lane 32-bit offset
+          const char* tb = reinterpret_cast<const char*>(Kb) + (size_t)st * TILE_ROWS * pitchB;
+#pragma unroll
+          for (int j = 0; j < 8; ++j)
+            t[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tb + (size_t)j * pitchB + lane_off));
+        } else {
+          const int r0 = st * TILE_ROWS + rg * 8;
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            const int r = min(r0 + j, len - 1);       // rows past the end re-read the last row; masked below
+            t[j] = col_active ? __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(Kb + (size_t)r * a.d + mycol))
+                              : u32x4{0u, 0u, 0u, 0u};
+          }
+        }
+      };
+      // One tile; SI is k % PD as a type, so that the register set is a compile-time choice.
+      auto step = [&](int k, auto SI) {
+        u32x4 (&cur)[8] = ts[decltype(SI)::value];
+        // ---- scores of this unit's heads for the lane's 8 rows (log2 domain) --------------------
+        float sc[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          float d0 = 0.f, d1 = 0.f;
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            const unsigned kw = cur[j][c];             // (a scalar copy: bit_cast of a vector element picks lane 0)
+            const bf16x2 kv = __builtin_bit_cast(bf16x2, kw);
+            d0 = __builtin_amdgcn_fdot2_f32_bf16(kv, __builtin_bit_cast(bf16x2, qh[c]), d0, false);
+            d1 = __builtin_amdgcn_fdot2_f32_bf16(kv, __builtin_bit_cast(bf16x2, ql[c]), d1, false);
+          }
+          sc[j] = d0 + d1;
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {                 // sum over the head's lanes, all inside a 16-lane row
+          sc[j] = dpp_add<0xB1>(sc[j]);               // lane ^ 1
+          sc[j] = dpp_add<0x4E>(sc[j]);               // lane ^ 2
+          if (a.lphp > 4) sc[j] = dpp_add<0x141>(sc[j]);   // other quad of the 8-lane half
+          if (a.lphp > 8) sc[j] = dpp_add<0x140>(sc[j]);   // other half of the row
+        }
+        // ---- this tile's softmax numerators of the unit's heads, against the running maximum -----
+        const int st = s0 + p + k * NP;
+        if ((st + 1) * TILE_ROWS > len) {             // last, partial tile: rows past the end weigh nothing
+          const int row0 = st * TILE_ROWS + rg * 8;
+#pragma unroll
+          for (int j = 0; j < 8; ++j) sc[j] = (row0 + j < len) ? sc[j] : NEG_INF;
+        }
+        float tmax = fmaxf(fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3])), fmaxf(fmaxf(sc[4], sc[5]), fmaxf(sc[6], sc[7])));
+        tmax = max_over_row_groups(tmax);
+        mrun = fmaxf(mrun, tmax);
+        const float ref = (mrun == NEG_INF) ? 0.f : mrun;
+        unsigned pw[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const bf16x2 v = {(__bf16)__builtin_amdgcn_exp2f(sc[2 * i] - ref), (__bf16)__builtin_amdgcn_exp2f(sc[2 * i + 1] - ref)};
+          pw[i] = __builtin_bit_cast(unsigned, v);
+        }
+        // ---- hand the tile over: slot k % NS, once the summing wave has taken tile k-NS out of it;
+        //      the tile is in LDS before the words that announce it leave
+        {
+          int spins = 0;
+          while (!dead && __hip_atomic_load(&consumed[p], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) < k - NS + 1) {
+            if (++spins > a.spin_limit) { give_up(); break; }
+            __builtin_amdgcn_s_sleep(2);
+          }
+          asm volatile("" ::: "memory");
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) tiles[p][k % NS][j * 64 + lane] = cur[j];
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        // ---- publish: {tag, running max, p0 p1, p2 p3} and {tag, 0, p4 p5, p6 p7} per row group ----
+        const unsigned itk = sg.it0 + (unsigned)k + 1u;
+        const unsigned tag = a.tag_base + itk;
+        u32x4* ring = team_ring + (size_t)(itk & (EXCH_SLOTS - 1)) * (HP * 8);
+        if (pub_lane) {
+          st_exch(ring + (myhead * 4 + rg), u32x4{tag, __float_as_uint(mrun), pw[0], pw[1]}, xl);
+          st_exch(ring + ((HP + myhead) * 4 + rg), u32x4{tag, 0u, pw[2], pw[3]}, xl);
+        }
+        // a hint for the summing wave (the words themselves carry the proof)
+        if (lane == 0) __hip_atomic_store(&published[p], k + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        if (k + PD < ntl) load_tile(cur, k + PD);
+      };
+#pragma unroll
+      for (int k = 0; k < PD; ++k)
+        if (k < ntl) load_tile(ts[k], k);
+      for (int k = 0; k < ntl; k += PD) unrolled_steps<0, PD>(k, ntl, step);
+
+      // ---- end of this sequence's share (the barriers of the summing waves' merge) ---------------
+      __syncthreads();
+      __syncthreads();
+      __syncthreads();
+      write_partial(sg.b + g);
+      __syncthreads();
+    }
+  } else {
+    // ========================= summing waves: gather, rescale, MFMA ==============================
+    Seg sg;
+    while (next_segment(sg)) {
+      const int ntl = sg.ntl;
+      // (threads 0..NP-1, which reset the hand-over counters, belong to a scoring wave)
+      __syncthreads();
+      // softmax state and accumulators; accl: sum of the weights (an all-ones A operand)
+      float m[NT];
+      f32x4 acc[8][NT], accl[NT];
+#pragma unroll
+      for (int t = 0; t < NT; ++t) {
+        m[t] = NEG_INF;
+        accl[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+      }
+      constexpr int GW = 2 * NT;                      // 16-byte words per lane and tile
+      constexpr int DEPTH = FUSED_GATHERS;            // gathers in flight; buffer of tile k is k % DEPTH
+      auto gather = [&](u32x4 (&q)[GW], int k) {
+        const u32x4* base = team_ring + (size_t)((sg.it0 + (unsigned)k + 1u) & (EXCH_SLOTS - 1)) * (HP * 8) + (n * 4 + kg);
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+#pragma unroll
+          for (int t = 0; t < NT; ++t) q[c * NT + t] = ld_exch(base + (c * HP + t * 16) * 4);
+      };
+      // A gather is only worth issuing once the words are probably there: the partner's own
+      // progress is the hint (the workgroups of a group move at about the same pace).
+      auto partner_at = [&]() {
+        return __builtin_amdgcn_readfirstlane(
+            __hip_atomic_load(&published[p], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
+      };
+      u32x4 gq[DEPTH][GW];
+      int issued = 0;                                 // gathers of tiles 0 .. issued-1 have been issued
+      // One tile; BI is k % DEPTH as a type, so that every buffer index is a compile-time constant
+      // (the buffers must stay in the registers their loads were issued to).
+      auto step = [&](int k, auto BI) {
+        constexpr int B0 = decltype(BI)::value;
+        const unsigned tag = a.tag_base + sg.it0 + (unsigned)k + 1u;
+        if (issued == k) {                            // nothing in flight for this tile yet
+          int hs = 0;
+          while (!dead && partner_at() < k + 1) {
+            if (++hs > a.spin_limit) { give_up(); break; }
+            __builtin_amdgcn_s_sleep(1);
+          }
+          gather(gq[B0], k);
+          issued = k + 1;
+        }
+        {                                             // look ahead as far as the partner has published
+          const int pa = partner_at();
+#pragma unroll
+          for (int i = 1; i < DEPTH; ++i)
+            if (issued == k + i && issued < ntl && pa > issued) {
+              gather(gq[(B0 + i) % DEPTH], issued);
+              ++issued;
+            }
+        }
+        wait_vm_outstanding((issued - k - 1) * GW);
+        u32x4 (&q)[GW] = gq[B0];
+        if constexpr (NT == 1) asm volatile("" : "+v"(q[0]), "+v"(q[1]) : : "memory");
+        else asm volatile("" : "+v"(q[0]), "+v"(q[1]), "+v"(q[2]), "+v"(q[3]) : : "memory");
+        // every word of tile k must carry its tag; gather again while any is missing
+        int spins = 0;
+        for (;;) {
+          unsigned bad = 0;
+#pragma unroll
+          for (int t = 0; t < NT; ++t) {
+            const unsigned bt = (q[t][0] ^ tag) | (q[NT + t][0] ^ tag);
+            bad |= (heads_full || (t * 16 + n) < a.H) ? bt : 0u;
+          }
+          if (__all(bad == 0)) break;
+          if (dead || ++spins > a.spin_limit) { give_up(); break; }
+          __builtin_amdgcn_s_sleep(8);
+          gather(q, k);
+          asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+          if constexpr (NT == 1) asm volatile("" : "+v"(q[0]), "+v"(q[1]) : : "memory");
+          else asm volatile("" : "+v"(q[0]), "+v"(q[1]), "+v"(q[2]), "+v"(q[3]) : : "memory");
+        }
+        // the scoring wave published after it had written the tile, so the tile is in its slot
+        u32x4 kt[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) kt[j] = tiles[p][k % NS][j * 64 + lane];
+        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(kt[0]), "+v"(kt[1]), "+v"(kt[2]), "+v"(kt[3]),
+                     "+v"(kt[4]), "+v"(kt[5]), "+v"(kt[6]), "+v"(kt[7]) : : "memory");
+        if (lane == 0) __hip_atomic_store(&consumed[p], k + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        bf16x8 pb[NT];
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+          const bool live = heads_full || (t * 16 + n) < a.H;      // padded head: no weights at all
+          const float mn = live ? __uint_as_float(q[t][1]) : NEG_INF;
+          const float ref = (mn == NEG_INF) ? 0.f : mn;            // all -inf so far: exp2(-inf - 0) = 0
+          const float alpha = __builtin_amdgcn_exp2f(m[t] - ref);
+          m[t] = mn;
+          const u32x4 pw = live ? u32x4{q[t][2], q[t][3], q[NT + t][2], q[NT + t][3]} : u32x4{0u, 0u, 0u, 0u};
+          pb[t] = __builtin_bit_cast(bf16x8, pw);
+          if (__any(alpha != 1.f)) {
+            accl[t] *= alpha;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[i][t] *= alpha;
+          }
+        }
+        u32x4 am[8];
+        transpose8x8(kt, am);
+        const u32x4 ones_bits = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
+        const bf16x8 ones = __builtin_bit_cast(bf16x8, ones_bits);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) accl[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pb[t], accl[t], 0, 0, 0);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const bf16x8 av = __builtin_bit_cast(bf16x8, am[i]);
+#pragma unroll
+          for (int t = 0; t < NT; ++t)
+            acc[i][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, pb[t], acc[i][t], 0, 0, 0);
+        }
+      };
+      for (int k = 0; k < ntl; k += DEPTH) unrolled_steps<0, DEPTH>(k, ntl, step);
+
+      // ---- end of this sequence's share: merge the summing waves and write one partial -----------
+      __syncthreads();                                // every slot is idle from here on
+      if (kg == 0) {
+#pragma unroll
+        for (int t = 0; t < NT; ++t) marr[p][t][n] = m[t];
+      }
+      __syncthreads();
+      {
+        // accumulators -> sbuf[pair][head][col] (row pitch 129 floats), in MFMA layout, scaled to
+        // the maximum over the four summing waves
+        float wsc[NT];
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+          float mall = NEG_INF;
+#pragma unroll
+          for (int ww = 0; ww < NP; ++ww) mall = fmaxf(mall, marr[ww][t][n]);
+          wsc[t] = (m[t] == NEG_INF) ? 0.f : exp2f(m[t] - mall);
+          if (kg == 0) larr[p][t][n] = accl[t][0] * wsc[t];   // every accumulator row holds the same sum
+        }
+        float* mine = sbuf + (size_t)p * HP * 129 + n * 129;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int mi = rg * 4 + r;                   // column group (the A operand's M index)
+          const int h2 = mi / a.lphp, l2 = mi % a.lphp;
+          if (!(l2 < a.lph && h2 < a.hpu)) continue;
+          const int oc = h2 * a.d_k + l2 * 8;          // first unit-local column of accumulator row r
+#pragma unroll
+          for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) mine[t * 16 * 129 + oc + i] = acc[i][t][r] * wsc[t];
+        }
+      }
+      __syncthreads();
+      write_partial(sg.b + g);
+      __syncthreads();                                // the slots are reused by the next segment
+    }
   }
 }
 
@@ -781,7 +813,8 @@ bool xcd_round_robin(int device) {
 }
 
 size_t fused_exch_bytes(const FusedGeom& g) {
-  return (size_t)g.NG * g.NP * EXCH_SLOTS * (g.NT * 16) * TILE_ROWS * sizeof(unsigned long long);
+  // per team and ring slot: two 16-byte words for each (padded head, row group of 8)
+  return (size_t)g.NG * g.NP * EXCH_SLOTS * (g.NT * 16) * 8 * 16;
 }
 
 void launch_fused_stream(const FusedGeom& g, const FusedArgs& a, hipStream_t st) {

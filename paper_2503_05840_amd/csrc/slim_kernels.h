@@ -50,7 +50,8 @@ constexpr int EXCH_SLOTS = 16;       // ring depth of the score exchange (a powe
 constexpr int FUSED_MAX_B = 1024;    // sequences per call the fast path handles
 constexpr int FUSED_PAIRS = 4;       // (scoring wave, summing wave) pairs per workgroup of the stream kernel
 constexpr int FUSED_SLOTS = 4;       // LDS landing slots (8 KB tiles) per pair
-constexpr int FUSED_AHEAD = 1;       // tiles a scoring wave keeps in flight (1..3, < FUSED_SLOTS)
+constexpr int FUSED_AHEAD = 2;       // register sets of a scoring wave: one tile being scored, the others in flight
+constexpr int FUSED_GATHERS = 4;     // score gathers a summing wave keeps in flight
 constexpr int PROJ_MAX_PARTS = 64;   // partials per sequence the projection merges
 
 struct FusedGeom {
@@ -67,7 +68,7 @@ struct FusedArgs {
   int T, B, H, d, d_k;
   int G, NG, gpx, lph, lphp, hpu;
   float qscale;                       // log2(e) / sqrt(d_k): scores live in the log2 domain
-  unsigned long long* exch;           // [NG][NP][EXCH_SLOTS][16*NT][TILE_ROWS] (tag, score) words
+  unsigned long long* exch;           // [NG][NP][EXCH_SLOTS][2][16*NT][4] 16-byte words {tag, max, 4 bf16 weights}
   unsigned tag_base, launch_id;
   int spin_limit;
   float* Cpart;                       // [nparts][H][d]
