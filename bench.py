@@ -30,7 +30,8 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 STAGES = {                      # kernels of one slim_decode call, in launch order, per variant
     "generic": ["head_scores", "weighted_sum", "combine", "project"],
-    "fused": ["fused_stream", "project_mfma"],
+    "fused": ["fused_stream", "project_mfma"],          # one launch when B <= 16: the second entry stays 0
+    "fused_split": ["fused_stream", "project_mfma"],
 }
 
 
@@ -44,7 +45,7 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=1, choices=[0, 1, 2, 3])
-    ap.add_argument("--variant", default="auto", choices=["auto", "generic", "fused"])
+    ap.add_argument("--variant", default="auto", choices=["auto", "generic", "fused", "fused_split"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copies", type=int, default=0, help="K-cache copies to rotate over (0 = enough to exceed 512 MB)")
     args = ap.parse_args()
@@ -96,7 +97,7 @@ def main():
     if ragged:
         kw.update(seq_lens=lens_dev, seq_lens_host=lens)
     variant = {"auto": binding.VARIANT_AUTO, "generic": binding.VARIANT_GENERIC,
-               "fused": binding.VARIANT_FUSED}[args.variant]
+               "fused": binding.VARIANT_FUSED, "fused_split": binding.VARIANT_FUSED_SPLIT}[args.variant]
 
     def slim(i, **extra):
         binding.slim_decode(q, Ks[i % ncopies], Wkv, out, B, H, T, d, variant=variant, **kw, **extra)

@@ -92,9 +92,11 @@ typedef struct slim_opts {
 
 #define SLIM_VARIANT_AUTO      0
 #define SLIM_VARIANT_GENERIC   1   /* plain vector-ALU kernels, any supported shape            */
+#define SLIM_VARIANT_FUSED_SPLIT 2 /* as FUSED, but the merge + projection always runs as a launch of
+                                      its own                                                  */
 #define SLIM_VARIANT_FUSED     3   /* bf16, H <= 32, d_k <= 128: single pass over K with the weighted
-                                      sum and the projection on MFMA; falls back to GENERIC when
-                                      the shape does not qualify                                */
+                                      sum and the projection on MFMA (one launch when B <= 16, else
+                                      two); falls back to GENERIC when the shape does not qualify */
 
 /* The implementation SLIM_VARIANT_AUTO resolves to for a K-cache decode of this shape
  * (one of the SLIM_VARIANT_* values above, never AUTO); 0 on invalid arguments. */

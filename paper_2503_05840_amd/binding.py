@@ -16,12 +16,12 @@ LIB_PATH = os.environ.get("SLIM_ATTENTION_LIB") or os.path.join(_PKG, "libslim_a
 
 SLIM_OK = 0
 SLIM_F32, SLIM_BF16 = 0, 1
-VARIANT_AUTO, VARIANT_GENERIC, VARIANT_FUSED = 0, 1, 3
+VARIANT_AUTO, VARIANT_GENERIC, VARIANT_FUSED_SPLIT, VARIANT_FUSED = 0, 1, 2, 3
 DTYPES = {"f32": SLIM_F32, "bf16": SLIM_BF16}
 
 EXPORTS = ("slim_strerror", "slim_prepare_wkv", "slim_pack_weights", "slim_workspace_bytes",
            "slim_variant_for", "slim_decode", "vanilla_kv_decode", "slim_decode_xcache")
-VARIANT_NAMES = {1: "generic", 3: "fused"}
+VARIANT_NAMES = {1: "generic", 2: "fused_split", 3: "fused"}
 
 
 class SlimOpts(ctypes.Structure):

@@ -101,6 +101,16 @@ __device__ __forceinline__ void st_exch(u32x4* p, u32x4 v, bool xcd_local) {
   if (xcd_local) asm volatile("s_nop 1\n\tglobal_store_dwordx4 %0, %1, off\n\ts_nop 1" : : "v"(p), "v"(v) : "memory");
   else asm volatile("s_nop 1\n\tglobal_store_dwordx4 %0, %1, off sc0 sc1\n\ts_nop 1" : : "v"(p), "v"(v) : "memory");
 }
+// Results other workgroups of the same launch will read (write_through): stored at system scope.
+__device__ __forceinline__ void st_result(float* p, float v, bool write_through) {
+  if (write_through) asm volatile("global_store_dword %0, %1, off sc0 sc1" : : "v"(p), "v"(v) : "memory");
+  else *p = v;
+}
+__device__ __forceinline__ void st_result(int* p, int v, bool write_through) {
+  if (write_through) asm volatile("global_store_dword %0, %1, off sc0 sc1" : : "v"(p), "v"(v) : "memory");
+  else *p = v;
+}
+
 // s_waitcnt vmcnt(n) for a run-time even n <= 30 (the instruction wants a constant).
 __device__ __forceinline__ void wait_vm_outstanding(int n) {
   switch (n >> 1) {
@@ -137,6 +147,254 @@ __device__ void build_tile_prefix(int* prefix, const int32_t* lens, int B, int T
 }
 
 // ------------------------------------------------------------------------------------------------
+// merge + projection:  out[b][h d_k + j] = sum_c Cn[b][h][c] W[c][h d_k + j]
+// One workgroup (8 waves) per (head h, row split cs of W, batch chunk bz of 16*NBT sequences).  The
+// wave tile is the same 32 x 128 register tile as above (rows = c, columns = the head's output
+// columns), A = W tile transposed, B = merged, normalised C^T split in bf16 hi + lo.
+// COH: the partials come from other workgroups of the same launch (loads at agent scope).
+// ------------------------------------------------------------------------------------------------
+template <int NBT>
+struct ProjShared {
+  int pid0s[16 * NBT], nps[16 * NBT];
+  float wpid[16 * NBT][PROJ_MAX_PARTS];
+  float buf[8][NBT * 4][64];
+  float obuf[16 * NBT][128];
+  int is_last;
+};
+
+template <bool COH>
+__device__ __forceinline__ float ld_part(const float* p) {
+  if constexpr (COH) return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  else return *p;
+}
+template <bool COH>
+__device__ __forceinline__ int ld_err(const int* p) {
+  if constexpr (COH) return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  else return *p;
+}
+
+// `after_w_issue` runs (all threads) once the first tile of W is in flight and before any partial
+// is read: the place to build the tile prefix, or to wait for the other workgroups' partials.
+template <int NBT, bool COH, class Hook>
+__device__ __forceinline__ void project_work(const ProjArgs& a, int h, int cs, int bz, const int* prefix,
+                                             ProjShared<NBT>& sm, Hook&& after_w_issue) {
+  const int bbase = bz * 16 * NBT;
+  const int nb = min(16 * NBT, a.B - bbase);
+  constexpr int NW = 8, NTHR = 512;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int idx = lane & 15, rg = lane >> 4;
+  const int n = idx, kg = rg;
+
+  const int lph = a.d_k / 8;
+  const bool col_active = idx < lph;
+  const uint16_t* Wh = a.W + (size_t)h * a.d_k + idx * 8;
+  const int c_lo = cs * a.crows, c_hi = min(a.rows, c_lo + a.crows);
+  const int ntile = (c_hi - c_lo + TILE_ROWS - 1) / TILE_ROWS;
+  auto load_w = [&](u32x4 (&wt)[8], int ct) {
+    const int c0 = c_lo + ct * TILE_ROWS;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int r = min(c0 + rg * 8 + j, a.rows - 1);
+      wt[j] = col_active ? *reinterpret_cast<const u32x4*>(Wh + (size_t)r * a.e) : u32x4{0u, 0u, 0u, 0u};
+    }
+  };
+  u32x4 wt[8], wn[8];
+  if (w < ntile) load_w(wt, w);                      // in flight while the merge weights are built
+  if (w + NW < ntile) load_w(wn, w + NW);
+
+  after_w_issue();
+
+  // ---- which partials belong to which sequence, and their merge weights for head h ------------
+  for (int bl = w; bl < nb; bl += NW) {              // one wave per sequence, one lane per partial
+    const int b = bbase + bl;
+    int p0, np;
+    if (a.mode == 0) {
+      const int VT = prefix[a.B];
+      const int Qt = (VT + a.NG - 1) / a.NG;
+      const int gf = prefix[b] / Qt, gl = (prefix[b + 1] - 1) / Qt;
+      p0 = b + gf;
+      np = gl - gf + 1;
+    } else {
+      p0 = b * a.nsplit;
+      np = a.nsplit;
+    }
+    np = min(np, PROJ_MAX_PARTS);
+    float mp = NEG_INF, lp = 0.f;
+    if (lane < np) {
+      mp = ld_part<COH>(a.mpart + (size_t)(p0 + lane) * a.H + h);
+      lp = ld_part<COH>(a.lpart + (size_t)(p0 + lane) * a.H + h);
+    }
+    float M = mp;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) M = fmaxf(M, __shfl_xor(M, o));
+    const float wgt = (mp == NEG_INF) ? 0.f : exp2f((mp - M) * a.mscale);
+    float L = wgt * lp;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) L += __shfl_xor(L, o);
+    if (lane < np) sm.wpid[bl][lane] = wgt / L;
+    if (lane == 0) { sm.pid0s[bl] = p0; sm.nps[bl] = np; }
+  }
+  __syncthreads();
+
+  f32x4 acc[8][NBT];
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int t = 0; t < NBT; ++t) acc[i][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  for (int ct = w; ct < ntile; ct += NW) {
+    const int c0 = c_lo + ct * TILE_ROWS;
+    const bool more = ct + NW < ntile;
+    // B operand: merged C for (b = bt*16 + n, rows c0 + kg*8 .. +8)
+    bf16x8 bhi[NBT], blo[NBT];
+    const int c = c0 + kg * 8;
+#pragma unroll
+    for (int t = 0; t < NBT; ++t) {
+      float cn[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) cn[j] = 0.f;
+      const int bl = t * 16 + n;
+      if (bl < nb && c < c_hi) {
+        const int p0 = sm.pid0s[bl], np = sm.nps[bl];
+        if constexpr (COH) {
+          // four partials per round trip: agent-scope loads, one wait
+          for (int pb = 0; pb < np; pb += 4) {
+            f32x4 x[4][2];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              const int pp = min(pb + q, np - 1);
+              const float* src = a.Cpart + ((size_t)(p0 + pp) * a.H + h) * a.rows + c;
+              asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(x[q][0]) : "v"(src) : "memory");
+              asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(x[q][1]) : "v"(src + 4) : "memory");
+            }
+            asm volatile("s_waitcnt vmcnt(0)" : "+v"(x[0][0]), "+v"(x[0][1]), "+v"(x[1][0]), "+v"(x[1][1]),
+                         "+v"(x[2][0]), "+v"(x[2][1]), "+v"(x[3][0]), "+v"(x[3][1]) : : "memory");
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              const float wgt = (pb + q < np) ? sm.wpid[bl][min(pb + q, np - 1)] : 0.f;
+#pragma unroll
+              for (int j = 0; j < 4; ++j) {
+                cn[j] = fmaf(wgt, x[q][0][j], cn[j]);
+                cn[4 + j] = fmaf(wgt, x[q][1][j], cn[4 + j]);
+              }
+            }
+          }
+        } else {
+          for (int p = 0; p < np; ++p) {
+            const float wgt = sm.wpid[bl][p];
+            const float* src = a.Cpart + ((size_t)(p0 + p) * a.H + h) * a.rows + c;
+            const float4 x0 = *reinterpret_cast<const float4*>(src);
+            const float4 x1 = *reinterpret_cast<const float4*>(src + 4);
+            cn[0] = fmaf(wgt, x0.x, cn[0]); cn[1] = fmaf(wgt, x0.y, cn[1]);
+            cn[2] = fmaf(wgt, x0.z, cn[2]); cn[3] = fmaf(wgt, x0.w, cn[3]);
+            cn[4] = fmaf(wgt, x1.x, cn[4]); cn[5] = fmaf(wgt, x1.y, cn[5]);
+            cn[6] = fmaf(wgt, x1.z, cn[6]); cn[7] = fmaf(wgt, x1.w, cn[7]);
+          }
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const __bf16 hi = (__bf16)cn[j];
+        bhi[t][j] = hi;
+        blo[t][j] = (__bf16)(cn[j] - (float)hi);
+      }
+    }
+    u32x4 am[8];
+    transpose8x8(wt, am);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const bf16x8 av = __builtin_bit_cast(bf16x8, am[i]);
+#pragma unroll
+      for (int t = 0; t < NBT; ++t) {
+        acc[i][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bhi[t], acc[i][t], 0, 0, 0);
+        acc[i][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, blo[t], acc[i][t], 0, 0, 0);
+      }
+    }
+    if (more) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) wt[j] = wn[j];
+      if (ct + 2 * NW < ntile) load_w(wn, ct + 2 * NW);
+    }
+  }
+
+  // ---- sum the 8 waves: sm.obuf[b][j] ---------------------------------------------------------------
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+#pragma unroll
+    for (int t = 0; t < NBT; ++t)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) sm.buf[w][t * 4 + r][lane] = acc[i][t][r];
+    __syncthreads();
+    for (int v = tid; v < NBT * 4 * 64; v += NTHR) {
+      const int reg = v >> 6, ln = v & 63;
+      float sum = 0.f;
+#pragma unroll
+      for (int ww = 0; ww < NW; ++ww) sum += sm.buf[ww][reg][ln];
+      const int t = reg >> 2, r = reg & 3;
+      const int bl = t * 16 + (ln & 15);
+      const int mi = (ln >> 4) * 4 + r;
+      if (mi < lph) sm.obuf[bl][mi * 8 + i] = sum;
+    }
+    __syncthreads();
+  }
+
+  if (a.csw == 1) {
+    const bool bad = a.err && ld_err<COH>(a.err) == (int)a.launch_id;      // the stream kernel gave up waiting
+    for (int v = tid; v < nb * a.d_k; v += NTHR) {
+      const int bl = v / a.d_k, j = v % a.d_k;
+      a.out[(size_t)(bbase + bl) * a.e + h * a.d_k + j] = bad ? NAN : sm.obuf[bl][j];
+    }
+    return;
+  }
+  // ---- several workgroups share the rows of W: last one to arrive adds the partial sums ---------
+  // No cache-wide fences: the partial sums are stored write-through and waited for (so they are
+  // visible device-wide) before this workgroup's arrival is counted, and the last workgroup reads
+  // them with device-coherent loads.
+  for (int v = tid; v < nb * a.d_k; v += NTHR) {
+    const int bl = v / a.d_k, j = v % a.d_k;
+    float* dst = &a.outpart[((size_t)cs * a.B + bbase + bl) * a.e + h * a.d_k + j];
+    asm volatile("global_store_dword %0, %1, off sc0 sc1" : : "v"(dst), "v"(sm.obuf[bl][j]) : "memory");
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  if (tid == 0) {
+    const int old = __hip_atomic_fetch_add(&a.counters[bz * a.H + h], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    sm.is_last = (old == a.csw - 1);
+  }
+  __syncthreads();
+  if (!sm.is_last) return;
+  const bool bad = a.err && __hip_atomic_load(a.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (int)a.launch_id;
+  for (int v = tid; v < nb * a.d_k; v += NTHR) {
+    const int bl = v / a.d_k, j = v % a.d_k;
+    float sum = 0.f;
+    for (int s0 = 0; s0 < a.csw; s0 += 8) {
+      float part[8];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        const int sp = min(s0 + q, a.csw - 1);
+        const float* src = &a.outpart[((size_t)sp * a.B + bbase + bl) * a.e + h * a.d_k + j];
+        asm volatile("global_load_dword %0, %1, off sc1" : "=v"(part[q]) : "v"(src) : "memory");
+      }
+      asm volatile("s_waitcnt vmcnt(0)" : "+v"(part[0]), "+v"(part[1]), "+v"(part[2]), "+v"(part[3]),
+                   "+v"(part[4]), "+v"(part[5]), "+v"(part[6]), "+v"(part[7]) : : "memory");
+#pragma unroll
+      for (int q = 0; q < 8; ++q) if (s0 + q < a.csw) sum += part[q];
+    }
+    a.out[(size_t)(bbase + bl) * a.e + h * a.d_k + j] = bad ? NAN : sum;    // NaN: the stream kernel gave up waiting
+  }
+  if (tid == 0) a.counters[bz * a.H + h] = 0;
+}
+
+template <int NBT>
+__global__ __launch_bounds__(512) void project_mfma_kernel(const ProjArgs a) {
+  __shared__ int prefix[FUSED_MAX_B + 1];
+  __shared__ ProjShared<NBT> sm;
+  project_work<NBT, false>(a, blockIdx.x, blockIdx.y, blockIdx.z, prefix, sm, [&]() {
+    if (a.mode == 0) build_tile_prefix(prefix, a.seq_lens, a.B, a.T);
+  });
+}
+
+// ------------------------------------------------------------------------------------------------
 // fused stream kernel
 //
 // A workgroup is FUSED_PAIRS pairs of waves.  The first wave of a pair (the "scoring" wave) streams
@@ -170,20 +428,21 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
   static_assert(NP == 4 && NS >= 3 && NS <= 5, "the thread mappings below assume 4 pairs");
 
   // ---- which group / column unit is this workgroup -------------------------------------------
-  int g, u;
+  int g = 0, u = 0;
+  bool has_work = true;                             // (workgroup-uniform)
   {
     const int i = blockIdx.x;
     if (a.gpx > 0) {                                // groups packed inside one XCD (WG i -> XCD i % 8)
       const int x = i & 7, r = i >> 3;
       const int gx = r / a.G;
-      if (gx >= a.gpx) return;
+      if (gx >= a.gpx) has_work = false;
       g = x * a.gpx + gx;
       u = r % a.G;
     } else {
       g = i / a.G;
       u = i % a.G;
     }
-    if (g >= a.NG) return;
+    if (g >= a.NG) has_work = false;
   }
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int idx = lane & 15, rg = lane >> 4;        // column group / row group of the register tile
@@ -192,14 +451,16 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
   const bool scoring = wu < NP;                     // wave role
   const int p = wu & (NP - 1);                      // pair
 
+  const bool fuse = a.fuse != 0;
   if (blockIdx.x == 0 && a.counters)                // the projection's arrival counters start at 0
-    for (int i = tid; i < a.ncounters; i += NTHR) a.counters[i] = 0;
+    for (int i = tid; i < a.ncounters; i += NTHR) st_result(a.counters + i, 0, fuse);
 
   build_tile_prefix(prefix, a.seq_lens, a.B, a.T);
   const int VT = prefix[a.B];
   const int Qt = (VT + a.NG - 1) / a.NG;            // tiles per group
   const int v0 = g * Qt, v1 = min(VT, v0 + Qt);
-  if (v0 >= v1) return;
+  if (v0 >= v1) has_work = false;
+  if (!has_work && !fuse) return;
 
   // ---- lane -> column mapping inside the unit --------------------------------------------------
   const int hh = idx / a.lphp, li = idx % a.lphp;
@@ -226,7 +487,8 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
   struct Seg { int b, s0, ntl, len; unsigned it0; const uint16_t* Kb; };
   int seg_b = 0;
   unsigned seg_it = 0;                              // tiles this pair has been through so far
-  while (prefix[seg_b + 1] <= v0) ++seg_b;
+  if (has_work)
+    while (prefix[seg_b + 1] <= v0) ++seg_b;
   auto next_segment = [&](Seg& sg) -> bool {
     for (; seg_b < a.B && prefix[seg_b] < v1; ++seg_b) {
       const int b = seg_b;
@@ -257,7 +519,7 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
         float osum = 0.f;
 #pragma unroll
         for (int ww = 0; ww < NP; ++ww) osum += sbuf[((size_t)ww * HP + h) * 129 + ocl];
-        if (h < a.H) a.Cpart[((size_t)pid * a.H + h) * a.d + ucol0 + ocl] = osum;
+        if (h < a.H) st_result(a.Cpart + ((size_t)pid * a.H + h) * a.d + ucol0 + ocl, osum, fuse);
       }
     }
     if (u == 0 && tid < a.H) {
@@ -268,12 +530,14 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
         mall = fmaxf(mall, marr[ww][t][nn]);
         l += larr[ww][t][nn];
       }
-      a.mpart[(size_t)pid * a.H + tid] = mall;
-      a.lpart[(size_t)pid * a.H + tid] = l;
+      st_result(a.mpart + (size_t)pid * a.H + tid, mall, fuse);
+      st_result(a.lpart + (size_t)pid * a.H + tid, l, fuse);
     }
   };
 
-  if (scoring) {
+  if (!has_work) {
+    // no share of the cache (fewer tiles than groups): straight to the projection
+  } else if (scoring) {
     // ========================= scoring waves: HBM -> registers -> LDS, scores, publish ===========
     Seg sg;
     while (next_segment(sg)) {
@@ -550,202 +814,31 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
       __syncthreads();                                // the slots are reused by the next segment
     }
   }
-}
+  if (!fuse) return;
 
-// ------------------------------------------------------------------------------------------------
-// merge + projection kernel:  out[b][h d_k + j] = sum_c Cn[b][h][c] W[c][h d_k + j]
-// grid (H, CSW, batch chunks of 16*NBT).  Workgroup = 8 waves over its share of the rows of W;
-// the wave tile is the same 32 x 128 register tile as above (rows = c, columns = the head's
-// output columns), A = W tile transposed, B = merged, normalised C^T split in bf16 hi + lo.
-// ------------------------------------------------------------------------------------------------
-template <int NBT>
-__global__ __launch_bounds__(512) void project_mfma_kernel(const ProjArgs a) {
-  constexpr int NW = 8, NTHR = 512;
-  __shared__ int prefix[FUSED_MAX_B + 1];
-  __shared__ int pid0s[16 * NBT], nps[16 * NBT];
-  __shared__ float wpid[16 * NBT][PROJ_MAX_PARTS];
-  __shared__ float buf[NW][NBT * 4][64];
-  __shared__ float obuf[16 * NBT][128];
-  __shared__ int is_last;
-
-  const int h = blockIdx.x, cs = blockIdx.y;
-  const int bbase = blockIdx.z * 16 * NBT;
-  const int nb = min(16 * NBT, a.B - bbase);
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const int idx = lane & 15, rg = lane >> 4;
-  const int n = idx, kg = rg;
-
-  const int lph = a.d_k / 8;
-  const bool col_active = idx < lph;
-  const uint16_t* Wh = a.W + (size_t)h * a.d_k + idx * 8;
-  const int c_lo = cs * a.crows, c_hi = min(a.rows, c_lo + a.crows);
-  const int ntile = (c_hi - c_lo + TILE_ROWS - 1) / TILE_ROWS;
-  auto load_w = [&](u32x4 (&wt)[8], int ct) {
-    const int c0 = c_lo + ct * TILE_ROWS;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const int r = min(c0 + rg * 8 + j, a.rows - 1);
-      wt[j] = col_active ? *reinterpret_cast<const u32x4*>(Wh + (size_t)r * a.e) : u32x4{0u, 0u, 0u, 0u};
-    }
-  };
-  u32x4 wt[8], wn[8];
-  if (w < ntile) load_w(wt, w);                      // in flight while the merge weights are built
-
-  // ---- which partials belong to which sequence, and their merge weights for head h ------------
-  if (a.mode == 0) build_tile_prefix(prefix, a.seq_lens, a.B, a.T);
-  for (int bl = w; bl < nb; bl += NW) {              // one wave per sequence, one lane per partial
-    const int b = bbase + bl;
-    int p0, np;
-    if (a.mode == 0) {
-      const int VT = prefix[a.B];
-      const int Qt = (VT + a.NG - 1) / a.NG;
-      const int gf = prefix[b] / Qt, gl = (prefix[b + 1] - 1) / Qt;
-      p0 = b + gf;
-      np = gl - gf + 1;
-    } else {
-      p0 = b * a.nsplit;
-      np = a.nsplit;
-    }
-    np = min(np, PROJ_MAX_PARTS);
-    float mp = NEG_INF, lp = 0.f;
-    if (lane < np) {
-      mp = a.mpart[(size_t)(p0 + lane) * a.H + h];
-      lp = a.lpart[(size_t)(p0 + lane) * a.H + h];
-    }
-    float M = mp;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) M = fmaxf(M, __shfl_xor(M, o));
-    const float wgt = (mp == NEG_INF) ? 0.f : exp2f((mp - M) * a.mscale);
-    float L = wgt * lp;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) L += __shfl_xor(L, o);
-    if (lane < np) wpid[bl][lane] = wgt / L;
-    if (lane == 0) { pid0s[bl] = p0; nps[bl] = np; }
-  }
-  __syncthreads();
-
-  f32x4 acc[8][NBT];
-#pragma unroll
-  for (int i = 0; i < 8; ++i)
-#pragma unroll
-    for (int t = 0; t < NBT; ++t) acc[i][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-  for (int ct = w; ct < ntile; ct += NW) {
-    const int c0 = c_lo + ct * TILE_ROWS;
-    const bool more = ct + NW < ntile;
-    if (more) load_w(wn, ct + NW);
-    // B operand: merged C for (b = bt*16 + n, rows c0 + kg*8 .. +8)
-    bf16x8 bhi[NBT], blo[NBT];
-    const int c = c0 + kg * 8;
-#pragma unroll
-    for (int t = 0; t < NBT; ++t) {
-      float cn[8];
-#pragma unroll
-      for (int j = 0; j < 8; ++j) cn[j] = 0.f;
-      const int bl = t * 16 + n;
-      if (bl < nb && c < c_hi) {
-        const int p0 = pid0s[bl], np = nps[bl];
-        for (int p = 0; p < np; ++p) {
-          const float wgt = wpid[bl][p];
-          const float* src = a.Cpart + ((size_t)(p0 + p) * a.H + h) * a.rows + c;
-          const float4 x0 = *reinterpret_cast<const float4*>(src);
-          const float4 x1 = *reinterpret_cast<const float4*>(src + 4);
-          cn[0] = fmaf(wgt, x0.x, cn[0]); cn[1] = fmaf(wgt, x0.y, cn[1]);
-          cn[2] = fmaf(wgt, x0.z, cn[2]); cn[3] = fmaf(wgt, x0.w, cn[3]);
-          cn[4] = fmaf(wgt, x1.x, cn[4]); cn[5] = fmaf(wgt, x1.y, cn[5]);
-          cn[6] = fmaf(wgt, x1.z, cn[6]); cn[7] = fmaf(wgt, x1.w, cn[7]);
-        }
-      }
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const __bf16 hi = (__bf16)cn[j];
-        bhi[t][j] = hi;
-        blo[t][j] = (__bf16)(cn[j] - (float)hi);
-      }
-    }
-    u32x4 am[8];
-    transpose8x8(wt, am);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const bf16x8 av = __builtin_bit_cast(bf16x8, am[i]);
-#pragma unroll
-      for (int t = 0; t < NBT; ++t) {
-        acc[i][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bhi[t], acc[i][t], 0, 0, 0);
-        acc[i][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, blo[t], acc[i][t], 0, 0, 0);
-      }
-    }
-    if (more) {
-#pragma unroll
-      for (int j = 0; j < 8; ++j) wt[j] = wn[j];
-    }
-  }
-
-  // ---- sum the 8 waves: obuf[b][j] ---------------------------------------------------------------
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-#pragma unroll
-    for (int t = 0; t < NBT; ++t)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) buf[w][t * 4 + r][lane] = acc[i][t][r];
-    __syncthreads();
-    for (int v = tid; v < NBT * 4 * 64; v += NTHR) {
-      const int reg = v >> 6, ln = v & 63;
-      float sum = 0.f;
-#pragma unroll
-      for (int ww = 0; ww < NW; ++ww) sum += buf[ww][reg][ln];
-      const int t = reg >> 2, r = reg & 3;
-      const int bl = t * 16 + (ln & 15);
-      const int mi = (ln >> 4) * 4 + r;
-      if (mi < lph) obuf[bl][mi * 8 + i] = sum;
-    }
-    __syncthreads();
-  }
-
-  if (a.csw == 1) {
-    const bool bad = a.err && *a.err == (int)a.launch_id;      // the stream kernel gave up waiting
-    for (int v = tid; v < nb * a.d_k; v += NTHR) {
-      const int bl = v / a.d_k, j = v % a.d_k;
-      a.out[(size_t)(bbase + bl) * a.e + h * a.d_k + j] = bad ? NAN : obuf[bl][j];
-    }
-    return;
-  }
-  // ---- several workgroups share the rows of W: last one to arrive adds the partial sums ---------
-  // No cache-wide fences: the partial sums are stored write-through and waited for (so they are
-  // visible device-wide) before this workgroup's arrival is counted, and the last workgroup reads
-  // them with device-coherent loads.
-  for (int v = tid; v < nb * a.d_k; v += NTHR) {
-    const int bl = v / a.d_k, j = v % a.d_k;
-    float* dst = &a.outpart[((size_t)cs * a.B + bbase + bl) * a.e + h * a.d_k + j];
-    asm volatile("global_store_dword %0, %1, off sc0 sc1" : : "v"(dst), "v"(obuf[bl][j]) : "memory");
-  }
+  // ========================= single-launch mode: merge + projection ===============================
+  // This workgroup's partials are out (write-through stores, waited for) before its arrival flag.
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
-  if (tid == 0) {
-    const int old = __hip_atomic_fetch_add(&a.counters[blockIdx.z * a.H + h], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    is_last = (old == a.csw - 1);
-  }
-  __syncthreads();
-  if (!is_last) return;
-  const bool bad = a.err && __hip_atomic_load(a.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (int)a.launch_id;
-  for (int v = tid; v < nb * a.d_k; v += NTHR) {
-    const int bl = v / a.d_k, j = v % a.d_k;
-    float sum = 0.f;
-    for (int s0 = 0; s0 < a.csw; s0 += 8) {
-      float part[8];
-#pragma unroll
-      for (int q = 0; q < 8; ++q) {
-        const int sp = min(s0 + q, a.csw - 1);
-        const float* src = &a.outpart[((size_t)sp * a.B + bbase + bl) * a.e + h * a.d_k + j];
-        asm volatile("global_load_dword %0, %1, off sc1" : "=v"(part[q]) : "v"(src) : "memory");
+  if (tid == 0) st_result(reinterpret_cast<int*>(a.flags) + blockIdx.x, (int)a.launch_id, true);
+  const int wg = blockIdx.x;
+  if (wg >= a.proj.H * a.proj.csw) return;
+  __shared__ ProjShared<1> psm;
+  project_work<1, true>(a.proj, wg / a.proj.csw, wg % a.proj.csw, 0, prefix, psm, [&]() {
+    // every workgroup's partials must be out: all arrival flags carry this launch's id
+    if (wu == 0) {
+      int spins = 0;
+      for (;;) {
+        bool ok = true;
+        for (int i = lane; i < (int)gridDim.x; i += 64)
+          ok = ok && (__hip_atomic_load(a.flags + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == a.launch_id);
+        if (__all(ok)) break;
+        if (dead || ++spins > a.spin_limit) { give_up(); break; }
+        __builtin_amdgcn_s_sleep(4);
       }
-      asm volatile("s_waitcnt vmcnt(0)" : "+v"(part[0]), "+v"(part[1]), "+v"(part[2]), "+v"(part[3]),
-                   "+v"(part[4]), "+v"(part[5]), "+v"(part[6]), "+v"(part[7]) : : "memory");
-#pragma unroll
-      for (int q = 0; q < 8; ++q) if (s0 + q < a.csw) sum += part[q];
     }
-    a.out[(size_t)(bbase + bl) * a.e + h * a.d_k + j] = bad ? NAN : sum;    // NaN: the stream kernel gave up waiting
-  }
-  if (tid == 0) a.counters[blockIdx.z * a.H + h] = 0;
+    __syncthreads();
+  });
 }
 
 // Records which XCD each workgroup of a 256-workgroup launch runs on.
@@ -824,19 +917,23 @@ void launch_fused_stream(const FusedGeom& g, const FusedArgs& a, hipStream_t st)
 }
 
 int proj_row_splits(int H, int rows, int B) {
-  // one 32-row tile of W per wave (8 waves = 256 rows per workgroup) unless that makes too many
-  // workgroups; everything a wave needs is then in flight from its first instruction
+  // one 32-row tile of W per wave (8 waves = 256 rows per workgroup) unless that makes more
+  // workgroups than CUs
   const int zb = (B + 63) / 64;
   int csw = (rows + 8 * TILE_ROWS - 1) / (8 * TILE_ROWS);
-  const int cap = (1024 + H * zb - 1) / (H * zb);
+  const int cap = (256 + H * zb - 1) / (H * zb);      // one workgroup per CU: a single round
   if (csw > cap) csw = cap;
   if (csw < 1) csw = 1;
   return csw;
 }
 
+int proj_rows_per_split(int rows, int csw) {
+  return ((rows + csw - 1) / csw + TILE_ROWS - 1) / TILE_ROWS * TILE_ROWS;
+}
+
 void launch_project_mfma(ProjArgs a, hipStream_t st) {
   const int nbt = a.B <= 16 ? 1 : (a.B <= 32 ? 2 : 4);
-  a.crows = ((a.rows + a.csw - 1) / a.csw + TILE_ROWS - 1) / TILE_ROWS * TILE_ROWS;
+  a.crows = proj_rows_per_split(a.rows, a.csw);
   dim3 grid(a.H, a.csw, (a.B + 16 * nbt - 1) / (16 * nbt)), block(512);
   if (nbt == 1) hipLaunchKernelGGL(project_mfma_kernel<1>, grid, block, 0, st, a);
   else if (nbt == 2) hipLaunchKernelGGL(project_mfma_kernel<2>, grid, block, 0, st, a);

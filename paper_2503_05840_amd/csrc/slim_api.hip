@@ -25,7 +25,8 @@ struct Plan {
   size_t off_exch = 0, off_outpart = 0, off_ctrl = 0;   // bf16 fast path
   bool fused_ok = false;
   FusedGeom geom{};
-  int csw = 1;         // row splits of W_KV in the MFMA projection
+  int csw = 1;         // row splits of W_KV in the MFMA projection (its own launch)
+  int csw_f = 0;       // same, when the stream kernel's workgroups do the projection (0: not possible)
   size_t total = 0;
 };
 
@@ -45,6 +46,10 @@ Plan make_plan(int B, int H, int T, int width, int e) {
   size_t nparts = (size_t)B * p.nsplit;
   if (p.fused_ok && (size_t)p.geom.nparts > nparts) nparts = p.geom.nparts;
   p.csw = proj_row_splits(H, width, B);
+  if (p.fused_ok && B <= 16 && p.geom.grid >= H) {
+    const int tiles_w = (width + TILE_ROWS - 1) / TILE_ROWS;
+    p.csw_f = p.geom.grid / H < tiles_w ? p.geom.grid / H : tiles_w;
+  }
   p.off_S = o;      o += up(sizeof(float) * (size_t)B * H * T);
   p.off_Cpart = o;  o += up(sizeof(float) * nparts * H * width);
   p.off_m = o;      o += up(sizeof(float) * nparts * H);
@@ -55,7 +60,7 @@ Plan make_plan(int B, int H, int T, int width, int e) {
   p.off_vm = o;     o += up(sizeof(float) * (size_t)B * p.nsplit_v * H);
   p.off_vl = o;     o += up(sizeof(float) * (size_t)B * p.nsplit_v * H);
   if (p.fused_ok) { p.off_exch = o; o += up(fused_exch_bytes(p.geom)); }
-  p.off_outpart = o; o += up(sizeof(float) * (size_t)p.csw * B * e);
+  p.off_outpart = o; o += up(sizeof(float) * (size_t)(p.csw > p.csw_f ? p.csw : p.csw_f) * B * e);
   p.off_ctrl = o;    o += up(sizeof(int) * CTRL_INTS);
   p.total = o;
   return p;
@@ -157,7 +162,8 @@ int pick_variant(int requested, int B, int H, int T, int d, int dtype) {
   if (requested == SLIM_VARIANT_GENERIC) return SLIM_VARIANT_GENERIC;
   FusedGeom g;
   const int zb = (B + 63) / 64;
-  if (dtype == SLIM_BF16 && fused_geometry(B, H, T, d, &g) && H * zb < CTRL_INTS) return SLIM_VARIANT_FUSED;
+  if (dtype == SLIM_BF16 && fused_geometry(B, H, T, d, &g) && H * zb < CTRL_INTS / 2 && g.grid <= CTRL_INTS / 2 - 1)
+    return requested == SLIM_VARIANT_FUSED_SPLIT ? SLIM_VARIANT_FUSED_SPLIT : SLIM_VARIANT_FUSED;
   return SLIM_VARIANT_GENERIC;
 }
 
@@ -202,7 +208,7 @@ extern "C" int slim_decode(const void* q, const void* Kcache, const void* W_KV, 
 
   StageTimer tm(o, st);
   const int variant = pick_variant(o ? o->variant : SLIM_VARIANT_AUTO, B, H, T, d, dtype);
-  if (variant == SLIM_VARIANT_FUSED) {
+  if (variant == SLIM_VARIANT_FUSED || variant == SLIM_VARIANT_FUSED_SPLIT) {
     const FusedGeom& g = p.geom;
     int* ctrl = (int*)(ws + p.off_ctrl);
     const int zb = (B + 63) / 64;
@@ -225,16 +231,25 @@ extern "C" int slim_decode(const void* q, const void* Kcache, const void* W_KV, 
     }
     fa.Cpart = Cpart; fa.mpart = mpart; fa.lpart = lpart;
     fa.err = ctrl + CTRL_INTS - 1; fa.counters = ctrl; fa.ncounters = H * zb;
-    launch_fused_stream(g, fa, st);
-    tm.mark();
     ProjArgs pa{};
     pa.Cpart = Cpart; pa.mpart = mpart; pa.lpart = lpart; pa.W = (const uint16_t*)W_KV;
     pa.out = (float*)out; pa.outpart = (float*)(ws + p.off_outpart); pa.counters = ctrl;
     pa.err = ctrl + CTRL_INTS - 1; pa.launch_id = lid; pa.seq_lens = lens;
     pa.B = B; pa.T = T; pa.H = H; pa.d_k = d_k; pa.rows = d; pa.e = d;
     pa.NG = g.NG; pa.nsplit = 0; pa.mode = 0; pa.mscale = 1.0f; pa.csw = p.csw;
-    launch_project_mfma(pa, st);
+    const bool one_launch = variant == SLIM_VARIANT_FUSED && p.csw_f > 0;
+    if (one_launch) {
+      // the stream kernel's workgroups also merge and project (flags after the counters)
+      pa.csw = p.csw_f;
+      pa.crows = proj_rows_per_split(d, p.csw_f);
+      fa.fuse = 1; fa.flags = (unsigned*)(ctrl + CTRL_INTS / 2); fa.proj = pa;
+    }
+    launch_fused_stream(g, fa, st);
     tm.mark();
+    if (!one_launch) {
+      launch_project_mfma(pa, st);
+      tm.mark();
+    }
     tm.finish();
     return launch_status();
   }

@@ -60,6 +60,18 @@ struct FusedGeom {
   int NT, NP, grid, nparts;   // MFMA head tiles, wave pairs per workgroup
 };
 
+struct ProjArgs {
+  const float* Cpart; const float* mpart; const float* lpart;
+  const uint16_t* W;                  // [rows][e] bf16
+  float* out; float* outpart;         // [B][e], [csw][B][e]
+  int* counters; const int* err; unsigned launch_id;
+  const int32_t* seq_lens;
+  int B, T, H, d_k, rows, e;
+  int NG, nsplit, mode;               // mode 0: partials laid out by the stream kernel; 1: [b][nsplit]
+  float mscale;                       // 1 for log2-domain maxima, log2(e) for natural-log ones
+  int csw, crows;                     // row splits of W across workgroups, rows per split
+};
+
 struct FusedArgs {
   const float* q;
   const uint16_t* K;
@@ -78,25 +90,20 @@ struct FusedArgs {
   int* counters;                      // arrival counters of the projection, zeroed here
   int ncounters;
   int xcd_local;                      // 1: a group's workgroups share an XCD, the exchange stays in its L2
+  // Single-launch mode: once all workgroups have written their partials (arrival flags, tagged
+  // with launch_id), each takes a (head, row split) share of the merge + projection.
+  int fuse;
+  unsigned* flags;                    // [grid]
+  ProjArgs proj;                      // csw * H <= grid, B <= 16
 };
 
-struct ProjArgs {
-  const float* Cpart; const float* mpart; const float* lpart;
-  const uint16_t* W;                  // [rows][e] bf16
-  float* out; float* outpart;         // [B][e], [csw][B][e]
-  int* counters; const int* err; unsigned launch_id;
-  const int32_t* seq_lens;
-  int B, T, H, d_k, rows, e;
-  int NG, nsplit, mode;               // mode 0: partials laid out by the stream kernel; 1: [b][nsplit]
-  float mscale;                       // 1 for log2-domain maxima, log2(e) for natural-log ones
-  int csw, crows;                     // row splits of W across workgroups, rows per split
-};
 
 bool fused_geometry(int B, int H, int T, int d, FusedGeom* g);
 size_t fused_exch_bytes(const FusedGeom& g);
 bool xcd_round_robin(int device);
 void launch_fused_stream(const FusedGeom& g, const FusedArgs& a, hipStream_t st);
 int proj_row_splits(int H, int rows, int B);
+int proj_rows_per_split(int rows, int csw);
 void launch_project_mfma(ProjArgs a, hipStream_t st);
 
 }  // namespace slim

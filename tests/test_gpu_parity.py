@@ -25,7 +25,8 @@ SMALL = {
     "two-heads-per-unit-multi-tile": synth.scaled(C[3], B=3, H=32, d=2048, T=5000, len_lo=3000),
     "dk96-multi-tile": synth.scaled(C[2], B=2, T=9000, len_lo=4000),
 }
-VARIANTS = {"auto": binding.VARIANT_AUTO, "generic": binding.VARIANT_GENERIC, "fused": binding.VARIANT_FUSED}
+VARIANTS = {"auto": binding.VARIANT_AUTO, "generic": binding.VARIANT_GENERIC, "fused": binding.VARIANT_FUSED,
+            "fused_split": binding.VARIANT_FUSED_SPLIT}
 
 
 @pytest.fixture(scope="module")
