@@ -157,7 +157,6 @@ template <int NBT>
 struct ProjShared {
   int pid0s[16 * NBT], nps[16 * NBT];
   float wpid[16 * NBT][PROJ_MAX_PARTS];
-  float buf[8][NBT * 4][64];
   float obuf[16 * NBT][128];
   int is_last;
 };
@@ -173,11 +172,12 @@ __device__ __forceinline__ int ld_err(const int* p) {
   else return *p;
 }
 
+// `red`: 64 KB of LDS for the cross-wave sum.
 // `after_w_issue` runs (all threads) once the first tile of W is in flight and before any partial
 // is read: the place to build the tile prefix, or to wait for the other workgroups' partials.
 template <int NBT, bool COH, class Hook>
 __device__ __forceinline__ void project_work(const ProjArgs& a, int h, int cs, int bz, const int* prefix,
-                                             ProjShared<NBT>& sm, Hook&& after_w_issue) {
+                                             ProjShared<NBT>& sm, float* red, Hook&& after_w_issue) {
   const int bbase = bz * 16 * NBT;
   const int nb = min(16 * NBT, a.B - bbase);
   constexpr int NW = 8, NTHR = 512;
@@ -257,11 +257,11 @@ __device__ __forceinline__ void project_work(const ProjArgs& a, int h, int cs, i
       if (bl < nb && c < c_hi) {
         const int p0 = sm.pid0s[bl], np = sm.nps[bl];
         if constexpr (COH) {
-          // four partials per round trip: agent-scope loads, one wait
-          for (int pb = 0; pb < np; pb += 4) {
-            f32x4 x[4][2];
+          // eight partials per round trip: agent-scope loads, one wait
+          for (int pb = 0; pb < np; pb += 8) {
+            f32x4 x[8][2];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
+            for (int q = 0; q < 8; ++q) {
               const int pp = min(pb + q, np - 1);
               const float* src = a.Cpart + ((size_t)(p0 + pp) * a.H + h) * a.rows + c;
               asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(x[q][0]) : "v"(src) : "memory");
@@ -269,8 +269,10 @@ __device__ __forceinline__ void project_work(const ProjArgs& a, int h, int cs, i
             }
             asm volatile("s_waitcnt vmcnt(0)" : "+v"(x[0][0]), "+v"(x[0][1]), "+v"(x[1][0]), "+v"(x[1][1]),
                          "+v"(x[2][0]), "+v"(x[2][1]), "+v"(x[3][0]), "+v"(x[3][1]) : : "memory");
+            asm volatile("" : "+v"(x[4][0]), "+v"(x[4][1]), "+v"(x[5][0]), "+v"(x[5][1]),
+                         "+v"(x[6][0]), "+v"(x[6][1]), "+v"(x[7][0]), "+v"(x[7][1]) : : "memory");
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
+            for (int q = 0; q < 8; ++q) {
               const float wgt = (pb + q < np) ? sm.wpid[bl][min(pb + q, np - 1)] : 0.f;
 #pragma unroll
               for (int j = 0; j < 4; ++j) {
@@ -317,23 +319,26 @@ __device__ __forceinline__ void project_work(const ProjArgs& a, int h, int cs, i
     }
   }
 
-  // ---- sum the 8 waves: sm.obuf[b][j] ---------------------------------------------------------------
+  // ---- sum the 8 waves: sm.obuf[b][j], IPR of the 8 accumulator columns per pass through LDS -----
+  constexpr int IPR = 8 / NBT;
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
+  for (int i0 = 0; i0 < 8; i0 += IPR) {
 #pragma unroll
-    for (int t = 0; t < NBT; ++t)
+    for (int ii = 0; ii < IPR; ++ii)
 #pragma unroll
-      for (int r = 0; r < 4; ++r) sm.buf[w][t * 4 + r][lane] = acc[i][t][r];
+      for (int t = 0; t < NBT; ++t)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) red[((w * IPR + ii) * (NBT * 4) + t * 4 + r) * 64 + lane] = acc[i0 + ii][t][r];
     __syncthreads();
-    for (int v = tid; v < NBT * 4 * 64; v += NTHR) {
-      const int reg = v >> 6, ln = v & 63;
+    for (int v = tid; v < IPR * NBT * 4 * 64; v += NTHR) {
+      const int ln = v & 63, reg = (v >> 6) % (NBT * 4), ii = (v >> 6) / (NBT * 4);
       float sum = 0.f;
 #pragma unroll
-      for (int ww = 0; ww < NW; ++ww) sum += sm.buf[ww][reg][ln];
+      for (int ww = 0; ww < NW; ++ww) sum += red[((ww * IPR + ii) * (NBT * 4) + reg) * 64 + ln];
       const int t = reg >> 2, r = reg & 3;
       const int bl = t * 16 + (ln & 15);
       const int mi = (ln >> 4) * 4 + r;
-      if (mi < lph) sm.obuf[bl][mi * 8 + i] = sum;
+      if (mi < lph) sm.obuf[bl][mi * 8 + i0 + ii] = sum;
     }
     __syncthreads();
   }
@@ -389,7 +394,8 @@ template <int NBT>
 __global__ __launch_bounds__(512) void project_mfma_kernel(const ProjArgs a) {
   __shared__ int prefix[FUSED_MAX_B + 1];
   __shared__ ProjShared<NBT> sm;
-  project_work<NBT, false>(a, blockIdx.x, blockIdx.y, blockIdx.z, prefix, sm, [&]() {
+  __shared__ float red[8 * 8 * 4 * 64];
+  project_work<NBT, false>(a, blockIdx.x, blockIdx.y, blockIdx.z, prefix, sm, red, [&]() {
     if (a.mode == 0) build_tile_prefix(prefix, a.seq_lens, a.B, a.T);
   });
 }
@@ -824,7 +830,8 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
   const int wg = blockIdx.x;
   if (wg >= a.proj.H * a.proj.csw) return;
   __shared__ ProjShared<1> psm;
-  project_work<1, true>(a.proj, wg / a.proj.csw, wg % a.proj.csw, 0, prefix, psm, [&]() {
+  // (the tile slots are idle by now: they serve the projection's cross-wave sum)
+  project_work<1, true>(a.proj, wg / a.proj.csw, wg % a.proj.csw, 0, prefix, psm, sbuf, [&]() {
     // every workgroup's partials must be out: all arrival flags carry this launch's id
     if (wu == 0) {
       int spins = 0;
@@ -916,10 +923,21 @@ void launch_fused_stream(const FusedGeom& g, const FusedArgs& a, hipStream_t st)
   else hipLaunchKernelGGL(fused_stream_kernel<2>, grid, block, 0, st, a);
 }
 
-int proj_row_splits(int H, int rows, int B) {
+// Sequences per workgroup of the projection, in MFMA N tiles of 16 (1, 2 or 4).  One tile keeps the
+// kernel out of register spills and gives more workgroups; it costs one more pass over W_KV per 16
+// sequences, which is only worth it while those passes stay small.
+int proj_batch_tiles(int B, int rows, int e) {
+  if (B <= 16) return 1;
+  const long w_bytes = (long)rows * e * 2, chunks = (B + 15) / 16;
+  if (w_bytes * chunks <= (64L << 20)) return 1;
+  return B <= 32 ? 2 : 4;
+}
+
+int proj_row_splits(int H, int rows, int e, int B) {
   // one 32-row tile of W per wave (8 waves = 256 rows per workgroup) unless that makes more
   // workgroups than CUs
-  const int zb = (B + 63) / 64;
+  const int per = 16 * proj_batch_tiles(B, rows, e);
+  const int zb = (B + per - 1) / per;
   int csw = (rows + 8 * TILE_ROWS - 1) / (8 * TILE_ROWS);
   const int cap = (256 + H * zb - 1) / (H * zb);      // one workgroup per CU: a single round
   if (csw > cap) csw = cap;
@@ -932,7 +950,7 @@ int proj_rows_per_split(int rows, int csw) {
 }
 
 void launch_project_mfma(ProjArgs a, hipStream_t st) {
-  const int nbt = a.B <= 16 ? 1 : (a.B <= 32 ? 2 : 4);
+  const int nbt = proj_batch_tiles(a.B, a.rows, a.e);
   a.crows = proj_rows_per_split(a.rows, a.csw);
   dim3 grid(a.H, a.csw, (a.B + 16 * nbt - 1) / (16 * nbt)), block(512);
   if (nbt == 1) hipLaunchKernelGGL(project_mfma_kernel<1>, grid, block, 0, st, a);

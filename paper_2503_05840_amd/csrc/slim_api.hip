@@ -45,7 +45,7 @@ Plan make_plan(int B, int H, int T, int width, int e) {
   p.fused_ok = (width == e) && fused_geometry(B, H, T, width, &p.geom);
   size_t nparts = (size_t)B * p.nsplit;
   if (p.fused_ok && (size_t)p.geom.nparts > nparts) nparts = p.geom.nparts;
-  p.csw = proj_row_splits(H, width, B);
+  p.csw = proj_row_splits(H, width, e, B);
   if (p.fused_ok && B <= 16 && p.geom.grid >= H) {
     const int tiles_w = (width + TILE_ROWS - 1) / TILE_ROWS;
     p.csw_f = p.geom.grid / H < tiles_w ? p.geom.grid / H : tiles_w;
@@ -161,7 +161,7 @@ extern "C" const char* slim_strerror(int code) {
 int pick_variant(int requested, int B, int H, int T, int d, int dtype) {
   if (requested == SLIM_VARIANT_GENERIC) return SLIM_VARIANT_GENERIC;
   FusedGeom g;
-  const int zb = (B + 63) / 64;
+  const int zb = (B + 15) / 16;                      // upper bound of the projection's batch chunks
   if (dtype == SLIM_BF16 && fused_geometry(B, H, T, d, &g) && H * zb < CTRL_INTS / 2 && g.grid <= CTRL_INTS / 2 - 1)
     return requested == SLIM_VARIANT_FUSED_SPLIT ? SLIM_VARIANT_FUSED_SPLIT : SLIM_VARIANT_FUSED;
   return SLIM_VARIANT_GENERIC;
@@ -211,7 +211,8 @@ extern "C" int slim_decode(const void* q, const void* Kcache, const void* W_KV, 
   if (variant == SLIM_VARIANT_FUSED || variant == SLIM_VARIANT_FUSED_SPLIT) {
     const FusedGeom& g = p.geom;
     int* ctrl = (int*)(ws + p.off_ctrl);
-    const int zb = (B + 63) / 64;
+    const int per = 16 * proj_batch_tiles(B, d, d);
+    const int zb = (B + per - 1) / per;
     FusedArgs fa{};
     fa.q = (const float*)q; fa.K = (const uint16_t*)Kcache; fa.k_bstride = kb; fa.seq_lens = lens;
     fa.T = T; fa.B = B; fa.H = H; fa.d = d; fa.d_k = d_k;

@@ -102,7 +102,8 @@ bool fused_geometry(int B, int H, int T, int d, FusedGeom* g);
 size_t fused_exch_bytes(const FusedGeom& g);
 bool xcd_round_robin(int device);
 void launch_fused_stream(const FusedGeom& g, const FusedArgs& a, hipStream_t st);
-int proj_row_splits(int H, int rows, int B);
+int proj_batch_tiles(int B, int rows, int e);
+int proj_row_splits(int H, int rows, int e, int B);
 int proj_rows_per_split(int rows, int csw);
 void launch_project_mfma(ProjArgs a, hipStream_t st);
 
