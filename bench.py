@@ -52,12 +52,106 @@ def measured_traffic(config_index, kernel):
     return None
 
 
+def timed(torch, fn, steps, warmup):
+    for i in range(warmup):
+        fn(i)
+    torch.cuda.synchronize()
+    t = time.perf_counter()
+    for i in range(steps):
+        fn(i)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t) * 1e3 / steps
+
+
+XCACHE_STAGES = ["q_tilde (head_scores on W_K)", "dense_scores", "weighted_sum", "combine", "project"]
+XCACHE_MFMA_STAGES = ["xq_tilde", "xscores", "xweighted", "project_mfma"]
+
+
+def bench_xcache(args, cfg, torch, binding, synth):
+    """configs[4]: the X-cache scheme for projection width e > d_model (absorbed form)."""
+    B, H, T, dm, d_k, e = cfg.B, cfg.H, cfg.T, cfg.d, cfg.d_k, cfg.e
+    log(f"[bench] building inputs for config {cfg.index} ({cfg.name}) ...")
+    p = synth.make_problem(cfg)
+    Xh = np.stack([synth.to_storage(sq.X, cfg.dtype) for sq in p.seqs])
+    to_device = binding.to_device
+    ncopies = args.copies or max(2, int(np.ceil(512e6 / Xh.nbytes)) + 1)
+    Xs = [to_device(Xh) for _ in range(ncopies)]
+    q = to_device(p.q.astype(np.float32))
+    Wk = to_device(binding.slim_pack_weights(p.w.W_K, cfg.dtype))
+    Wv = to_device(binding.slim_pack_weights(p.w.W_V, cfg.dtype))
+    out = torch.zeros((B, e), device="cuda", dtype=torch.float32)
+
+    def slim(i, **extra):
+        binding.slim_decode_xcache(q, Xs[i % ncopies], Wk, Wv, out, B, H, T, dm, d_k, dtype=cfg.dtype, **extra)
+
+    log("[bench] timing slim_decode_xcache ...")
+    ms = timed(torch, slim, args.steps, args.warmup)
+    # the same-GPU comparison reads e-wide K and V caches (random values: only the traffic matters)
+    Kr = torch.randn((B, T, e), device="cuda").to(torch.bfloat16)
+    Vr = torch.randn((B, T, e), device="cuda").to(torch.bfloat16)
+    out_v = torch.zeros_like(out)
+    log("[bench] timing vanilla_kv_decode on e-wide K and V ...")
+    ms_van = timed(torch, lambda i: binding.vanilla_kv_decode(q, Kr, Vr, out_v, B, H, T, e, dtype=cfg.dtype),
+                   max(5, args.steps // 10), 3)
+    del Kr, Vr
+    stage = binding.new_stage_buffer()
+    acc = np.zeros(binding.MAX_STAGES)
+    for i in range(args.steps):
+        slim(i, stage_ms=stage)
+        acc += np.array(list(stage))
+    acc /= args.steps
+    mfma_path = acc[4] == 0.0                      # four launches: the bf16 MFMA kernels; five: the plain ones
+    names = XCACHE_MFMA_STAGES if mfma_path else XCACHE_STAGES
+    dom = int(np.argmax(acc[:len(names)]))
+    # dense contractions over all heads: priced against the bf16 MFMA peak with the method's own
+    # flop counts (the hi + lo split of q~ doubles the MFMA work of the scores; not counted)
+    dense = 2.0 * B * H * T * dm
+    flops = {"xscores": dense, "xweighted": dense, "dense_scores": dense, "weighted_sum": dense}.get(names[dom], 2.0 * B * dm * e)
+    achieved = flops / (acc[dom] * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": names[dom], "achieved": round(achieved, 2), "peak": 2500.0, "unit": "TFLOP/s",
+                "frac": round(achieved / 2500.0, 5), "traffic": None, "kernel_ms": round(float(acc[dom]), 5),
+                "algorithmic_flops": flops,
+                "stage_ms": {n: round(float(acc[i]), 5) for i, n in enumerate(names)}}
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import mha_oracle as orc
+        log("[bench] timing the CPU oracle on sequence 0 (builds the e-wide K and V, then the decode step) ...")
+        t0, c0 = time.perf_counter(), os.times()
+        ref0 = orc.vanilla_decode_from_x(p.q[0], p.seqs[0].X, p.w.W_K, p.w.W_V, H)
+        wall = time.perf_counter() - t0
+        c1 = os.times()
+        busy = (c1.user - c0.user) + (c1.system - c0.system)
+        slim(0)
+        torch.cuda.synchronize()
+        got0 = out[0].cpu().numpy().astype(np.float64).reshape(H, d_k)
+        r0 = ref0.reshape(H, d_k)
+        err = float((np.abs(got0 - r0).max(axis=1) / np.abs(r0).max(axis=1)).max())
+        cpu = {"value": round(1.0 / wall, 4), "unit": "tokens/s", "cores": max(1, int(round(busy / wall))), "kind": "oracle",
+               "host_cores": os.cpu_count(),
+               "sample": f"sequence 0 of config {cfg.index} ({T} rows x {dm}), one fp64 evaluation including K = X W_K, V = X W_V (e = {e})",
+               "gpu_max_rel_err_vs_oracle_seq0": float(f"{err:.3e}")}
+    x_bytes = float(B) * T * dm * 2
+    result = {
+        "metric": "decode tokens/s (one attention layer step, X-cache, e > d_model), 1 GPU",
+        "value": round(B / (ms * 1e-3), 2), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms, 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"configs[{cfg.index}] {cfg.name}", "B": B, "H": H, "d_model": dm, "d_k": d_k, "e": e, "T": T,
+                   "x_cache_copies_rotated": ncopies},
+        "x_cache_gbps": round(x_bytes / (ms * 1e-3) / 1e9, 1),
+        "algorithmic_bytes_gbps": round((x_bytes + 2.0 * dm * e * 2) / (ms * 1e-3) / 1e9, 1),
+        "vanilla_kv_ms_per_step": round(ms_van, 5), "speedup_vs_vanilla_kv": round(ms_van / ms, 3),
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    print(json.dumps(result), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", type=int, default=1, choices=[0, 1, 2, 3])
+    ap.add_argument("--config", type=int, default=1, choices=[0, 1, 2, 3, 4])
     ap.add_argument("--variant", default="auto", choices=["auto", "generic", "fused", "fused_split"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copies", type=int, default=0, help="K-cache copies to rotate over (0 = enough to exceed 512 MB)")
@@ -74,6 +168,8 @@ def main():
         sys.exit("bench.py: no GPU visible")
     binding.load()
     cfg = synth.CONFIGS[args.config]
+    if cfg.kind == "xcache":
+        return bench_xcache(args, cfg, torch, binding, synth)
     B, H, T, d, d_k = cfg.B, cfg.H, cfg.T, cfg.d, cfg.d_k
     es = 2 if cfg.dtype == "bf16" else 4
     log(f"[bench] building inputs for config {cfg.index} ({cfg.name}) ...")

@@ -102,8 +102,10 @@ typedef struct slim_opts {
  * (one of the SLIM_VARIANT_* values above, never AUTO); 0 on invalid arguments. */
 int slim_variant_for(int B, int H, int T, int d, int dtype);
 
-/* Upper bound of the device scratch any decode call below needs for this shape. */
+/* Upper bound of the device scratch slim_decode / vanilla_kv_decode need for this shape. */
 size_t slim_workspace_bytes(int B, int H, int T, int d, int dtype);
+/* The same for slim_decode_xcache (projection width H*d_k, cache width d_model). */
+size_t slim_workspace_bytes_xcache(int B, int H, int T, int d_model, int d_k, int dtype);
 
 /* ---- the decode step ------------------------------------------------------------------- */
 

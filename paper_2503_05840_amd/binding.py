@@ -19,7 +19,7 @@ SLIM_F32, SLIM_BF16 = 0, 1
 VARIANT_AUTO, VARIANT_GENERIC, VARIANT_FUSED_SPLIT, VARIANT_FUSED = 0, 1, 2, 3
 DTYPES = {"f32": SLIM_F32, "bf16": SLIM_BF16}
 
-EXPORTS = ("slim_strerror", "slim_prepare_wkv", "slim_pack_weights", "slim_workspace_bytes",
+EXPORTS = ("slim_strerror", "slim_prepare_wkv", "slim_pack_weights", "slim_workspace_bytes", "slim_workspace_bytes_xcache",
            "slim_variant_for", "slim_decode", "vanilla_kv_decode", "slim_decode_xcache")
 VARIANT_NAMES = {1: "generic", 2: "fused_split", 3: "fused"}
 
@@ -70,6 +70,8 @@ def load():
     lib.slim_pack_weights.argtypes = [vp, vp, ci, ci, ci]
     lib.slim_workspace_bytes.restype = ctypes.c_size_t
     lib.slim_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
+    lib.slim_workspace_bytes_xcache.restype = ctypes.c_size_t
+    lib.slim_workspace_bytes_xcache.argtypes = [ci, ci, ci, ci, ci, ci]
     lib.slim_variant_for.restype = ci
     lib.slim_variant_for.argtypes = [ci, ci, ci, ci, ci]
     op = ctypes.POINTER(SlimOpts)
@@ -116,6 +118,10 @@ def slim_pack_weights(W: np.ndarray, dtype: str) -> np.ndarray:
 
 def slim_workspace_bytes(B, H, T, d, dtype: str) -> int:
     return int(load().slim_workspace_bytes(B, H, T, d, DTYPES[dtype]))
+
+
+def slim_workspace_bytes_xcache(B, H, T, d_model, d_k, dtype: str) -> int:
+    return int(load().slim_workspace_bytes_xcache(B, H, T, d_model, d_k, DTYPES[dtype]))
 
 
 def auto_variant_name(B, H, T, d, dtype: str) -> str:

@@ -20,6 +20,7 @@ inline size_t up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
 struct Plan {
   int nsplit = 1;      // context splits of the weighted-sum step
   int nsplit_v = 1;    // context splits of the vanilla kernel
+  int nsplit_x = 1;    // context splits of the X-cache MFMA path
   size_t off_S = 0, off_Cpart = 0, off_m = 0, off_l = 0, off_Cn = 0, off_qt = 0;
   size_t off_vacc = 0, off_vm = 0, off_vl = 0;
   size_t off_exch = 0, off_outpart = 0, off_ctrl = 0;   // bf16 fast path
@@ -43,7 +44,8 @@ Plan make_plan(int B, int H, int T, int width, int e) {
   p.nsplit_v = clampi((int)((1024 + per_split_v - 1) / per_split_v), 1, clampi((T + 127) / 128, 1, 256));
   size_t o = 0;
   p.fused_ok = (width == e) && fused_geometry(B, H, T, width, &p.geom);
-  size_t nparts = (size_t)B * p.nsplit;
+  p.nsplit_x = xcache_splits(B, H, T, width);
+  size_t nparts = (size_t)B * (p.nsplit > p.nsplit_x ? p.nsplit : p.nsplit_x);
   if (p.fused_ok && (size_t)p.geom.nparts > nparts) nparts = p.geom.nparts;
   p.csw = proj_row_splits(H, width, e, B);
   if (p.fused_ok && B <= 16 && p.geom.grid >= H) {
@@ -185,6 +187,12 @@ extern "C" size_t slim_workspace_bytes(int B, int H, int T, int d, int dtype) {
   return make_plan(B, H, T, d, d).total;
 }
 
+extern "C" size_t slim_workspace_bytes_xcache(int B, int H, int T, int d_model, int d_k, int dtype) {
+  if (B < 1 || H < 1 || T < 1 || d_model < 1 || d_k < 1) return 0;
+  (void)dtype;
+  return make_plan(B, H, T, d_model, H * d_k).total;
+}
+
 extern "C" int slim_decode(const void* q, const void* Kcache, const void* W_KV, void* out, int B,
                            int H, int T, int d, const slim_opts* o) {
   if (!q || !Kcache || !W_KV || !out) return SLIM_ERR_ARG;
@@ -299,7 +307,7 @@ extern "C" int slim_decode_xcache(const void* q, const void* X, const void* W_K,
   if (int rc = check_common(B, H, T, e, d_k, d_model, o, &dtype, &t_stride)) return rc;
   if (misaligned(q) || misaligned(X) || misaligned(W_K) || misaligned(W_V) || misaligned(out))
     return SLIM_ERR_ALIGN;
-  const Plan p = make_plan(B, H, T, d_model, d_model);
+  const Plan p = make_plan(B, H, T, d_model, e);
   char* ws;
   if (int rc = get_workspace(o, p.total, &ws)) return rc;
   hipStream_t st = o ? (hipStream_t)o->stream : nullptr;
@@ -313,8 +321,32 @@ extern "C" int slim_decode_xcache(const void* q, const void* X, const void* W_K,
   float* qt = (float*)(ws + p.off_qt);
   const long xb = t_stride * d_model;
 
-  // qt[b][h][c] = sum_j q[b][h d_k + j] W_K[c][h d_k + j]   ("rows" of W_K scored against q)
   StageTimer tm(o, st);
+  const int req = o ? o->variant : SLIM_VARIANT_AUTO;
+  if (req != SLIM_VARIANT_GENERIC && xcache_fast_ok(dtype, H, d_model, d_k) && H < CTRL_INTS / 2) {
+    // MFMA path: q~, scores (log2 domain), weighted sum per context split, merge + projection
+    int* ctrl = (int*)(ws + p.off_ctrl);
+    const int per = 16 * proj_batch_tiles(B, d_model, e);
+    const int zb = (B + per - 1) / per;
+    launch_xq_tilde((const float*)q, W_K, qt, B, H, d_k, d_model, e, ctrl, H * zb, st);
+    tm.mark();
+    launch_xscores(qt, X, xb, lens, T, H, d_model, scale * 1.4426950408889634f, S, B, st);
+    tm.mark();
+    launch_xweighted(S, X, xb, lens, T, H, d_model, p.nsplit_x, Cpart, mpart, lpart, B, st);
+    tm.mark();
+    ProjArgs pa{};
+    pa.Cpart = Cpart; pa.mpart = mpart; pa.lpart = lpart; pa.W = (const uint16_t*)W_V;
+    pa.out = (float*)out; pa.outpart = (float*)(ws + p.off_outpart); pa.counters = ctrl;
+    pa.err = nullptr; pa.launch_id = 0; pa.seq_lens = lens;
+    pa.B = B; pa.T = T; pa.H = H; pa.d_k = d_k; pa.rows = d_model; pa.e = e;
+    pa.NG = 0; pa.nsplit = p.nsplit_x; pa.mode = 1; pa.mscale = 1.0f;
+    pa.csw = proj_row_splits(H, d_model, e, B);
+    launch_project_mfma(pa, st);
+    tm.mark();
+    tm.finish();
+    return launch_status();
+  }
+  // qt[b][h][c] = sum_j q[b][h d_k + j] W_K[c][h d_k + j]   ("rows" of W_K scored against q)
   launch_head_scores(dtype, (const float*)q, e, W_K, 0, e, nullptr, d_model, e, H, d_k, 1.0f, qt,
                      (long)H * d_model, B, st);
   tm.mark();

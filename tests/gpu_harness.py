@@ -131,19 +131,22 @@ class KCase:
 class XCase:
     """An X-cache problem (projection width e > d_model) on the device, with its oracle."""
 
-    def __init__(self, cfg: synth.Config, oracle_seqs=None):
+    def __init__(self, cfg: synth.Config, oracle_seqs=None, q_scale: float = 1.0, lens=None):
         self.cfg = cfg
         p = synth.make_problem(cfg)
         self.p = p
         B, T, d = cfg.B, cfg.T, cfg.d
+        self.lens = None if lens is None else np.asarray(lens, dtype=np.int32)
+        q64 = p.q * q_scale
         Xh = np.zeros((B, T, d), dtype=np.uint16 if cfg.dtype == "bf16" else np.float32)
         self.ref = np.full((B, cfg.e), np.nan)
         for b, sq in enumerate(p.seqs):
             Xh[b] = synth.to_storage(sq.X, cfg.dtype)
             if oracle_seqs is None or b in oracle_seqs:
-                self.ref[b] = orc.vanilla_decode_from_x(p.q[b], sq.X, p.w.W_K, p.w.W_V, cfg.H)
+                n = T if self.lens is None else int(self.lens[b])
+                self.ref[b] = orc.vanilla_decode_from_x(q64[b], sq.X[:n], p.w.W_K, p.w.W_V, cfg.H)
         self.oracle_rows = [b for b in range(B) if not np.isnan(self.ref[b]).any()]
-        self.q = to_device(p.q.astype(np.float32))
+        self.q = to_device(q64.astype(np.float32))
         self.X = to_device(Xh)
         self.Wk = to_device(binding.slim_pack_weights(p.w.W_K, cfg.dtype))
         self.Wv = to_device(binding.slim_pack_weights(p.w.W_V, cfg.dtype))
@@ -151,6 +154,9 @@ class XCase:
     def run(self, **kw):
         import torch
         c = self.cfg
+        if self.lens is not None:
+            kw.setdefault("seq_lens", torch.from_numpy(self.lens).cuda())
+            kw.setdefault("seq_lens_host", self.lens)
         out = torch.full((c.B, c.e), float("nan"), device="cuda", dtype=torch.float32)
         binding.slim_decode_xcache(self.q, self.X, self.Wk, self.Wv, out, c.B, c.H, c.T, c.d, c.d_k,
                                    dtype=c.dtype, **kw)
