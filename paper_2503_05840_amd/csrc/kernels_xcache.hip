@@ -54,41 +54,60 @@ __device__ __forceinline__ void transpose8x8(const u32x4 (&kt)[8], u32x4 (&a)[8]
 
 // ------------------------------------------------------------------------------------------------
 // q~[b][h][c] = sum_j q[b][h d_k + j] W_K[c][h d_k + j]
-// grid (H, d_model / 128, batch chunks of 16); a wave owns 16 rows c of W_K for head h.
+// grid (H / XQ_HEADS, d_model / 128, batch chunks of 16); a wave owns 16 rows c of W_K for XQ_HEADS heads.
 // MFMA: A = W_K block (M = 16 rows c, K = the head's columns j), B = q^T (N = sequences) as hi + lo.
 // ------------------------------------------------------------------------------------------------
+constexpr int XQ_HEADS = 4;
+
 __global__ __launch_bounds__(512) void xq_tilde_kernel(const float* q, const uint16_t* Wk, float* qt, int B,
                                                        int H, int d_k, int dm, int e, int* counters, int ncounters) {
   // (the arrival counters of the projection that ends this call start at 0)
   if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0)
     for (int i = threadIdx.x; i < ncounters; i += 512) counters[i] = 0;
-  const int h = blockIdx.x, bbase = blockIdx.z * 16;
+  const int bbase = blockIdx.z * 16;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int n = lane & 15, kq = lane >> 4;
   const int c0 = (blockIdx.y * 8 + w) * 16;
   if (c0 >= dm) return;
   const int b = bbase + n;
-  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-  const uint16_t* wrow = Wk + (size_t)min(c0 + n, dm - 1) * e + (size_t)h * d_k + kq * 8;
-  for (int ks = 0; ks < d_k / 32; ++ks) {
-    const u32x4 av = *reinterpret_cast<const u32x4*>(wrow + ks * 32);
-    float x[8];
+  const int nks = d_k / 32;                            // 1..4 k-steps per head
+  // XQ_HEADS heads per wave: all their loads of W_K are issued before the first MFMA
+  u32x4 av[XQ_HEADS][4];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) x[j] = (b < B) ? q[(size_t)b * e + (size_t)h * d_k + ks * 32 + kq * 8 + j] : 0.f;
-    bf16x8 hi, lo;
-    split_hi_lo(x, hi, lo);
-    const bf16x8 a8 = __builtin_bit_cast(bf16x8, av);
-    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a8, hi, acc, 0, 0, 0);
-    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a8, lo, acc, 0, 0, 0);
+  for (int hh = 0; hh < XQ_HEADS; ++hh) {
+    const int h = min(blockIdx.x * XQ_HEADS + hh, H - 1);
+    const uint16_t* wrow = Wk + (size_t)(c0 + n) * e + (size_t)h * d_k + kq * 8;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) av[hh][ks] = *reinterpret_cast<const u32x4*>(wrow + min(ks, nks - 1) * 32);
   }
-  // D: column n = sequence, rows kq*4 + r = c0 + ...
-  if (b < B) *reinterpret_cast<f32x4*>(qt + ((size_t)b * H + h) * dm + c0 + kq * 4) = acc;
+#pragma unroll
+  for (int hh = 0; hh < XQ_HEADS; ++hh) {
+    const int h = blockIdx.x * XQ_HEADS + hh;
+    if (h >= H) break;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      if (ks >= nks) break;
+      float x[8];
+      const float* qsrc = q + (size_t)min(b, B - 1) * e + (size_t)h * d_k + ks * 32 + kq * 8;
+      const f32x4 lo4 = *reinterpret_cast<const f32x4*>(qsrc), hi4 = *reinterpret_cast<const f32x4*>(qsrc + 4);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) { x[j] = (b < B) ? lo4[j] : 0.f; x[4 + j] = (b < B) ? hi4[j] : 0.f; }
+      bf16x8 hi, lo;
+      split_hi_lo(x, hi, lo);
+      const bf16x8 a8 = __builtin_bit_cast(bf16x8, av[hh][ks]);
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a8, hi, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a8, lo, acc, 0, 0, 0);
+    }
+    // D: column n = sequence, rows kq*4 + r = c0 + ...
+    if (b < B) *reinterpret_cast<f32x4*>(qt + ((size_t)b * H + h) * dm + c0 + kq * 4) = acc;
+  }
 }
 
 // ------------------------------------------------------------------------------------------------
 // s[b][h][t] = scale * sum_c X[b][t][c] q~[b][h][c]       (scale = log2(e) / sqrt(d_k))
-// grid (ceil(T / 128), ceil(H / 32), B).  The workgroup keeps q~ of its 32 heads in LDS as bf16
-// hi + lo (B operands); a wave owns 16 rows of X (A operands straight from global memory).
+// grid (row chunks of nblk x 256, ceil(H / 32), B).  The workgroup keeps q~ of its 32 heads in LDS as bf16
+// hi + lo (B operands); a wave owns 32 rows of X per block (A operands straight from global memory).
 // ------------------------------------------------------------------------------------------------
 constexpr int XS_PAD = 8;   // bf16 elements of padding per q~ row in LDS (spreads the rows over the banks)
 
@@ -101,7 +120,7 @@ __global__ __launch_bounds__(512) void xscores_kernel(const float* qt, const uin
   const int n = lane & 15, kq = lane >> 4;
   const int pitch = dm + XS_PAD;
   const int len = seq_len_of(seq_lens, b, T);
-  const int row_base = blockIdx.x * nblk * 128;       // this workgroup: nblk blocks of 128 rows
+  const int row_base = blockIdx.x * nblk * 256;       // this workgroup: nblk blocks of 256 rows
   if (row_base >= len) return;                        // (workgroup-uniform) nothing to score here
   {
     const int dm8 = dm >> 3;
@@ -127,58 +146,70 @@ __global__ __launch_bounds__(512) void xscores_kernel(const float* qt, const uin
   __syncthreads();
   const int nks = dm / 32;                             // a multiple of 4
   const uint16_t* Xb = X + (size_t)b * x_bstride + kq * 8;
-  // 16 k-steps (512 columns) of A operands per buffer; the other buffer is in flight meanwhile
-  constexpr int KH = 16;
-  u32x4 a0[KH], a1[KH];
-  auto load_half = [&](u32x4 (&a)[KH], int blk, int kbase) {
-    const int t0 = row_base + blk * 128 + w * 16;
-    const uint16_t* xrow = Xb + (size_t)min(t0 + n, len - 1) * dm;
+  // A wave owns 32 rows of a 256-row block (two A operands share every B operand read from LDS);
+  // 8 k-steps (256 columns) of A operands per buffer, the other buffer is in flight meanwhile.
+  constexpr int KH = 8;
+  u32x4 a0[2][KH], a1[2][KH];
+  auto load_part = [&](u32x4 (&a)[2][KH], int blk, int kbase) {
+    const int t0 = row_base + blk * 256 + w * 32;
 #pragma unroll
-    for (int u = 0; u < KH; ++u) a[u] = *reinterpret_cast<const u32x4*>(xrow + min(kbase + u, nks - 1) * 32);
+    for (int rb = 0; rb < 2; ++rb) {
+      const uint16_t* xrow = Xb + (size_t)min(t0 + rb * 16 + n, len - 1) * dm;
+#pragma unroll
+      for (int u = 0; u < KH; ++u) a[rb][u] = *reinterpret_cast<const u32x4*>(xrow + min(kbase + u, nks - 1) * 32);
+    }
   };
-  auto mma_half = [&](const u32x4 (&a)[KH], int kbase, f32x4 (&acc)[2]) {
+  auto mma_part = [&](const u32x4 (&a)[2][KH], int kbase, f32x4 (&acc)[2][2]) {
 #pragma unroll
     for (int u = 0; u < KH; ++u) {
       if (kbase + u >= nks) break;
-      const bf16x8 a8 = __builtin_bit_cast(bf16x8, a[u]);
       const int coff = (kbase + u) * 32 + kq * 8;
 #pragma unroll
       for (int ht = 0; ht < 2; ++ht) {
         const bf16x8 bh = *reinterpret_cast<const bf16x8*>(&qs[(ht * 16 + n) * pitch + coff]);
         const bf16x8 bl = *reinterpret_cast<const bf16x8*>(&qs[(32 + ht * 16 + n) * pitch + coff]);
-        acc[ht] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a8, bh, acc[ht], 0, 0, 0);
-        acc[ht] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a8, bl, acc[ht], 0, 0, 0);
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) {
+          const bf16x8 a8 = __builtin_bit_cast(bf16x8, a[rb][u]);
+          acc[rb][ht] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a8, bh, acc[rb][ht], 0, 0, 0);
+          acc[rb][ht] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a8, bl, acc[rb][ht], 0, 0, 0);
+        }
       }
     }
   };
-  const int nhalf = (nks + KH - 1) / KH;               // halves per block
-  const int nb_here = min(nblk, (len - row_base + 127) / 128);
-  const int total = nb_here * nhalf;                   // halves this wave goes through
-  load_half(a0, 0, 0);
-  f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
-  for (int i = 0; i < total; i += 2) {
-    // even half in a0, odd half in a1
-    if (i + 1 < total) load_half(a1, (i + 1) / nhalf, ((i + 1) % nhalf) * KH);
-    mma_half(a0, (i % nhalf) * KH, acc);
-    auto flush = [&](int half_index) {                 // last half of a block: write its scores
-      if ((half_index + 1) % nhalf != 0) return;
-      const int t0 = row_base + (half_index / nhalf) * 128 + w * 16;
+  const int nparts = (nks + KH - 1) / KH;              // parts per block
+  const int nb_here = min(nblk, (len - row_base + 255) / 256);
+  const int total = nb_here * nparts;                  // parts this wave goes through
+  f32x4 acc[2][2];
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+    for (int ht = 0; ht < 2; ++ht) acc[rb][ht] = f32x4{0.f, 0.f, 0.f, 0.f};
+  auto flush = [&](int part) {                         // last part of a block: write its scores
+    if ((part + 1) % nparts != 0) return;
+    const int t0 = row_base + (part / nparts) * 256 + w * 32;
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
       for (int ht = 0; ht < 2; ++ht) {
-        const int h = hg * 32 + ht * 16 + n;           // D[ht]: column n = head, rows kq*4 + r
+        const int h = hg * 32 + ht * 16 + n;           // D: column n = head, rows kq*4 + r
         if (h < H) {
-          float* dst = S + ((size_t)b * H + h) * T + t0 + kq * 4;
+          float* dst = S + ((size_t)b * H + h) * T + t0 + rb * 16 + kq * 4;
 #pragma unroll
           for (int r = 0; r < 4; ++r)
-            if (t0 + kq * 4 + r < len) dst[r] = acc[ht][r];
+            if (t0 + rb * 16 + kq * 4 + r < len) dst[r] = acc[rb][ht][r];
         }
-        acc[ht] = f32x4{0.f, 0.f, 0.f, 0.f};
+        acc[rb][ht] = f32x4{0.f, 0.f, 0.f, 0.f};
       }
-    };
+  };
+  load_part(a0, 0, 0);
+  for (int i = 0; i < total; i += 2) {                 // even parts in a0, odd parts in a1
+    if (i + 1 < total) load_part(a1, (i + 1) / nparts, ((i + 1) % nparts) * KH);
+    mma_part(a0, (i % nparts) * KH, acc);
     flush(i);
-    if (i + 2 < total) load_half(a0, (i + 2) / nhalf, ((i + 2) % nhalf) * KH);
+    if (i + 2 < total) load_part(a0, (i + 2) / nparts, ((i + 2) % nparts) * KH);
     if (i + 1 < total) {
-      mma_half(a1, ((i + 1) % nhalf) * KH, acc);
+      mma_part(a1, ((i + 1) % nparts) * KH, acc);
       flush(i + 1);
     }
   }
@@ -331,15 +362,15 @@ int xcache_splits(int B, int H, int T, int d_model) {
 
 void launch_xq_tilde(const float* q, const void* Wk, float* qt, int B, int H, int d_k, int d_model, int e,
                      int* counters, int ncounters, hipStream_t st) {
-  dim3 grid(H, (d_model + 127) / 128, (B + 15) / 16);
+  dim3 grid((H + XQ_HEADS - 1) / XQ_HEADS, (d_model + 127) / 128, (B + 15) / 16);
   hipLaunchKernelGGL(xq_tilde_kernel, grid, dim3(512), 0, st, q, (const uint16_t*)Wk, qt, B, H, d_k, d_model, e,
                      counters, ncounters);
 }
 
 void launch_xscores(const float* qt, const void* X, long x_bstride, const int32_t* seq_lens, int T, int H,
                     int d_model, float scale, float* S, int B, hipStream_t st) {
-  // blocks of 128 rows per workgroup: about one workgroup per CU (the q~ operands are staged per workgroup)
-  const int blocks = (T + 127) / 128, per = ((H + 31) / 32) * B;
+  // blocks of 256 rows per workgroup: about one workgroup per CU (the q~ operands are staged per workgroup)
+  const int blocks = (T + 255) / 256, per = ((H + 31) / 32) * B;
   int nblk = (blocks * per + 255) / 256;
   if (nblk < 1) nblk = 1;
   dim3 grid((blocks + nblk - 1) / nblk, (H + 31) / 32, B);
