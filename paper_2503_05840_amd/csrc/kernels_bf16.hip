@@ -111,6 +111,12 @@ __device__ __forceinline__ void st_result(int* p, int v, bool write_through) {
   else *p = v;
 }
 
+__device__ __forceinline__ void st_result4(float* p, f32x4 v, bool write_through) {
+  // (s_nops: see st_exch)
+  if (write_through) asm volatile("s_nop 1\n\tglobal_store_dwordx4 %0, %1, off sc0 sc1\n\ts_nop 1" : : "v"(p), "v"(v) : "memory");
+  else *reinterpret_cast<f32x4*>(p) = v;
+}
+
 // s_waitcnt vmcnt(n) for a run-time even n <= 30 (the instruction wants a constant).
 __device__ __forceinline__ void wait_vm_outstanding(int n) {
   switch (n >> 1) {
@@ -425,12 +431,20 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
   __shared__ int prefix[FUSED_MAX_B + 1];
   __shared__ float marr[NP][NT][16];
   __shared__ float larr[NP][NT][16];
-  __shared__ int consumed[NP];                      // tiles of this segment the summing wave has taken
-  __shared__ int published[NP];                     // tiles of this segment the scoring wave has published
+  __shared__ int consumed[NP];                      // tiles (of all segments so far) the summing wave has taken
+  __shared__ int published[NP];                     // tiles (of all segments so far) the scoring wave has published
   __shared__ u32x4 tiles[NP][NS][512];              // per pair: 8 KB landing slots for K tiles
-  // the end-of-segment reduction reuses the (then idle) landing slots
-  float* const sbuf = reinterpret_cast<float*>(&tiles[0][0][0]);   // [NP][HP][129] floats
-  static_assert(sizeof(float) * NP * HP * 129 <= sizeof(u32x4) * NP * NS * 512, "reduction buffer must fit the slots");
+  // By-context partition: the end-of-share merge of the four summing waves goes through the (then
+  // idle) slots.  By-sequence partition: the scoring waves keep streaming, so a summing wave
+  // transposes its result through a part of its own, TRANSPOSE_HEADS heads per pass.  The
+  // projection of the single-launch mode runs after everything else and reuses both.
+  constexpr int TRANSPOSE_HEADS = 8;
+  __shared__ __align__(16) float sbuf[(sizeof(ProjShared<1>) > sizeof(float) * NP * TRANSPOSE_HEADS * 129
+                                           ? sizeof(ProjShared<1>) : sizeof(float) * NP * TRANSPOSE_HEADS * 129) / sizeof(float)];
+  float* const mbuf = reinterpret_cast<float*>(&tiles[0][0][0]);   // [NP][HP][129] floats
+  static_assert(sizeof(float) * NP * HP * 129 <= sizeof(u32x4) * NP * NS * 512, "merge buffer must fit the slots");
+  float* const red = reinterpret_cast<float*>(&tiles[0][0][0]);    // 64 KB for the projection's cross-wave sum
+  static_assert(sizeof(float) * 8 * 8 * 4 * 64 <= sizeof(u32x4) * NP * NS * 512, "cross-wave sum must fit the slots");
   static_assert(NP == 4 && NS >= 3 && NS <= 5, "the thread mappings below assume 4 pairs");
 
   // ---- which group / column unit is this workgroup -------------------------------------------
@@ -461,11 +475,12 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
   if (blockIdx.x == 0 && a.counters)                // the projection's arrival counters start at 0
     for (int i = tid; i < a.ncounters; i += NTHR) st_result(a.counters + i, 0, fuse);
 
-  build_tile_prefix(prefix, a.seq_lens, a.B, a.T);
+  if (tid < NP) { consumed[tid] = 0; published[tid] = 0; }
+  build_tile_prefix(prefix, a.seq_lens, a.B, a.T);     // (ends with a workgroup barrier)
   const int VT = prefix[a.B];
   const int Qt = (VT + a.NG - 1) / a.NG;            // tiles per group
   const int v0 = g * Qt, v1 = min(VT, v0 + Qt);
-  if (v0 >= v1) has_work = false;
+  if (a.by_sequence ? (g * NP >= a.B) : (v0 >= v1)) has_work = false;
   if (!has_work && !fuse) return;
 
   // ---- lane -> column mapping inside the unit --------------------------------------------------
@@ -476,6 +491,13 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
   const bool pub_lane = col_active && (li == 0);    // one lane per head publishes its row group
   const int ucol0 = u * a.hpu * a.d_k;
   const int uwc = min(a.hpu * a.d_k, a.d - ucol0);  // columns of this unit
+  int ocol[4];                                      // first unit-local column of accumulator row r, or -1
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int mi = rg * 4 + r;                      // column group (the A operand's M index)
+    const int h2 = mi / a.lphp, l2 = mi % a.lphp;
+    ocol[r] = (l2 < a.lph && h2 < a.hpu) ? h2 * a.d_k + l2 * 8 : -1;
+  }
 
   const bool xl = a.xcd_local != 0;
   const bool all_active = __all(col_active) != 0;    // every lane of the wave owns live columns
@@ -488,34 +510,52 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
     dead = true;
   };
 
-  // The segments (sequence shares) of this group, the same walk for both roles.  Both roles run
-  // the same sequence of workgroup barriers per segment.
-  struct Seg { int b, s0, ntl, len; unsigned it0; const uint16_t* Kb; };
-  int seg_b = 0;
+  // The work of this wave pair, the same walk for both roles, as a list of segments (a sequence or
+  // a share of one); tile k of a segment is row tile t0 + k * stride of sequence b.  Two partitions:
+  //  * by context (default): the group's range of tiles [v0, v1) is cut at sequence boundaries and
+  //    the four pairs take the tiles of a share round-robin; the pairs' results are merged at the
+  //    end of each share and the groups' partials by the projection.  Balanced for any lengths.
+  //  * by sequence: pair slot g * NP + p takes whole sequences round-robin; nothing to merge, one
+  //    partial per sequence.  For batches with many short sequences.
+  struct Seg { int b, t0, stride, ntl, len; unsigned it0; const uint16_t* Kb; };   // it0: tiles of earlier segments
+  const bool by_seq = a.by_sequence != 0;
+  int seg_b = by_seq ? g * NP + p : 0;
   unsigned seg_it = 0;                              // tiles this pair has been through so far
-  if (has_work)
+  if (has_work && !by_seq)
     while (prefix[seg_b + 1] <= v0) ++seg_b;
   auto next_segment = [&](Seg& sg) -> bool {
+    if (by_seq) {
+      if (seg_b >= a.B) return false;
+      const int b = seg_b;
+      seg_b += a.NG * NP;
+      sg.b = b; sg.t0 = 0; sg.stride = 1;
+      sg.len = seq_len_of(a.seq_lens, b, a.T);
+      sg.Kb = a.K + (size_t)b * a.k_bstride;
+      sg.ntl = prefix[b + 1] - prefix[b];
+      sg.it0 = seg_it;
+      seg_it += (unsigned)sg.ntl;
+      return true;
+    }
     for (; seg_b < a.B && prefix[seg_b] < v1; ++seg_b) {
       const int b = seg_b;
       const int s0 = max(v0, prefix[b]) - prefix[b];
       const int s1 = min(v1, prefix[b + 1]) - prefix[b];
       if (s0 >= s1) continue;
       sg.b = b;
-      sg.s0 = s0;
+      sg.t0 = s0 + p; sg.stride = NP;                 // this pair's tiles are s0+p, s0+p+NP, ...
       sg.len = seq_len_of(a.seq_lens, b, a.T);
       sg.Kb = a.K + (size_t)b * a.k_bstride;
-      // this pair's tiles are s0+p, s0+p+NP, ...; tile k carries tag tag_base + it0 + k + 1
       sg.ntl = max(0, (s1 - s0 - p + NP - 1) / NP);
-      sg.it0 = seg_it;
+      sg.it0 = seg_it;                                // tile k carries tag tag_base + it0 + k + 1
       seg_it += (unsigned)sg.ntl;
       ++seg_b;
       return true;
     }
     return false;
   };
-  // End of a segment, all threads: sum the summing waves' accumulators out of sbuf[pair][head][col]
-  // (one thread per column and head quarter) and write the group's partial for this sequence.
+  // End of a share in the by-context partition, all threads: sum the summing waves' accumulators
+  // out of mbuf[pair][head][col] (one thread per column and head quarter) and write the group's
+  // partial for this sequence.
   auto write_partial = [&](int pid) {
     const int ocl = tid & 127, ohq = tid >> 7;
     if (ocl < uwc) {
@@ -524,7 +564,7 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
         const int h = ohq + 4 * jj;
         float osum = 0.f;
 #pragma unroll
-        for (int ww = 0; ww < NP; ++ww) osum += sbuf[((size_t)ww * HP + h) * 129 + ocl];
+        for (int ww = 0; ww < NP; ++ww) osum += mbuf[((size_t)ww * HP + h) * 129 + ocl];
         if (h < a.H) st_result(a.Cpart + ((size_t)pid * a.H + h) * a.d + ucol0 + ocl, osum, fuse);
       }
     }
@@ -547,10 +587,8 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
     // ========================= scoring waves: HBM -> registers -> LDS, scores, publish ===========
     Seg sg;
     while (next_segment(sg)) {
-      const int ntl = sg.ntl, len = sg.len, s0 = sg.s0;
+      const int ntl = sg.ntl, len = sg.len;
       const uint16_t* Kb = sg.Kb;
-      if (tid < NP) { consumed[tid] = 0; published[tid] = 0; }
-      __syncthreads();
       // query for this lane's 8 columns, pre-scaled (log2 domain), split into bf16 hi + lo pairs
       // so that the dot products run on v_dot2c_f32_bf16 without losing the fp32 query
       unsigned qh[4], ql[4];
@@ -571,7 +609,7 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
       // to issue here, and a wave's LDS operations queue behind those it has in flight.
       u32x4 ts[PD][8];
       auto load_tile = [&](u32x4 (&t)[8], int k) {
-        const int st = __builtin_amdgcn_readfirstlane(s0 + p + k * NP);
+        const int st = __builtin_amdgcn_readfirstlane(sg.t0 + k * sg.stride);
         if ((st + 1) * TILE_ROWS <= len && all_active) {
           // full tile, every lane loads: uniform row base + per-lane 32-bit offset
           const char* tb = reinterpret_cast<const char*>(Kb) + (size_t)st * TILE_ROWS * pitchB;
@@ -613,7 +651,7 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
           if (a.lphp > 8) sc[j] = dpp_add<0x140>(sc[j]);   // other half of the row
         }
         // ---- this tile's softmax numerators of the unit's heads, against the running maximum -----
-        const int st = s0 + p + k * NP;
+        const int st = sg.t0 + k * sg.stride;
         if ((st + 1) * TILE_ROWS > len) {             // last, partial tile: rows past the end weigh nothing
           const int row0 = st * TILE_ROWS + rg * 8;
 #pragma unroll
@@ -629,18 +667,20 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
           const bf16x2 v = {(__bf16)__builtin_amdgcn_exp2f(sc[2 * i] - ref), (__bf16)__builtin_amdgcn_exp2f(sc[2 * i + 1] - ref)};
           pw[i] = __builtin_bit_cast(unsigned, v);
         }
-        // ---- hand the tile over: slot k % NS, once the summing wave has taken tile k-NS out of it;
-        //      the tile is in LDS before the words that announce it leave
+        // ---- hand the tile over: slot gk % NS (gk counts this pair's tiles over all segments), once
+        //      the summing wave has taken tile gk-NS out of it; the tile is in LDS before the words
+        //      that announce it leave
+        const int gk = (int)sg.it0 + k;
         {
           int spins = 0;
-          while (!dead && __hip_atomic_load(&consumed[p], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) < k - NS + 1) {
+          while (!dead && __hip_atomic_load(&consumed[p], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) < gk - NS + 1) {
             if (++spins > a.spin_limit) { give_up(); break; }
             __builtin_amdgcn_s_sleep(2);
           }
           asm volatile("" ::: "memory");
         }
 #pragma unroll
-        for (int j = 0; j < 8; ++j) tiles[p][k % NS][j * 64 + lane] = cur[j];
+        for (int j = 0; j < 8; ++j) tiles[p][gk % NS][j * 64 + lane] = cur[j];
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         // ---- publish: {tag, running max, p0 p1, p2 p3} and {tag, 0, p4 p5, p6 p7} per row group ----
         const unsigned itk = sg.it0 + (unsigned)k + 1u;
@@ -651,28 +691,29 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
           st_exch(ring + ((HP + myhead) * 4 + rg), u32x4{tag, 0u, pw[2], pw[3]}, xl);
         }
         // a hint for the summing wave (the words themselves carry the proof)
-        if (lane == 0) __hip_atomic_store(&published[p], k + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        if (lane == 0) __hip_atomic_store(&published[p], gk + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         if (k + PD < ntl) load_tile(cur, k + PD);
       };
 #pragma unroll
       for (int k = 0; k < PD; ++k)
         if (k < ntl) load_tile(ts[k], k);
       for (int k = 0; k < ntl; k += PD) unrolled_steps<0, PD>(k, ntl, step);
-
-      // ---- end of this sequence's share (the barriers of the summing waves' merge) ---------------
-      __syncthreads();
-      __syncthreads();
-      __syncthreads();
-      write_partial(sg.b + g);
-      __syncthreads();
+      if (!by_seq) {
+        // ---- end of this share (the barriers of the merge; the slots are its buffer) --------------
+        __syncthreads();
+        __syncthreads();
+        __syncthreads();
+        write_partial(sg.b + g);
+        __syncthreads();
+      }
+      // (by sequence: on to the next sequence at once; its tiles wait in the slots meanwhile)
     }
   } else {
     // ========================= summing waves: gather, rescale, MFMA ==============================
     Seg sg;
     while (next_segment(sg)) {
       const int ntl = sg.ntl;
-      // (threads 0..NP-1, which reset the hand-over counters, belong to a scoring wave)
-      __syncthreads();
+      const int gk0 = (int)sg.it0;                    // this pair's tiles before this segment
       // softmax state and accumulators; accl: sum of the weights (an all-ones A operand)
       float m[NT];
       f32x4 acc[8][NT], accl[NT];
@@ -707,7 +748,7 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
         const unsigned tag = a.tag_base + sg.it0 + (unsigned)k + 1u;
         if (issued == k) {                            // nothing in flight for this tile yet
           int hs = 0;
-          while (!dead && partner_at() < k + 1) {
+          while (!dead && partner_at() < gk0 + k + 1) {
             if (++hs > a.spin_limit) { give_up(); break; }
             __builtin_amdgcn_s_sleep(1);
           }
@@ -718,7 +759,7 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
           const int pa = partner_at();
 #pragma unroll
           for (int i = 1; i < DEPTH; ++i)
-            if (issued == k + i && issued < ntl && pa > issued) {
+            if (issued == k + i && issued < ntl && pa > gk0 + issued) {
               gather(gq[(B0 + i) % DEPTH], issued);
               ++issued;
             }
@@ -747,10 +788,10 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
         // the scoring wave published after it had written the tile, so the tile is in its slot
         u32x4 kt[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) kt[j] = tiles[p][k % NS][j * 64 + lane];
+        for (int j = 0; j < 8; ++j) kt[j] = tiles[p][(gk0 + k) % NS][j * 64 + lane];
         asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(kt[0]), "+v"(kt[1]), "+v"(kt[2]), "+v"(kt[3]),
                      "+v"(kt[4]), "+v"(kt[5]), "+v"(kt[6]), "+v"(kt[7]) : : "memory");
-        if (lane == 0) __hip_atomic_store(&consumed[p], k + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        if (lane == 0) __hip_atomic_store(&consumed[p], gk0 + k + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         bf16x8 pb[NT];
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
@@ -783,7 +824,46 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
       };
       for (int k = 0; k < ntl; k += DEPTH) unrolled_steps<0, DEPTH>(k, ntl, step);
 
-      // ---- end of this sequence's share: merge the summing waves and write one partial -----------
+      // ---- end of this sequence's share: merge the four summing waves and write one partial -------
+      if (by_seq) {
+        // the whole sequence was this wave's: transpose through the pair's part of sbuf
+        // (TRANSPOSE_HEADS heads per pass, no other wave involved) and write the sequence's partial
+        float* mine = sbuf + (size_t)p * TRANSPOSE_HEADS * 129;
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+#pragma unroll 1
+          for (int hq = 0; hq < 16 / TRANSPOSE_HEADS; ++hq) {
+            const int n0 = hq * TRANSPOSE_HEADS;
+            if (n >= n0 && n < n0 + TRANSPOSE_HEADS) {
+#pragma unroll
+              for (int r = 0; r < 4; ++r) {
+                if (ocol[r] < 0) continue;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) mine[(n - n0) * 129 + ocol[r] + i] = acc[i][t][r];
+              }
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+            for (int hl = 0; hl < TRANSPOSE_HEADS; ++hl) {
+              const int h = t * 16 + n0 + hl;
+              if (h >= a.H) break;
+#pragma unroll
+              for (int cc = 0; cc < 2; ++cc) {
+                const int col = lane + 64 * cc;
+                if (col < uwc) st_result(a.Cpart + ((size_t)sg.b * a.H + h) * a.d + ucol0 + col, mine[hl * 129 + col], fuse);
+              }
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+          }
+          const int h = t * 16 + n;
+          if (u == 0 && kg == 0 && h < a.H) {
+            st_result(a.mpart + (size_t)sg.b * a.H + h, m[t], fuse);
+            st_result(a.lpart + (size_t)sg.b * a.H + h, accl[t][0], fuse);
+          }
+        }
+        continue;
+      }
+      // ---- by context: merge the four summing waves and write one partial -------------------------
       __syncthreads();                                // every slot is idle from here on
       if (kg == 0) {
 #pragma unroll
@@ -791,7 +871,7 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
       }
       __syncthreads();
       {
-        // accumulators -> sbuf[pair][head][col] (row pitch 129 floats), in MFMA layout, scaled to
+        // accumulators -> mbuf[pair][head][col] (row pitch 129 floats), in MFMA layout, scaled to
         // the maximum over the four summing waves
         float wsc[NT];
 #pragma unroll
@@ -802,22 +882,19 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
           wsc[t] = (m[t] == NEG_INF) ? 0.f : exp2f(m[t] - mall);
           if (kg == 0) larr[p][t][n] = accl[t][0] * wsc[t];   // every accumulator row holds the same sum
         }
-        float* mine = sbuf + (size_t)p * HP * 129 + n * 129;
+        float* mine = mbuf + (size_t)p * HP * 129 + n * 129;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          const int mi = rg * 4 + r;                   // column group (the A operand's M index)
-          const int h2 = mi / a.lphp, l2 = mi % a.lphp;
-          if (!(l2 < a.lph && h2 < a.hpu)) continue;
-          const int oc = h2 * a.d_k + l2 * 8;          // first unit-local column of accumulator row r
+          if (ocol[r] < 0) continue;
 #pragma unroll
           for (int t = 0; t < NT; ++t)
 #pragma unroll
-            for (int i = 0; i < 8; ++i) mine[t * 16 * 129 + oc + i] = acc[i][t][r] * wsc[t];
+            for (int i = 0; i < 8; ++i) mine[t * 16 * 129 + ocol[r] + i] = acc[i][t][r] * wsc[t];
         }
       }
       __syncthreads();
       write_partial(sg.b + g);
-      __syncthreads();                                // the slots are reused by the next segment
+      __syncthreads();                                // the slots are reused by the next share
     }
   }
   if (!fuse) return;
@@ -829,9 +906,9 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
   if (tid == 0) st_result(reinterpret_cast<int*>(a.flags) + blockIdx.x, (int)a.launch_id, true);
   const int wg = blockIdx.x;
   if (wg >= a.proj.H * a.proj.csw) return;
-  __shared__ ProjShared<1> psm;
-  // (the tile slots are idle by now: they serve the projection's cross-wave sum)
-  project_work<1, true>(a.proj, wg / a.proj.csw, wg % a.proj.csw, 0, prefix, psm, sbuf, [&]() {
+  // (everything of the stream phase is over in this workgroup: its LDS is reused)
+  ProjShared<1>& psm = *reinterpret_cast<ProjShared<1>*>(sbuf);
+  project_work<1, true>(a.proj, wg / a.proj.csw, wg % a.proj.csw, 0, prefix, psm, red, [&]() {
     // every workgroup's partials must be out: all arrival flags carry this launch's id
     if (wu == 0) {
       int spins = 0;
@@ -910,6 +987,14 @@ bool xcd_round_robin(int device) {
   (void)hipGetLastError();
   cached[device] = ok ? 1 : 2;
   return ok;
+}
+
+// Whether wave pairs take whole sequences (nothing to merge) instead of shares of the group's
+// context range: for batches that fill most pair slots with sequences of one length (ragged
+// batches keep the balanced partition unless there are many sequences per slot).
+bool fused_by_sequence(const FusedGeom& g, int B, bool ragged) {
+  const int slots = g.NG * FUSED_PAIRS;
+  return ragged ? B >= 4 * slots : 5 * B >= 3 * slots;
 }
 
 size_t fused_exch_bytes(const FusedGeom& g) {

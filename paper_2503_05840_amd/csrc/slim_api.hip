@@ -246,7 +246,11 @@ extern "C" int slim_decode(const void* q, const void* Kcache, const void* W_KV, 
     pa.err = ctrl + CTRL_INTS - 1; pa.launch_id = lid; pa.seq_lens = lens;
     pa.B = B; pa.T = T; pa.H = H; pa.d_k = d_k; pa.rows = d; pa.e = d;
     pa.NG = g.NG; pa.nsplit = 0; pa.mode = 0; pa.mscale = 1.0f; pa.csw = p.csw;
-    const bool one_launch = variant == SLIM_VARIANT_FUSED && p.csw_f > 0;
+    if (fused_by_sequence(g, B, lens != nullptr)) {
+      fa.by_sequence = 1;
+      pa.mode = 1; pa.nsplit = 1;                    // one partial per sequence
+    }
+    const bool one_launch = variant == SLIM_VARIANT_FUSED && p.csw_f > 0 && !fa.by_sequence;
     if (one_launch) {
       // the stream kernel's workgroups also merge and project (flags after the counters)
       pa.csw = p.csw_f;

@@ -24,6 +24,10 @@ SMALL = {
     "whisper-width-all-waves": synth.scaled(C[3], B=1, T=6144),
     "two-heads-per-unit-multi-tile": synth.scaled(C[3], B=3, H=32, d=2048, T=5000, len_lo=3000),
     "dk96-multi-tile": synth.scaled(C[2], B=2, T=9000, len_lo=4000),
+    # batches that fill the wave-pair slots: whole sequences per pair (uniform lengths with a partial
+    # last tile; ragged with many sequences per slot, 1-row sequences included)
+    "batch-by-sequence": synth.scaled(C[1], B=40, H=16, d=2048, T=203),
+    "batch-by-sequence-ragged": synth.scaled(C[1], B=130, H=32, d=4096, T=150, len_lo=1),
 }
 VARIANTS = {"auto": binding.VARIANT_AUTO, "generic": binding.VARIANT_GENERIC, "fused": binding.VARIANT_FUSED,
             "fused_split": binding.VARIANT_FUSED_SPLIT}
