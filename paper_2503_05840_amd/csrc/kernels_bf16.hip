@@ -480,7 +480,7 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
   const int VT = prefix[a.B];
   const int Qt = (VT + a.NG - 1) / a.NG;            // tiles per group
   const int v0 = g * Qt, v1 = min(VT, v0 + Qt);
-  if (a.by_sequence ? (g * NP >= a.B) : (v0 >= v1)) has_work = false;
+  if (a.by_sequence ? (g * NP >= a.B * a.by_sequence) : (v0 >= v1)) has_work = false;
   if (!has_work && !fuse) return;
 
   // ---- lane -> column mapping inside the unit --------------------------------------------------
@@ -515,9 +515,10 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
   //  * by context (default): the group's range of tiles [v0, v1) is cut at sequence boundaries and
   //    the four pairs take the tiles of a share round-robin; the pairs' results are merged at the
   //    end of each share and the groups' partials by the projection.  Balanced for any lengths.
-  //  * by sequence: pair slot g * NP + p takes whole sequences round-robin; nothing to merge, one
-  //    partial per sequence.  For batches with many short sequences.
-  struct Seg { int b, t0, stride, ntl, len; unsigned it0; const uint16_t* Kb; };   // it0: tiles of earlier segments
+  //  * by sequence: every sequence is cut into a.by_sequence equal shares and pair slot g * NP + p
+  //    takes shares round-robin; no merge inside the workgroup, one partial per share.  For batches
+  //    whose shares fill the slots evenly (many short sequences).
+  struct Seg { int b, t0, stride, ntl, len, pid; unsigned it0; const uint16_t* Kb; };   // it0: tiles of earlier segments
   const bool by_seq = a.by_sequence != 0;
   int seg_b = by_seq ? g * NP + p : 0;
   unsigned seg_it = 0;                              // tiles this pair has been through so far
@@ -525,13 +526,15 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
     while (prefix[seg_b + 1] <= v0) ++seg_b;
   auto next_segment = [&](Seg& sg) -> bool {
     if (by_seq) {
-      if (seg_b >= a.B) return false;
-      const int b = seg_b;
+      const int shares = a.by_sequence;               // shares per sequence (equal runs of tiles)
+      if (seg_b >= a.B * shares) return false;
+      const int q = seg_b, b = q / shares, j = q - b * shares;
       seg_b += a.NG * NP;
-      sg.b = b; sg.t0 = 0; sg.stride = 1;
+      const int tiles_b = prefix[b + 1] - prefix[b], per = (tiles_b + shares - 1) / shares;
+      sg.b = b; sg.t0 = j * per; sg.stride = 1; sg.pid = q;
       sg.len = seq_len_of(a.seq_lens, b, a.T);
       sg.Kb = a.K + (size_t)b * a.k_bstride;
-      sg.ntl = prefix[b + 1] - prefix[b];
+      sg.ntl = max(0, min(per, tiles_b - j * per));
       sg.it0 = seg_it;
       seg_it += (unsigned)sg.ntl;
       return true;
@@ -541,7 +544,7 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
       const int s0 = max(v0, prefix[b]) - prefix[b];
       const int s1 = min(v1, prefix[b + 1]) - prefix[b];
       if (s0 >= s1) continue;
-      sg.b = b;
+      sg.b = b; sg.pid = b + g;
       sg.t0 = s0 + p; sg.stride = NP;                 // this pair's tiles are s0+p, s0+p+NP, ...
       sg.len = seq_len_of(a.seq_lens, b, a.T);
       sg.Kb = a.K + (size_t)b * a.k_bstride;
@@ -703,7 +706,7 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
         __syncthreads();
         __syncthreads();
         __syncthreads();
-        write_partial(sg.b + g);
+        write_partial(sg.pid);
         __syncthreads();
       }
       // (by sequence: on to the next sequence at once; its tiles wait in the slots meanwhile)
@@ -850,15 +853,15 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
 #pragma unroll
               for (int cc = 0; cc < 2; ++cc) {
                 const int col = lane + 64 * cc;
-                if (col < uwc) st_result(a.Cpart + ((size_t)sg.b * a.H + h) * a.d + ucol0 + col, mine[hl * 129 + col], fuse);
+                if (col < uwc) st_result(a.Cpart + ((size_t)sg.pid * a.H + h) * a.d + ucol0 + col, mine[hl * 129 + col], fuse);
               }
             }
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
           }
           const int h = t * 16 + n;
           if (u == 0 && kg == 0 && h < a.H) {
-            st_result(a.mpart + (size_t)sg.b * a.H + h, m[t], fuse);
-            st_result(a.lpart + (size_t)sg.b * a.H + h, accl[t][0], fuse);
+            st_result(a.mpart + (size_t)sg.pid * a.H + h, m[t], fuse);
+            st_result(a.lpart + (size_t)sg.pid * a.H + h, accl[t][0], fuse);
           }
         }
         continue;
@@ -893,7 +896,7 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
         }
       }
       __syncthreads();
-      write_partial(sg.b + g);
+      write_partial(sg.pid);
       __syncthreads();                                // the slots are reused by the next share
     }
   }
@@ -989,12 +992,20 @@ bool xcd_round_robin(int device) {
   return ok;
 }
 
-// Whether wave pairs take whole sequences (nothing to merge) instead of shares of the group's
-// context range: for batches that fill most pair slots with sequences of one length (ragged
-// batches keep the balanced partition unless there are many sequences per slot).
-bool fused_by_sequence(const FusedGeom& g, int B, bool ragged) {
-  const int slots = g.NG * FUSED_PAIRS;
-  return ragged ? B >= 4 * slots : 5 * B >= 3 * slots;
+// By-sequence partition: how many equal shares to cut every sequence into so that the shares fill
+// the wave-pair slots evenly (1..4), or 0 to keep the balanced by-context partition.  Ragged
+// batches qualify only with many shares per slot.
+int fused_by_sequence(const FusedGeom& g, int B, bool ragged) {
+  const long slots = (long)g.NG * FUSED_PAIRS;
+  int best = 0;
+  double best_waste = 1.13;                           // at most 13 % idle slot-time
+  for (int s = 1; s <= 4; ++s) {
+    const long shares = (long)B * s, rounds = (shares + slots - 1) / slots;
+    const double waste = (double)(rounds * slots) / (double)shares;
+    if (ragged && shares < 4 * slots) continue;
+    if (waste < best_waste - 0.04) { best = s; best_waste = waste; }
+  }
+  return best;
 }
 
 size_t fused_exch_bytes(const FusedGeom& g) {

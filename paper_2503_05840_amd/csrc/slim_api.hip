@@ -47,6 +47,7 @@ Plan make_plan(int B, int H, int T, int width, int e) {
   p.nsplit_x = xcache_splits(B, H, T, width);
   size_t nparts = (size_t)B * (p.nsplit > p.nsplit_x ? p.nsplit : p.nsplit_x);
   if (p.fused_ok && (size_t)p.geom.nparts > nparts) nparts = p.geom.nparts;
+  if (p.fused_ok && (size_t)B * 4 > nparts && fused_by_sequence(p.geom, B, false)) nparts = (size_t)B * 4;
   p.csw = proj_row_splits(H, width, e, B);
   if (p.fused_ok && B <= 16 && p.geom.grid >= H) {
     const int tiles_w = (width + TILE_ROWS - 1) / TILE_ROWS;
@@ -246,9 +247,9 @@ extern "C" int slim_decode(const void* q, const void* Kcache, const void* W_KV, 
     pa.err = ctrl + CTRL_INTS - 1; pa.launch_id = lid; pa.seq_lens = lens;
     pa.B = B; pa.T = T; pa.H = H; pa.d_k = d_k; pa.rows = d; pa.e = d;
     pa.NG = g.NG; pa.nsplit = 0; pa.mode = 0; pa.mscale = 1.0f; pa.csw = p.csw;
-    if (fused_by_sequence(g, B, lens != nullptr)) {
-      fa.by_sequence = 1;
-      pa.mode = 1; pa.nsplit = 1;                    // one partial per sequence
+    if (const int shares = fused_by_sequence(g, B, lens != nullptr)) {
+      fa.by_sequence = shares;
+      pa.mode = 1; pa.nsplit = shares;               // partials laid out [sequence][share]
     }
     const bool one_launch = variant == SLIM_VARIANT_FUSED && p.csw_f > 0 && !fa.by_sequence;
     if (one_launch) {

@@ -92,7 +92,7 @@ struct FusedArgs {
   int xcd_local;                      // 1: a group's workgroups share an XCD, the exchange stays in its L2
   // Single-launch mode: once all workgroups have written their partials (arrival flags, tagged
   // with launch_id), each takes a (head, row split) share of the merge + projection.
-  int by_sequence;                    // 1: wave pairs take whole sequences, one partial per sequence
+  int by_sequence;                    // > 0: by-sequence partition with this many shares per sequence
   int fuse;
   unsigned* flags;                    // [grid]
   ProjArgs proj;                      // csw * H <= grid, B <= 16
@@ -100,7 +100,7 @@ struct FusedArgs {
 
 
 bool fused_geometry(int B, int H, int T, int d, FusedGeom* g);
-bool fused_by_sequence(const FusedGeom& g, int B, bool ragged);
+int fused_by_sequence(const FusedGeom& g, int B, bool ragged);
 size_t fused_exch_bytes(const FusedGeom& g);
 bool xcd_round_robin(int device);
 void launch_fused_stream(const FusedGeom& g, const FusedArgs& a, hipStream_t st);
