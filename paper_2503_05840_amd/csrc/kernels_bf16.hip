@@ -589,6 +589,7 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
   } else if (scoring) {
     // ========================= scoring waves: HBM -> registers -> LDS, scores, publish ===========
     Seg sg;
+    int seen_consumed = 0;                          // last value read from consumed[p]
     while (next_segment(sg)) {
       const int ntl = sg.ntl, len = sg.len;
       const uint16_t* Kb = sg.Kb;
@@ -674,14 +675,15 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
         //      the summing wave has taken tile gk-NS out of it; the tile is in LDS before the words
         //      that announce it leave
         const int gk = (int)sg.it0 + k;
-        {
+        if (seen_consumed < gk - NS + 1) {            // (the counter only grows: re-read it only when needed)
           int spins = 0;
-          while (!dead && __hip_atomic_load(&consumed[p], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) < gk - NS + 1) {
+          while (!dead && (seen_consumed = __builtin_amdgcn_readfirstlane(__hip_atomic_load(
+                               &consumed[p], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP))) < gk - NS + 1) {
             if (++spins > a.spin_limit) { give_up(); break; }
             __builtin_amdgcn_s_sleep(2);
           }
-          asm volatile("" ::: "memory");
         }
+        asm volatile("" ::: "memory");
 #pragma unroll
         for (int j = 0; j < 8; ++j) tiles[p][gk % NS][j * 64 + lane] = cur[j];
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
