@@ -500,7 +500,6 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
   }
 
   const bool xl = a.xcd_local != 0;
-  const bool all_active = __all(col_active) != 0;    // every lane of the wave owns live columns
   const bool heads_full = (a.H == HP);               // no padded heads in the MFMA N tiles
   const unsigned pitchB = (unsigned)a.d * 2u;        // bytes per cache row
   u32x4* const team_ring = reinterpret_cast<u32x4*>(a.exch) + (size_t)(g * NP + p) * EXCH_SLOTS * (HP * 8);
@@ -606,7 +605,9 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
         qh[c] = __builtin_bit_cast(unsigned, hi);
         ql[c] = __builtin_bit_cast(unsigned, lo);
       }
-      const unsigned lane_off = (unsigned)(rg * 8) * pitchB + (unsigned)mycol * 2u;
+      // (lanes without live columns re-read the unit's first columns: finite values that meet a zero
+      //  query here and accumulator rows nobody reads in the summing wave)
+      const unsigned lane_off = (unsigned)(rg * 8) * pitchB + (unsigned)(col_active ? mycol : ucol0) * 2u;
       float mrun = NEG_INF;                           // running maximum of this lane's head (log2 domain)
       // Tiles travel HBM -> registers (PD register sets: PD-1 tiles in flight while one is being
       // scored) -> LDS slot, where the summing wave picks them up.  Direct-to-LDS loads are slower
@@ -614,8 +615,8 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
       u32x4 ts[PD][8];
       auto load_tile = [&](u32x4 (&t)[8], int k) {
         const int st = __builtin_amdgcn_readfirstlane(sg.t0 + k * sg.stride);
-        if ((st + 1) * TILE_ROWS <= len && all_active) {
-          // full tile, every lane loads: uniform row base + per-lane 32-bit offset
+        if ((st + 1) * TILE_ROWS <= len) {
+          // full tile: uniform row base + per-lane 32-bit offset
           const char* tb = reinterpret_cast<const char*>(Kb) + (size_t)st * TILE_ROWS * pitchB;
 #pragma unroll
           for (int j = 0; j < 8; ++j)
