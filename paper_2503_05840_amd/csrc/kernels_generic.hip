@@ -24,6 +24,12 @@ struct F32 {
     const float4 x = *reinterpret_cast<const float4*>(p);
     v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
   }
+  // the same for data that is read once (non-temporal: does not displace what is reused)
+  static __device__ __forceinline__ void load_stream(const elem* p, float (&v)[4]) {
+    typedef float f4 __attribute__((ext_vector_type(4)));
+    const f4 x = __builtin_nontemporal_load(reinterpret_cast<const f4*>(p));
+    v[0] = x[0]; v[1] = x[1]; v[2] = x[2]; v[3] = x[3];
+  }
   static __device__ __forceinline__ float one(const elem* p) { return *p; }
   static __device__ __forceinline__ void two(const elem* p, float& a, float& b) {
     const float2 x = *reinterpret_cast<const float2*>(p);
@@ -40,6 +46,14 @@ struct BF16 {
     v[2] = __uint_as_float(x.y << 16); v[3] = __uint_as_float(x.y & 0xffff0000u);
     v[4] = __uint_as_float(x.z << 16); v[5] = __uint_as_float(x.z & 0xffff0000u);
     v[6] = __uint_as_float(x.w << 16); v[7] = __uint_as_float(x.w & 0xffff0000u);
+  }
+  static __device__ __forceinline__ void load_stream(const elem* p, float (&v)[8]) {
+    typedef unsigned u4 __attribute__((ext_vector_type(4)));
+    const u4 x = __builtin_nontemporal_load(reinterpret_cast<const u4*>(p));
+    v[0] = __uint_as_float(x[0] << 16); v[1] = __uint_as_float(x[0] & 0xffff0000u);
+    v[2] = __uint_as_float(x[1] << 16); v[3] = __uint_as_float(x[1] & 0xffff0000u);
+    v[4] = __uint_as_float(x[2] << 16); v[5] = __uint_as_float(x[2] & 0xffff0000u);
+    v[6] = __uint_as_float(x[3] << 16); v[7] = __uint_as_float(x[3] & 0xffff0000u);
   }
   static __device__ __forceinline__ float one(const elem* p) {
     return __uint_as_float(((uint32_t)*p) << 16);
@@ -380,8 +394,8 @@ __global__ __launch_bounds__(256) void vanilla_kernel(
 #pragma unroll
       for (int p = 0; p < NPASS; ++p) {
         if (act[p]) {
-          ET::load(Kb + (long)t * e + (p * 16 + idx) * VEC, kv[u][p]);
-          ET::load(Vb + (long)t * e + (p * 16 + idx) * VEC, vv[u][p]);
+          ET::load_stream(Kb + (long)t * e + (p * 16 + idx) * VEC, kv[u][p]);
+          ET::load_stream(Vb + (long)t * e + (p * 16 + idx) * VEC, vv[u][p]);
         } else {
 #pragma unroll
           for (int j = 0; j < VEC; ++j) kv[u][p][j] = vv[u][p][j] = 0.f;
