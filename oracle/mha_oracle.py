@@ -19,6 +19,12 @@ What it computes (row-vector convention, W[in][out], head i = column block
                              scores via (q_i W_K,i^T) X^T, output via (p X) W_V,i.
   * `split_merge_decode`  -- a decode evaluated on an arbitrary partition of the context
                              with a log-sum-exp merge (the algebra behind split-T).
+  * `rope_encode/decode`  -- the 2-D rotation of the RoPE appendix applied to adjacent column
+                             pairs of every head, with one angle table for both directions.
+  * `vanilla_decode_rope` -- the reference result when keys carry rotary positions: scores
+                             against the rotated keys, values untouched.
+  * `slim_option2_rope`   -- option 1 of the RoPE appendix on top of eq. 7 option 2: the cache
+                             holds raw keys, rotated after reading for the scores only.
   * `mha_ops_reads`       -- App. B / Table 2 op and read counts, by enumerating matmuls.
   * `whisper_reads_per_token` -- the closed-form arithmetic of the Whisper table.
 
@@ -113,6 +119,72 @@ def slim_option2(q, K, W_KV, h):
         cols = slice(i * d_k, (i + 1) * d_k)
         c_i = P[i] @ K                      # (d,)
         out[cols] = c_i @ W_KV[:, cols]
+    return out
+
+
+# --------------------------------------------------------------------------------------
+# RoPE appendix: rotary positions on the keys, option 1 (rotate after reading the cache)
+# --------------------------------------------------------------------------------------
+def rope_angles(positions, d_k: int, base: float = 10000.0) -> np.ndarray:
+    """m * theta_j for every position m and column pair j of a head; returns (n, d_k/2).
+
+    The appendix writes only "m theta" for the 2-D case; the frequencies are those of the
+    RoPE paper it cites: theta_j = base^(-2j/d_k), j = 0 .. d_k/2 - 1."""
+    assert d_k % 2 == 0
+    m = np.asarray(positions, np.float64).reshape(-1, 1)
+    theta = np.asarray([base ** (-2.0 * j / d_k) for j in range(d_k // 2)], np.float64)
+    return m * theta.reshape(1, -1)
+
+
+def _rotate_pairs(M, h, ang, direction):
+    M = np.asarray(M, np.float64)
+    n, e = M.shape
+    d_k = e // h
+    assert d_k * h == e and ang.shape == (n, d_k // 2)
+    c, s = np.cos(ang), np.sin(ang) * direction
+    out = np.empty_like(M)
+    for i in range(h):
+        x1 = M[:, i * d_k + 0:(i + 1) * d_k:2]     # first element of each adjacent pair
+        x2 = M[:, i * d_k + 1:(i + 1) * d_k:2]
+        out[:, i * d_k + 0:(i + 1) * d_k:2] = x1 * c + x2 * s
+        out[:, i * d_k + 1:(i + 1) * d_k:2] = -x1 * s + x2 * c
+    return out
+
+
+def rope_encode(M, h, positions, base=10000.0):
+    """RoPE encoding of the appendix, per head and adjacent pair (x1, x2) at position m:
+    y1 = x1 cos(m theta) + x2 sin(m theta),  y2 = -x1 sin(m theta) + x2 cos(m theta)."""
+    M = np.asarray(M, np.float64)
+    return _rotate_pairs(M, h, rope_angles(positions, M.shape[1] // h, base), +1.0)
+
+
+def rope_decode(Y, h, positions, base=10000.0):
+    """RoPE decoding of the appendix: the opposite rotation with the same coefficients,
+    x1 = y1 cos - y2 sin,  x2 = y1 sin + y2 cos."""
+    Y = np.asarray(Y, np.float64)
+    return _rotate_pairs(Y, h, rope_angles(positions, Y.shape[1] // h, base), -1.0)
+
+
+def vanilla_decode_rope(q, K, V, h, base=10000.0):
+    """Vanilla decode when keys carry rotary positions: cached row t is rotated by position t,
+    the query is taken as given (already rotated to its own position by the caller), values
+    are not rotated."""
+    n = np.asarray(K).shape[0]
+    return vanilla_decode(q, rope_encode(K, h, np.arange(n), base), V, h)
+
+
+def slim_option2_rope(q, K, W_KV, h, base=10000.0):
+    """Option 1 of the RoPE appendix with eq. 7 option 2: the cache holds the raw keys; they are
+    rotated after reading for the softmax arguments, and the raw rows enter the weighted sum
+    that W_KV,i turns into the head output."""
+    K = np.asarray(K, np.float64)
+    n, d = K.shape
+    d_k = d // h
+    P = attention_probs(q, rope_encode(K, h, np.arange(n), base), h)
+    out = np.empty(d)
+    for i in range(h):
+        cols = slice(i * d_k, (i + 1) * d_k)
+        out[cols] = (P[i] @ K) @ W_KV[:, cols]
     return out
 
 

@@ -286,3 +286,109 @@ def test_phi3_worked_example():
     assert round(kv_gb) == 26 and abs(k_gb - kv_gb / 2) < 1e-9      # Table 1 prints 25.8B
     assert round((25 + 3.8) / (12.5 + 3.8), 1) == 1.8
     assert round((400 + 3.8) / (200 + 3.8)) == 2
+
+
+# ------------------------------------------------------------------------------------------
+# RoPE appendix: the rotation, its inverse, and option 1 (raw keys in the cache)
+# ------------------------------------------------------------------------------------------
+def test_rope_quarter_turn_by_hand():
+    """d_k = 2, theta_0 = 1: at m = pi/2 the printed encoding gives y1 = x2, y2 = -x1."""
+    y = orc.rope_encode(np.array([[1.0, 0.0], [0.0, 1.0], [3.0, -2.0]]), 1, [math.pi / 2] * 3)
+    np.testing.assert_allclose(y, [[0.0, -1.0], [1.0, 0.0], [-2.0, -3.0]], atol=1e-15)
+    x = orc.rope_decode(np.array([[0.0, -1.0]]), 1, [math.pi / 2])
+    np.testing.assert_allclose(x, [[1.0, 0.0]], atol=1e-15)
+
+
+def test_rope_is_complex_multiplication_per_adjacent_pair():
+    """(x1 + i x2) e^{-i m theta_j} on pair j of every head, with theta_j = base^(-2j/d_k) --
+    written with python complex numbers, element by element."""
+    rng = np.random.default_rng(11)
+    n, h, d_k, base = 5, 3, 8, 500.0
+    M = rng.standard_normal((n, h * d_k))
+    pos = [0, 1, 2, 7, 1000]
+    got = orc.rope_encode(M, h, pos, base)
+    for t in range(n):
+        for i in range(h):
+            for j in range(d_k // 2):
+                z = complex(M[t, i * d_k + 2 * j], M[t, i * d_k + 2 * j + 1])
+                w = z * complex(math.cos(pos[t] * base ** (-2 * j / d_k)), -math.sin(pos[t] * base ** (-2 * j / d_k)))
+                assert abs(got[t, i * d_k + 2 * j] - w.real) < 1e-12
+                assert abs(got[t, i * d_k + 2 * j + 1] - w.imag) < 1e-12
+
+
+def test_rope_touches_only_its_own_pair():
+    """A unit vector in column 2 of a d_k = 4 head moves only into columns 2 and 3."""
+    M = np.zeros((1, 8)); M[0, 6] = 1.0                      # head 1, pair 1, first element
+    y = orc.rope_encode(M, 2, [3.0], base=100.0)
+    th = 3.0 * 100.0 ** (-2 / 4)
+    np.testing.assert_allclose(y[0], [0, 0, 0, 0, 0, 0, math.cos(th), -math.sin(th)], atol=1e-15)
+
+
+def test_rope_decode_undoes_encode_with_the_same_table():
+    rng = np.random.default_rng(12)
+    M = rng.standard_normal((40, 4 * 16))
+    pos = rng.integers(0, 40000, size=40)
+    back = orc.rope_decode(orc.rope_encode(M, 4, pos), 4, pos)
+    np.testing.assert_allclose(back, M, atol=1e-13)
+    np.testing.assert_allclose(orc.rope_encode(M, 4, np.zeros(40)), M, atol=0)      # position 0: identity
+    # rotations: norms of every pair are kept, and positions add up
+    Y = orc.rope_encode(M, 4, pos)
+    np.testing.assert_allclose(Y[:, 0::2] ** 2 + Y[:, 1::2] ** 2, M[:, 0::2] ** 2 + M[:, 1::2] ** 2, rtol=1e-12)
+    np.testing.assert_allclose(orc.rope_encode(Y, 4, 17 - pos), orc.rope_encode(M, 4, np.full(40, 17)), atol=1e-10)
+
+
+def test_rope_scores_depend_on_relative_position_only():
+    """<R_m q, R_t k> is a function of m - t: shifting every position by the same amount leaves
+    the softmax arguments, and so the decode result, unchanged."""
+    rng = np.random.default_rng(13)
+    n, h, d_k = 9, 2, 8
+    K = rng.standard_normal((n, h * d_k)); V = rng.standard_normal((n, h * d_k))
+    q_raw = rng.standard_normal((1, h * d_k))
+    outs = []
+    for shift in (0, 5, 123):
+        q = orc.rope_encode(q_raw, h, [n + shift])[0]
+        Kr = orc.rope_encode(K, h, np.arange(n) + shift)
+        outs.append(orc.vanilla_decode(q, Kr, V, h))
+    np.testing.assert_allclose(outs[1], outs[0], rtol=1e-11)
+    np.testing.assert_allclose(outs[2], outs[0], rtol=1e-10)
+    # and the unshifted case is what vanilla_decode_rope computes (row t sits at position t)
+    np.testing.assert_allclose(orc.vanilla_decode_rope(orc.rope_encode(q_raw, h, [n])[0], K, V, h), outs[0], rtol=1e-13)
+
+
+def test_rope_brute_force_decode():
+    """vanilla_decode_rope against loops over python floats: rotate each key pair with the
+    printed encoding, naive exp, weighted sum of the raw values."""
+    rng = np.random.default_rng(14)
+    n, h, d_k, base = 6, 2, 4, 50.0
+    e = h * d_k
+    K = rng.standard_normal((n, e)); V = rng.standard_normal((n, e)); q = rng.standard_normal(e)
+    want = [0.0] * e
+    for i in range(h):
+        w = []
+        for t in range(n):
+            dot = 0.0
+            for j in range(d_k // 2):
+                th = t * base ** (-2 * j / d_k)
+                x1, x2 = K[t, i * d_k + 2 * j], K[t, i * d_k + 2 * j + 1]
+                y1 = x1 * math.cos(th) + x2 * math.sin(th)
+                y2 = -x1 * math.sin(th) + x2 * math.cos(th)
+                dot += q[i * d_k + 2 * j] * y1 + q[i * d_k + 2 * j + 1] * y2
+            w.append(math.exp(dot / math.sqrt(d_k)))
+        for c in range(d_k):
+            want[i * d_k + c] = sum(w[t] * V[t, i * d_k + c] for t in range(n)) / sum(w)
+    np.testing.assert_allclose(orc.vanilla_decode_rope(q, K, V, h, base), want, rtol=1e-12)
+
+
+def test_rope_option1_on_raw_keys_equals_vanilla_with_rotated_keys(cfg0_problem):
+    """The cache keeps raw keys (so that V = K W_KV still holds); rotating them after the read,
+    for the scores only, gives the result of a vanilla decode over rotated keys and raw values."""
+    p = cfg0_problem
+    w, sq, h = p.w, p.seqs[0], p.cfg.H
+    q = p.q[0] * 30.0                                       # peaky enough that positions matter
+    K = orc.project(sq.X, w.W_K); V = orc.project(sq.X, w.W_V)
+    W_KV = orc.wkv_by_inverse(w.W_K, w.W_V)
+    ref = orc.vanilla_decode_rope(q, K, V, h)
+    got = orc.slim_option2_rope(q, K, W_KV, h)
+    assert np.abs(got - ref).max() <= 1e-10 * np.abs(ref).max()
+    plain = orc.vanilla_decode(q, K, V, h)
+    assert np.abs(plain - ref).max() > 1e-2 * np.abs(ref).max()   # the rotation is not a no-op here
