@@ -34,7 +34,7 @@ extern "C" {
 
 /* ---- status codes ------------------------------------------------------------------- */
 #define SLIM_OK              0
-#define SLIM_ERR_ARG        -1   /* null pointer, negative size                              */
+#define SLIM_ERR_ARG        -1   /* null pointer, negative size, option the call does not take */
 #define SLIM_ERR_SHAPE      -2   /* d % H != 0, d_k not a multiple of the 16-byte vector, T<1 */
 #define SLIM_ERR_DTYPE      -3   /* dtype is neither SLIM_F32 nor SLIM_BF16                   */
 #define SLIM_ERR_ALIGN      -4   /* a device pointer is not 16-byte aligned                   */
@@ -68,6 +68,14 @@ int slim_prepare_wkv(const double* Wk, const double* Wv, double* Wkv, int d, dou
  * caller copies `dst_host` (rows*cols*elemsize bytes, host) to the device. */
 int slim_pack_weights(const double* W, void* dst_host, int rows, int cols, int dtype);
 
+/* The look-up table of the RoPE appendix, one table for encoding and decoding:
+ *   table[t][j] = { cos(t * theta_j), sin(t * theta_j) },  theta_j = base^(-2j/d_k),
+ * for positions t = 0 .. T-1 and the d_k/2 adjacent column pairs (2j, 2j+1) of a head, angles
+ * and functions evaluated in fp64, stored as fp32.  The appendix names only "m theta"; the
+ * frequencies are those of the RoPE paper it cites (base 10000 there).
+ *   table_host: host, T*(d_k/2)*2 floats, written.  d_k even, base > 0. */
+int slim_rope_table(float* table_host, int T, int d_k, double base);
+
 /* ---- options -------------------------------------------------------------------------- */
 typedef struct slim_opts {
   int            dtype;          /* SLIM_F32 | SLIM_BF16: elements of Kcache/Vcache/X and weights */
@@ -86,6 +94,8 @@ typedef struct slim_opts {
                                     the call brackets each of its kernels with HIP events on
                                     `stream`, waits for the stream, and writes each kernel's
                                     milliseconds in launch order (unused entries = 0)             */
+  const float*   rope_table;     /* device fp32 [T][d_k/2][2] from slim_rope_table, nullable => keys
+                                    carry no rotary position.  slim_decode only (see there)       */
 } slim_opts;
 
 #define SLIM_MAX_STAGES 8
@@ -115,7 +125,15 @@ size_t slim_workspace_bytes_xcache(int B, int H, int T, int d_model, int d_k, in
  *            [0, seq_lens[b]) of sequence b are read
  *   W_KV   : device dtype [d][d]          from slim_prepare_wkv + slim_pack_weights
  *   out    : device fp32 [B][d]           concat of heads, written
- *   d = H*d_k.  No V-cache exists anywhere in this call. */
+ *   d = H*d_k.  No V-cache exists anywhere in this call.
+ * With opts->rope_table set (RoPE appendix, option 1): the cache holds the raw keys, cached row t
+ * of every sequence sits at position t, and each key row is rotated by its position after it is
+ * read, for the softmax arguments only -- per head and adjacent pair (x1, x2):
+ *   y1 = x1 cos + x2 sin,  y2 = -x1 sin + x2 cos -- while the raw rows enter the weighted sum.
+ * q is taken as given (the caller has rotated it to the new token's position).
+ * vanilla_kv_decode and slim_decode_xcache return SLIM_ERR_ARG when the table is set: a vanilla
+ * cache stores rotated keys and needs no table, and a position-dependent rotation cannot be
+ * folded into the X-cache scheme's query. */
 int slim_decode(const void* q, const void* Kcache, const void* W_KV, void* out,
                 int B, int H, int T, int d, const slim_opts* opts);
 

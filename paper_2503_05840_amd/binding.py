@@ -19,7 +19,8 @@ SLIM_F32, SLIM_BF16 = 0, 1
 VARIANT_AUTO, VARIANT_GENERIC, VARIANT_FUSED_SPLIT, VARIANT_FUSED = 0, 1, 2, 3
 DTYPES = {"f32": SLIM_F32, "bf16": SLIM_BF16}
 
-EXPORTS = ("slim_strerror", "slim_prepare_wkv", "slim_pack_weights", "slim_workspace_bytes", "slim_workspace_bytes_xcache",
+EXPORTS = ("slim_strerror", "slim_prepare_wkv", "slim_pack_weights", "slim_rope_table", "slim_workspace_bytes",
+           "slim_workspace_bytes_xcache",
            "slim_variant_for", "slim_decode", "vanilla_kv_decode", "slim_decode_xcache")
 VARIANT_NAMES = {1: "generic", 2: "fused_split", 3: "fused"}
 
@@ -35,6 +36,7 @@ class SlimOpts(ctypes.Structure):
         ("stream", ctypes.c_void_p),
         ("variant", ctypes.c_int),
         ("stage_ms", ctypes.POINTER(ctypes.c_float)),
+        ("rope_table", ctypes.c_void_p),
     ]
 
 
@@ -68,6 +70,8 @@ def load():
     lib.slim_prepare_wkv.argtypes = [vp, vp, vp, ci, cd]
     lib.slim_pack_weights.restype = ci
     lib.slim_pack_weights.argtypes = [vp, vp, ci, ci, ci]
+    lib.slim_rope_table.restype = ci
+    lib.slim_rope_table.argtypes = [vp, ci, ci, ctypes.c_double]
     lib.slim_workspace_bytes.restype = ctypes.c_size_t
     lib.slim_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
     lib.slim_workspace_bytes_xcache.restype = ctypes.c_size_t
@@ -116,6 +120,15 @@ def slim_pack_weights(W: np.ndarray, dtype: str) -> np.ndarray:
     return out
 
 
+def slim_rope_table(T: int, d_k: int, base: float = 10000.0) -> np.ndarray:
+    """(T, d_k/2, 2) float32 table of cos / sin(t * theta_j) for opts.rope_table."""
+    out = np.empty((T, max(d_k // 2, 0), 2), dtype=np.float32)
+    rc = load().slim_rope_table(out.ctypes.data, T, d_k, float(base))
+    if rc != SLIM_OK:
+        raise SlimError(rc, "slim_rope_table")
+    return out
+
+
 def slim_workspace_bytes(B, H, T, d, dtype: str) -> int:
     return int(load().slim_workspace_bytes(B, H, T, d, DTYPES[dtype]))
 
@@ -138,7 +151,7 @@ def to_device(a: np.ndarray):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
-def _opts(dtype, seq_lens, seq_lens_host, t_stride, workspace, variant, stage_ms=None):
+def _opts(dtype, seq_lens, seq_lens_host, t_stride, workspace, variant, stage_ms=None, rope_table=None):
     import torch
     o = SlimOpts()
     o.dtype = DTYPES[dtype]
@@ -155,6 +168,8 @@ def _opts(dtype, seq_lens, seq_lens_host, t_stride, workspace, variant, stage_ms
     o.variant = int(variant)
     if stage_ms is not None:      # a ctypes float array of MAX_STAGES entries, filled by the call
         o.stage_ms = ctypes.cast(stage_ms, ctypes.POINTER(ctypes.c_float))
+    if rope_table is not None:
+        o.rope_table = _dev_ptr(rope_table)
     return o, keep
 
 
@@ -170,8 +185,8 @@ def _dev_ptr(t):
 
 
 def slim_decode(q, Kcache, W_KV, out, B, H, T, d, dtype="bf16", seq_lens=None, seq_lens_host=None,
-                t_stride=0, workspace=None, variant=VARIANT_AUTO, stage_ms=None):
-    o, keep = _opts(dtype, seq_lens, seq_lens_host, t_stride, workspace, variant, stage_ms)
+                t_stride=0, workspace=None, variant=VARIANT_AUTO, stage_ms=None, rope_table=None):
+    o, keep = _opts(dtype, seq_lens, seq_lens_host, t_stride, workspace, variant, stage_ms, rope_table)
     rc = load().slim_decode(_dev_ptr(q), _dev_ptr(Kcache), _dev_ptr(W_KV), _dev_ptr(out), B, H, T, d,
                             ctypes.byref(o))
     if rc != SLIM_OK:
@@ -180,8 +195,8 @@ def slim_decode(q, Kcache, W_KV, out, B, H, T, d, dtype="bf16", seq_lens=None, s
 
 
 def vanilla_kv_decode(q, Kcache, Vcache, out, B, H, T, d, dtype="bf16", seq_lens=None,
-                      seq_lens_host=None, t_stride=0, workspace=None, variant=VARIANT_AUTO, stage_ms=None):
-    o, keep = _opts(dtype, seq_lens, seq_lens_host, t_stride, workspace, variant, stage_ms)
+                      seq_lens_host=None, t_stride=0, workspace=None, variant=VARIANT_AUTO, stage_ms=None, rope_table=None):
+    o, keep = _opts(dtype, seq_lens, seq_lens_host, t_stride, workspace, variant, stage_ms, rope_table)
     rc = load().vanilla_kv_decode(_dev_ptr(q), _dev_ptr(Kcache), _dev_ptr(Vcache), _dev_ptr(out),
                                   B, H, T, d, ctypes.byref(o))
     if rc != SLIM_OK:
@@ -190,8 +205,8 @@ def vanilla_kv_decode(q, Kcache, Vcache, out, B, H, T, d, dtype="bf16", seq_lens
 
 
 def slim_decode_xcache(q, X, W_K, W_V, out, B, H, T, d_model, d_k, dtype="bf16", seq_lens=None,
-                       seq_lens_host=None, t_stride=0, workspace=None, variant=VARIANT_AUTO, stage_ms=None):
-    o, keep = _opts(dtype, seq_lens, seq_lens_host, t_stride, workspace, variant, stage_ms)
+                       seq_lens_host=None, t_stride=0, workspace=None, variant=VARIANT_AUTO, stage_ms=None, rope_table=None):
+    o, keep = _opts(dtype, seq_lens, seq_lens_host, t_stride, workspace, variant, stage_ms, rope_table)
     rc = load().slim_decode_xcache(_dev_ptr(q), _dev_ptr(X), _dev_ptr(W_K), _dev_ptr(W_V),
                                    _dev_ptr(out), B, H, T, d_model, d_k, ctypes.byref(o))
     if rc != SLIM_OK:

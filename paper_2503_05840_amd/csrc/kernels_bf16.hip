@@ -423,7 +423,14 @@ __global__ __launch_bounds__(512) void project_mfma_kernel(const ProjArgs a) {
 // not wait for a gather without also waiting for every tile load issued before it.  A slot goes
 // back to the scoring wave through a counter in LDS.
 // ------------------------------------------------------------------------------------------------
-template <int NT>
+//
+// ROPE (RoPE appendix, option 1): the cache holds raw keys and row t sits at position t.  The
+// scoring wave rotates each key pair by its position for the score only; the tile that goes to
+// the summing wave stays raw.  With (y1, y2) = (x1 c + x2 s, -x1 s + x2 c) the pair's share of the
+// score is c (q1 x1 + q2 x2) + s (q1 x2 - q2 x1): two dot products of the raw pair, with (q1, q2)
+// and with (-q2, q1).  cos / sin of a lane's first row come from the table with the tile; the
+// following seven rows advance by the one-position rotation (table row 1), kept in registers.
+template <int NT, bool ROPE>
 __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const FusedArgs a) {
   constexpr int NP = FUSED_PAIRS, NS = FUSED_SLOTS, PD = FUSED_AHEAD;
   constexpr int NTHR = NP * 128;
@@ -589,6 +596,17 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
     // ========================= scoring waves: HBM -> registers -> LDS, scores, publish ===========
     Seg sg;
     int seen_consumed = 0;                          // last value read from consumed[p]
+    // rotary table: this lane's 4 column pairs start at pair li * 4 of the head
+    const float* rope_lane = nullptr;
+    const unsigned rope_pitch = (unsigned)(a.d_k / 2) * 8u;   // bytes per table row
+    float w1c[4], w1s[4];                           // rotation by one position
+    if constexpr (ROPE) {
+      rope_lane = a.rope + (size_t)(col_active ? li : 0) * 8;
+      const f32x4* r1 = reinterpret_cast<const f32x4*>(reinterpret_cast<const char*>(rope_lane) + (size_t)min(1, a.T - 1) * rope_pitch);
+      const f32x4 v0 = r1[0], v1 = r1[1];
+      w1c[0] = v0[0]; w1s[0] = v0[1]; w1c[1] = v0[2]; w1s[1] = v0[3];
+      w1c[2] = v1[0]; w1s[2] = v1[1]; w1c[3] = v1[2]; w1s[3] = v1[3];
+    }
     while (next_segment(sg)) {
       const int ntl = sg.ntl, len = sg.len;
       const uint16_t* Kb = sg.Kb;
@@ -605,6 +623,14 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
         qh[c] = __builtin_bit_cast(unsigned, hi);
         ql[c] = __builtin_bit_cast(unsigned, lo);
       }
+      unsigned ph[4], pl[4];                          // (-q2, q1) of every pair, same split
+      if constexpr (ROPE) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          ph[c] = ((qh[c] >> 16) ^ 0x8000u) | (qh[c] << 16);
+          pl[c] = ((ql[c] >> 16) ^ 0x8000u) | (ql[c] << 16);
+        }
+      }
       // (lanes without live columns re-read the unit's first columns: finite values that meet a zero
       //  query here and accumulator rows nobody reads in the summing wave)
       const unsigned lane_off = (unsigned)(rg * 8) * pitchB + (unsigned)(col_active ? mycol : ucol0) * 2u;
@@ -613,8 +639,15 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
       // scored) -> LDS slot, where the summing wave picks them up.  Direct-to-LDS loads are slower
       // to issue here, and a wave's LDS operations queue behind those it has in flight.
       u32x4 ts[PD][8];
-      auto load_tile = [&](u32x4 (&t)[8], int k) {
+      f32x4 tr[PD][2];                                // ROPE: {cos, sin} x 4 pairs at the lane's first row of the tile
+      auto load_tile = [&](u32x4 (&t)[8], f32x4 (&r)[2], int k) {
         const int st = __builtin_amdgcn_readfirstlane(sg.t0 + k * sg.stride);
+        if constexpr (ROPE) {
+          const int row = min(st * TILE_ROWS + rg * 8, a.T - 1);
+          const f32x4* rp = reinterpret_cast<const f32x4*>(reinterpret_cast<const char*>(rope_lane) + (size_t)row * rope_pitch);
+          r[0] = rp[0];
+          r[1] = rp[1];
+        }
         if ((st + 1) * TILE_ROWS <= len) {
           // full tile: uniform row base + per-lane 32-bit offset
           const char* tb = reinterpret_cast<const char*>(Kb) + (size_t)st * TILE_ROWS * pitchB;
@@ -634,19 +667,46 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
       // One tile; SI is k % PD as a type, so that the register set is a compile-time choice.
       auto step = [&](int k, auto SI) {
         u32x4 (&cur)[8] = ts[decltype(SI)::value];
+        f32x4 (&rot)[2] = tr[decltype(SI)::value];
         // ---- scores of this unit's heads for the lane's 8 rows (log2 domain) --------------------
         float sc[8];
+        if constexpr (ROPE) {
+          float cc[4] = {rot[0][0], rot[0][2], rot[1][0], rot[1][2]};
+          float ss[4] = {rot[0][1], rot[0][3], rot[1][1], rot[1][3]};
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          float d0 = 0.f, d1 = 0.f;
+          for (int j = 0; j < 8; ++j) {
+            float sj = 0.f;
 #pragma unroll
-          for (int c = 0; c < 4; ++c) {
-            const unsigned kw = cur[j][c];             // (a scalar copy: bit_cast of a vector element picks lane 0)
-            const bf16x2 kv = __builtin_bit_cast(bf16x2, kw);
-            d0 = __builtin_amdgcn_fdot2_f32_bf16(kv, __builtin_bit_cast(bf16x2, qh[c]), d0, false);
-            d1 = __builtin_amdgcn_fdot2_f32_bf16(kv, __builtin_bit_cast(bf16x2, ql[c]), d1, false);
+            for (int c = 0; c < 4; ++c) {
+              const unsigned kw = cur[j][c];
+              const bf16x2 kv = __builtin_bit_cast(bf16x2, kw);
+              float da = __builtin_amdgcn_fdot2_f32_bf16(kv, __builtin_bit_cast(bf16x2, qh[c]), 0.f, false);
+              da = __builtin_amdgcn_fdot2_f32_bf16(kv, __builtin_bit_cast(bf16x2, ql[c]), da, false);
+              float db = __builtin_amdgcn_fdot2_f32_bf16(kv, __builtin_bit_cast(bf16x2, ph[c]), 0.f, false);
+              db = __builtin_amdgcn_fdot2_f32_bf16(kv, __builtin_bit_cast(bf16x2, pl[c]), db, false);
+              sj = fmaf(cc[c], da, sj);
+              sj = fmaf(ss[c], db, sj);
+              if (j < 7) {                              // on to the next row's position
+                const float nc = fmaf(cc[c], w1c[c], -ss[c] * w1s[c]);
+                ss[c] = fmaf(ss[c], w1c[c], cc[c] * w1s[c]);
+                cc[c] = nc;
+              }
+            }
+            sc[j] = sj;
           }
-          sc[j] = d0 + d1;
+        } else {
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            float d0 = 0.f, d1 = 0.f;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+              const unsigned kw = cur[j][c];           // (a scalar copy: bit_cast of a vector element picks lane 0)
+              const bf16x2 kv = __builtin_bit_cast(bf16x2, kw);
+              d0 = __builtin_amdgcn_fdot2_f32_bf16(kv, __builtin_bit_cast(bf16x2, qh[c]), d0, false);
+              d1 = __builtin_amdgcn_fdot2_f32_bf16(kv, __builtin_bit_cast(bf16x2, ql[c]), d1, false);
+            }
+            sc[j] = d0 + d1;
+          }
         }
 #pragma unroll
         for (int j = 0; j < 8; ++j) {                 // sum over the head's lanes, all inside a 16-lane row
@@ -698,11 +758,11 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
         }
         // a hint for the summing wave (the words themselves carry the proof)
         if (lane == 0) __hip_atomic_store(&published[p], gk + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        if (k + PD < ntl) load_tile(cur, k + PD);
+        if (k + PD < ntl) load_tile(cur, rot, k + PD);
       };
 #pragma unroll
       for (int k = 0; k < PD; ++k)
-        if (k < ntl) load_tile(ts[k], k);
+        if (k < ntl) load_tile(ts[k], tr[k], k);
       for (int k = 0; k < ntl; k += PD) unrolled_steps<0, PD>(k, ntl, step);
       if (!by_seq) {
         // ---- end of this share (the barriers of the merge; the slots are its buffer) --------------
@@ -1018,8 +1078,13 @@ size_t fused_exch_bytes(const FusedGeom& g) {
 
 void launch_fused_stream(const FusedGeom& g, const FusedArgs& a, hipStream_t st) {
   dim3 grid(g.grid), block(g.NP * 128);
-  if (g.NT == 1) hipLaunchKernelGGL(fused_stream_kernel<1>, grid, block, 0, st, a);
-  else hipLaunchKernelGGL(fused_stream_kernel<2>, grid, block, 0, st, a);
+  if (a.rope) {
+    if (g.NT == 1) hipLaunchKernelGGL((fused_stream_kernel<1, true>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((fused_stream_kernel<2, true>), grid, block, 0, st, a);
+  } else {
+    if (g.NT == 1) hipLaunchKernelGGL((fused_stream_kernel<1, false>), grid, block, 0, st, a);
+    else hipLaunchKernelGGL((fused_stream_kernel<2, false>), grid, block, 0, st, a);
+  }
 }
 
 // Sequences per workgroup of the projection, in MFMA N tiles of 16 (1, 2 or 4).  One tile keeps the

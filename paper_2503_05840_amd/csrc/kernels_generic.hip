@@ -82,7 +82,7 @@ template <class ET>
 __global__ __launch_bounds__(256) void head_scores_kernel(
     const float* __restrict__ q, long q_bstride, const typename ET::elem* __restrict__ M,
     long m_bstride, long row_pitch, const int32_t* __restrict__ rows_per_b, int rows, int e, int H,
-    int d_k, float scale, float* __restrict__ S, long s_bstride) {
+    int d_k, float scale, float* __restrict__ S, long s_bstride, const float* __restrict__ rope) {
   extern __shared__ float smem[];
   constexpr int VEC = ET::VEC;
   const int nvec = e / VEC;
@@ -106,8 +106,20 @@ __global__ __launch_bounds__(256) void head_scores_kernel(
         float v[VEC];
         ET::load(row + ci * VEC, v);
         float acc = 0.f;
+        if (rope) {
+          // RoPE appendix, option 1: the raw row is rotated by its position r for the score only.
+          // With (y1, y2) = (x1 c + x2 s, -x1 s + x2 c):  q1 y1 + q2 y2 = c (q1 x1 + q2 x2) + s (q1 x2 - q2 x1).
+          const float* cs = rope + ((size_t)r * (d_k / 2) + (ci * VEC) % d_k / 2) * 2;
 #pragma unroll
-        for (int j = 0; j < VEC; ++j) acc = fmaf(v[j], q_s[ci * VEC + j], acc);
+          for (int j = 0; j < VEC; j += 2) {
+            const float q1 = q_s[ci * VEC + j], q2 = q_s[ci * VEC + j + 1];
+            acc = fmaf(cs[j], fmaf(q1, v[j], q2 * v[j + 1]), acc);
+            acc = fmaf(cs[j + 1], fmaf(q1, v[j + 1], -q2 * v[j]), acc);
+          }
+        } else {
+#pragma unroll
+          for (int j = 0; j < VEC; ++j) acc = fmaf(v[j], q_s[ci * VEC + j], acc);
+        }
         mypart[ci] = acc;
       }
     }
@@ -506,18 +518,18 @@ __global__ __launch_bounds__(256) void vanilla_combine_kernel(const float* __res
 // ------------------------------------------------------------------------------------------------
 void launch_head_scores(int dtype, const float* q, long q_bstride, const void* M, long m_bstride,
                         long row_pitch, const int32_t* rows_per_b, int rows, int e, int H, int d_k,
-                        float scale, float* S, long s_bstride, int B, hipStream_t st) {
+                        float scale, float* S, long s_bstride, const float* rope, int B, hipStream_t st) {
   dim3 grid((rows + HS_ROWS - 1) / HS_ROWS, B);
   const int nvec = e / vec_elems(dtype);
   const size_t smem = sizeof(float) * ((size_t)e + 4 * (size_t)nvec);
   if (dtype == DT_BF16) {
     (void)hipFuncSetAttribute((const void*)head_scores_kernel<BF16>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     hipLaunchKernelGGL(head_scores_kernel<BF16>, grid, dim3(256), smem, st, q, q_bstride,
-                       (const uint16_t*)M, m_bstride, row_pitch, rows_per_b, rows, e, H, d_k, scale, S, s_bstride);
+                       (const uint16_t*)M, m_bstride, row_pitch, rows_per_b, rows, e, H, d_k, scale, S, s_bstride, rope);
   } else {
     (void)hipFuncSetAttribute((const void*)head_scores_kernel<F32>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     hipLaunchKernelGGL(head_scores_kernel<F32>, grid, dim3(256), smem, st, q, q_bstride,
-                       (const float*)M, m_bstride, row_pitch, rows_per_b, rows, e, H, d_k, scale, S, s_bstride);
+                       (const float*)M, m_bstride, row_pitch, rows_per_b, rows, e, H, d_k, scale, S, s_bstride, rope);
   }
 }
 

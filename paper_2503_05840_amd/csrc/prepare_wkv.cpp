@@ -270,3 +270,19 @@ extern "C" int slim_pack_weights(const double* W, void* dst_host, int rows, int 
   }
   return SLIM_ERR_DTYPE;
 }
+
+// RoPE appendix: the one table both rotation directions use.
+extern "C" int slim_rope_table(float* table_host, int T, int d_k, double base) {
+  if (!table_host) return SLIM_ERR_ARG;
+  if (T < 1 || d_k < 2 || (d_k & 1) || !(base > 0.0)) return SLIM_ERR_SHAPE;
+  const int half = d_k / 2;
+  for (int j = 0; j < half; ++j) {
+    const double theta = std::pow(base, -2.0 * (double)j / (double)d_k);
+    for (long t = 0; t < T; ++t) {
+      const double ang = (double)t * theta;
+      table_host[((size_t)t * half + j) * 2 + 0] = (float)std::cos(ang);
+      table_host[((size_t)t * half + j) * 2 + 1] = (float)std::sin(ang);
+    }
+  }
+  return SLIM_OK;
+}

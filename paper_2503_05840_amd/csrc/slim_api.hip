@@ -147,7 +147,7 @@ class StageTimer {
 extern "C" const char* slim_strerror(int code) {
   switch (code) {
     case SLIM_OK: return "ok";
-    case SLIM_ERR_ARG: return "null pointer or negative size";
+    case SLIM_ERR_ARG: return "null pointer, negative size, or an option this entry point does not take";
     case SLIM_ERR_SHAPE: return "unsupported shape (d % H, d_k vs 16-byte vectors, T, t_stride)";
     case SLIM_ERR_DTYPE: return "dtype must be SLIM_F32 or SLIM_BF16";
     case SLIM_ERR_ALIGN: return "device pointer not 16-byte aligned";
@@ -202,6 +202,9 @@ extern "C" int slim_decode(const void* q, const void* Kcache, const void* W_KV, 
   int dtype; long t_stride;
   if (int rc = check_common(B, H, T, d, d_k, d, o, &dtype, &t_stride)) return rc;
   if (misaligned(q) || misaligned(Kcache) || misaligned(W_KV) || misaligned(out)) return SLIM_ERR_ALIGN;
+  const float* rope = o ? o->rope_table : nullptr;
+  if (rope && (d_k & 1)) return SLIM_ERR_SHAPE;
+  if (rope && misaligned(rope)) return SLIM_ERR_ALIGN;
   const Plan p = make_plan(B, H, T, d, d);
   char* ws;
   if (int rc = get_workspace(o, p.total, &ws)) return rc;
@@ -239,6 +242,7 @@ extern "C" int slim_decode(const void* q, const void* Kcache, const void* W_KV, 
       (void)hipGetDevice(&dev);
       fa.xcd_local = (g.gpx > 0 && xcd_round_robin(dev)) ? 1 : 0;
     }
+    fa.rope = rope;
     fa.Cpart = Cpart; fa.mpart = mpart; fa.lpart = lpart;
     fa.err = ctrl + CTRL_INTS - 1; fa.counters = ctrl; fa.ncounters = H * zb;
     ProjArgs pa{};
@@ -268,7 +272,7 @@ extern "C" int slim_decode(const void* q, const void* Kcache, const void* W_KV, 
     return launch_status();
   }
   launch_head_scores(dtype, (const float*)q, d, Kcache, kb, d, lens, T, d, H, d_k, scale, S,
-                     (long)H * T, B, st);
+                     (long)H * T, rope, B, st);
   tm.mark();
   launch_weighted_sum(dtype, S, Kcache, kb, d, lens, T, H, p.nsplit, Cpart, mpart, lpart, B, st);
   tm.mark();
@@ -283,6 +287,7 @@ extern "C" int slim_decode(const void* q, const void* Kcache, const void* W_KV, 
 extern "C" int vanilla_kv_decode(const void* q, const void* Kcache, const void* Vcache, void* out,
                                  int B, int H, int T, int d, const slim_opts* o) {
   if (!q || !Kcache || !Vcache || !out) return SLIM_ERR_ARG;
+  if (o && o->rope_table) return SLIM_ERR_ARG;        // a vanilla cache stores rotated keys
   if (H < 1 || d < 1 || d % H != 0) return SLIM_ERR_SHAPE;
   const int d_k = d / H;
   int dtype; long t_stride;
@@ -306,6 +311,7 @@ extern "C" int slim_decode_xcache(const void* q, const void* X, const void* W_K,
                                   void* out, int B, int H, int T, int d_model, int d_k,
                                   const slim_opts* o) {
   if (!q || !X || !W_K || !W_V || !out) return SLIM_ERR_ARG;
+  if (o && o->rope_table) return SLIM_ERR_ARG;        // no rotary positions in the X-cache scheme
   if (H < 1 || d_k < 1 || d_model < 1) return SLIM_ERR_SHAPE;
   const int e = H * d_k;
   int dtype; long t_stride;
@@ -353,7 +359,7 @@ extern "C" int slim_decode_xcache(const void* q, const void* X, const void* W_K,
   }
   // qt[b][h][c] = sum_j q[b][h d_k + j] W_K[c][h d_k + j]   ("rows" of W_K scored against q)
   launch_head_scores(dtype, (const float*)q, e, W_K, 0, e, nullptr, d_model, e, H, d_k, 1.0f, qt,
-                     (long)H * d_model, B, st);
+                     (long)H * d_model, nullptr, B, st);
   tm.mark();
   launch_dense_scores(dtype, qt, X, xb, d_model, lens, T, H, scale, S, B, st);
   tm.mark();

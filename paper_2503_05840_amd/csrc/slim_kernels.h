@@ -16,10 +16,11 @@ inline int elem_bytes(int dtype) { return dtype == DT_BF16 ? 2 : 4; }
 
 // S[b][h][r] = scale * sum_j q[b][h*d_k + j] * M[b][r][h*d_k + j]   for r < rows_b
 // (attention scores against a K-cache, eq. 2; also q_h W_K,h^T for the X-cache scheme with
-//  M := W_K, rows := d_model, m_bstride := 0).
+//  M := W_K, rows := d_model, m_bstride := 0).  rope: nullable [rows][d_k/2] {cos, sin}; when set,
+// row r is rotated by position r before the dot product (RoPE appendix, option 1).
 void launch_head_scores(int dtype, const float* q, long q_bstride, const void* M, long m_bstride,
                         long row_pitch, const int32_t* rows_per_b, int rows, int e, int H, int d_k,
-                        float scale, float* S, long s_bstride, int B, hipStream_t st);
+                        float scale, float* S, long s_bstride, const float* rope, int B, hipStream_t st);
 
 // S[b][h][t] = scale * sum_c qt[b][h][c] * X[b][t][c]   (X-cache scores, Fig. 4)
 void launch_dense_scores(int dtype, const float* qt, const void* X, long x_bstride, int d_model,
@@ -92,6 +93,7 @@ struct FusedArgs {
   int xcd_local;                      // 1: a group's workgroups share an XCD, the exchange stays in its L2
   // Single-launch mode: once all workgroups have written their partials (arrival flags, tagged
   // with launch_id), each takes a (head, row split) share of the merge + projection.
+  const float* rope;                  // nullable [T][d_k/2] {cos, sin}: rotate key rows by position for the scores
   int by_sequence;                    // > 0: by-sequence partition with this many shares per sequence
   int fuse;
   unsigned* flags;                    // [grid]

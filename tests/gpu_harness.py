@@ -47,9 +47,10 @@ class KCase:
     see the full batch; only the comparison is sampled."""
 
     def __init__(self, cfg: synth.Config, q_scale: float = 1.0, t_stride: int = 0, lens=None,
-                 oracle_seqs=None, need_v=True):
+                 oracle_seqs=None, need_v=True, rope_base=None):
         import torch
         self.cfg = cfg
+        self.rope_base = rope_base        # keys carry rotary positions (row t at position t)
         keep = None
         p = synth.make_problem(cfg)
         self.p = p
@@ -59,6 +60,7 @@ class KCase:
         el = np.float32 if cfg.dtype == "f32" else np.uint16
         Kh = np.zeros((B, ts, d), dtype=el)
         Vh = np.zeros((B, ts, d), dtype=el) if need_v else None
+        Krh = np.zeros((B, ts, d), dtype=el) if (need_v and rope_base) else None   # rotated keys, for the vanilla kernel
         self.kv64 = {}
         W_K32 = W_V32 = None
         for b, sq in enumerate(p.seqs):
@@ -71,19 +73,26 @@ class KCase:
                 Kh[b, :n] = synth.to_storage(K, cfg.dtype)
                 if need_v:
                     Vh[b, :n] = synth.to_storage(V, cfg.dtype)
+                if Krh is not None:
+                    Krh[b, :n] = synth.to_storage(orc.rope_encode(K, cfg.H, np.arange(n), rope_base), cfg.dtype)
             else:
                 if W_K32 is None:
                     W_K32, W_V32 = p.w.W_K.astype(np.float32), p.w.W_V.astype(np.float32)
                 X32 = X.astype(np.float32)
-                Kh[b, :n] = synth.to_storage(X32 @ W_K32, cfg.dtype)
+                K32 = X32 @ W_K32
+                Kh[b, :n] = synth.to_storage(K32, cfg.dtype)
                 if need_v:
                     Vh[b, :n] = synth.to_storage(X32 @ W_V32, cfg.dtype)
+                if Krh is not None:
+                    Krh[b, :n] = synth.to_storage(orc.rope_encode(K32, cfg.H, np.arange(n), rope_base), cfg.dtype)
             sq.X = None
         self.oracle_rows = sorted(self.kv64)
         wkv, self.rcond = binding.slim_prepare_wkv(p.w.W_K, p.w.W_V)
         self.t_stride = ts
         self.K = to_device(Kh)
         self.V = to_device(Vh) if need_v else None
+        self.K_rot = to_device(Krh) if Krh is not None else None
+        self.rope_table = to_device(binding.slim_rope_table(T, cfg.d_k, rope_base)) if rope_base else None
         self.Wkv = to_device(binding.slim_pack_weights(wkv, cfg.dtype))
         self.lens_dev = torch.from_numpy(self.lens).cuda()
         self.ragged = bool((self.lens != T).any())
@@ -96,7 +105,10 @@ class KCase:
         self.q = to_device(self.q64.astype(np.float32))
         self.ref = np.full((c.B, c.d), np.nan)
         for b, (K, V) in self.kv64.items():
-            self.ref[b] = orc.vanilla_decode(self.q64[b], K, V, c.H)
+            if self.rope_base:
+                self.ref[b] = orc.vanilla_decode_rope(self.q64[b], K, V, c.H, self.rope_base)
+            else:
+                self.ref[b] = orc.vanilla_decode(self.q64[b], K, V, c.H)
         return self
 
     def _kw(self, **kw):
@@ -110,6 +122,8 @@ class KCase:
         import torch
         c = self.cfg
         out = torch.full((c.B, c.d), float("nan"), device="cuda", dtype=torch.float32)
+        if self.rope_table is not None:
+            kw.setdefault("rope_table", self.rope_table)
         binding.slim_decode(self.q, self.K, self.Wkv, out, c.B, c.H, c.T, c.d, **self._kw(**kw))
         torch.cuda.synchronize()
         return out.cpu().numpy()
@@ -118,7 +132,8 @@ class KCase:
         import torch
         c = self.cfg
         out = torch.full((c.B, c.d), float("nan"), device="cuda", dtype=torch.float32)
-        binding.vanilla_kv_decode(self.q, self.K, self.V, out, c.B, c.H, c.T, c.d, **self._kw(**kw))
+        Kc = self.K_rot if self.rope_base else self.K       # a vanilla cache stores the rotated keys
+        binding.vanilla_kv_decode(self.q, Kc, self.V, out, c.B, c.H, c.T, c.d, **self._kw(**kw))
         torch.cuda.synchronize()
         return out.cpu().numpy()
 

@@ -70,3 +70,35 @@ def test_workspace_size_is_positive_and_monotone():
     b = binding.slim_workspace_bytes(2, 8, 256, 512, "f32")
     assert 0 < a < b
     assert binding.slim_workspace_bytes(0, 8, 256, 512, "f32") == 0
+
+
+def test_rope_table_against_the_oracle_angles_and_its_argument_checks():
+    """cos / sin of m * theta_j in fp32, pair-major, one table for both rotation directions."""
+    import numpy as np
+    from oracle import mha_oracle as orc
+    T, d_k, base = 3000, 96, 10000.0
+    tab = binding.slim_rope_table(T, d_k, base)
+    ang = orc.rope_angles(np.arange(T), d_k, base)
+    assert tab.shape == (T, d_k // 2, 2) and tab.dtype == np.float32
+    assert np.abs(tab[..., 0] - np.cos(ang)).max() <= 6e-8
+    assert np.abs(tab[..., 1] - np.sin(ang)).max() <= 6e-8
+    assert (tab[0, :, 0] == 1).all() and (tab[0, :, 1] == 0).all()
+    assert abs(tab[1, 0, 0] - np.cos(1.0)) < 1e-7          # theta_0 = 1 for any base
+    lib = binding.load()
+    buf = (ctypes.c_float * 8)()
+    assert lib.slim_rope_table(None, 1, 8, 10000.0) == -1
+    assert lib.slim_rope_table(buf, 1, 7, 10000.0) == -2
+    assert lib.slim_rope_table(buf, 0, 8, 10000.0) == -2
+    assert lib.slim_rope_table(buf, 1, 8, 0.0) == -2
+
+
+def test_rope_table_is_refused_where_it_has_no_meaning():
+    lib = binding.load()
+    o = binding.SlimOpts()
+    o.dtype = binding.SLIM_BF16
+    fake = ctypes.c_void_p(4096)
+    o.rope_table = 4096
+    assert lib.vanilla_kv_decode(fake, fake, fake, fake, 1, 8, 16, 512, ctypes.byref(o)) == -1
+    assert lib.slim_decode_xcache(fake, fake, fake, fake, fake, 1, 8, 16, 64, 16, ctypes.byref(o)) == -1
+    o.rope_table = 4100
+    assert lib.slim_decode(fake, fake, fake, fake, 1, 8, 16, 512, ctypes.byref(o)) == -4

@@ -79,6 +79,41 @@ def test_peaky_softmax(cases, name, factor):
     assert e <= TOL[k.cfg.dtype]
 
 
+ROPE_CASES = ["cfg0-exact", "cfg1-like", "cfg2-like-ragged", "cfg3-like", "f32-dk128", "dk96-multi-tile",
+              "two-heads-per-unit-multi-tile", "batch-by-sequence-ragged"]
+
+
+@pytest.mark.parametrize("name", ROPE_CASES)
+def test_slim_decode_with_rotary_keys_matches_oracle(cases, name):
+    """RoPE appendix, option 1: raw keys in the cache, rotated by position after the read for the
+    scores only.  Queries are scaled up so that the weights depend visibly on the rotation."""
+    say(f"[case] slim_decode + rope {name}")
+    k = cases(name, rope_base=10000.0, q_scale=30.0)
+    tol = TOL[k.cfg.dtype]
+    for vname, variant in VARIANTS.items():
+        e = k.err(k.run_slim(variant=variant))
+        say(f"  variant {vname}: rel err {e:.3e} (tol {tol})")
+        assert e <= tol
+    e = k.err(k.run_vanilla())                      # rotated keys stored, no table
+    say(f"  vanilla on rotated keys: {e:.3e}")
+    assert e <= tol
+    # the check has teeth: the same call without the table is far from this reference
+    e0 = k.err(k.run_slim(rope_table=None))
+    say(f"  without the table: {e0:.3e}")
+    assert e0 > 5 * tol
+
+
+def test_rotary_keys_other_base_near_uniform_weights_and_one_row():
+    say("[case] rope base 500, q x1")
+    k = KCase(synth.scaled(C[1], H=8, d=1024, T=1000), rope_base=500.0)
+    for variant in VARIANTS.values():
+        assert k.err(k.run_slim(variant=variant)) <= TOL["bf16"]
+    say("[case] rope T=1")
+    k = KCase(synth.scaled(C[1], H=4, d=512, T=1), rope_base=10000.0)
+    for variant in VARIANTS.values():
+        assert k.err(k.run_slim(variant=variant)) <= TOL["bf16"]
+
+
 def test_single_row_context_and_length_one_sequences():
     say("[case] T=1")
     k = KCase(synth.scaled(C[1], H=4, d=512, T=1))
