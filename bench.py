@@ -155,6 +155,8 @@ def main():
     ap.add_argument("--variant", default="auto", choices=["auto", "generic", "fused", "fused_split"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copies", type=int, default=0, help="K-cache copies to rotate over (0 = enough to exceed 512 MB)")
+    ap.add_argument("--rope", action="store_true",
+                    help="keys carry rotary positions: slim_decode rotates the raw cached keys for the scores (K-cache configs)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a few plain 128 MiB device copies (a kernel of known traffic, for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -207,11 +209,18 @@ def main():
     kw = dict(dtype=cfg.dtype, workspace=ws)
     if ragged:
         kw.update(seq_lens=lens_dev, seq_lens_host=lens)
+    rope_bytes = 0.0
+    if args.rope:
+        # vanilla keeps reading the same buffers: its cache would hold the rotated keys, same bytes
+        kw_rope = dict(rope_table=to_device(binding.slim_rope_table(T, d_k, 10000.0)))
+        rope_bytes = float(T) * (d_k // 2) * 8
+    else:
+        kw_rope = {}
     variant = {"auto": binding.VARIANT_AUTO, "generic": binding.VARIANT_GENERIC,
                "fused": binding.VARIANT_FUSED, "fused_split": binding.VARIANT_FUSED_SPLIT}[args.variant]
 
     def slim(i, **extra):
-        binding.slim_decode(q, Ks[i % ncopies], Wkv, out, B, H, T, d, variant=variant, **kw, **extra)
+        binding.slim_decode(q, Ks[i % ncopies], Wkv, out, B, H, T, d, variant=variant, **kw, **kw_rope, **extra)
 
     def vanilla(i, **extra):
         binding.vanilla_kv_decode(q, Ks[i % ncopies], Vs[i % ncopies], out_v, B, H, T, d, **kw, **extra)
@@ -263,13 +272,13 @@ def main():
     if one_launch:
         names = ["fused_stream"]
     dom = int(np.argmax(acc[:len(names)]))
-    alg_bytes = {"project": w_bytes, "project_mfma": w_bytes}.get(names[dom], k_bytes + (w_bytes if one_launch else 0.0))
+    alg_bytes = {"project": w_bytes, "project_mfma": w_bytes}.get(names[dom], k_bytes + rope_bytes + (w_bytes if one_launch else 0.0))
     kern_s = acc[dom] * 1e-3
     achieved = alg_bytes / kern_s / 1e9
     roofline = {"bound": "hbm", "kernel": names[dom] + (" (one launch: stream + merge + projection)" if one_launch else ""),
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                "traffic": measured_traffic(cfg.index, names[dom]),
+                "traffic": None if args.rope else measured_traffic(cfg.index, names[dom]),
                 "algorithmic_bytes": alg_bytes, "kernel_ms": round(float(acc[dom]), 5),
                 "stage_ms": {n: round(float(acc[i]), 5) for i, n in enumerate(names)}}
 
@@ -281,7 +290,7 @@ def main():
         log("[bench] timing the CPU oracle (decode step only, fp64 K and V resident) ...")
         n0 = int(lens[0])
         Kc, Vc = K64[:n0], V64[:n0]
-        ref0 = orc.vanilla_decode(p.q[0], Kc, Vc, H)
+        ref0 = orc.vanilla_decode_rope(p.q[0], Kc, Vc, H) if args.rope else orc.vanilla_decode(p.q[0], Kc, Vc, H)
         slim(0)
         torch.cuda.synchronize()
         got0 = out[0].cpu().numpy().astype(np.float64).reshape(H, d_k)
@@ -305,7 +314,8 @@ def main():
         "value": round(B / (ms * 1e-3), 2), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms, 5), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
-        "config": {"workload": f"configs[{cfg.index}] {cfg.name}", "B": B, "H": H, "d": d, "d_k": d_k, "T": T,
+        "config": {"workload": f"configs[{cfg.index}] {cfg.name}" + (" + rotary keys (RoPE option 1, raw keys cached)" if args.rope else ""),
+                   "B": B, "H": H, "d": d, "d_k": d_k, "T": T,
                    "sum_len": int(lens.sum()), "variant": which, "k_cache_copies_rotated": ncopies},
         "k_cache_gbps": round(k_bytes / (ms * 1e-3) / 1e9, 1),
         "k_cache_frac_of_hbm_peak": round(k_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
