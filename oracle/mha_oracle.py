@@ -25,6 +25,9 @@ What it computes (row-vector convention, W[in][out], head i = column block
                              against the rotated keys, values untouched.
   * `slim_option2_rope`   -- option 1 of the RoPE appendix on top of eq. 7 option 2: the cache
                              holds raw keys, rotated after reading for the scores only.
+  * `attention_block`     -- the whole attention block of one generated token (Fig. 1 / Table 2's
+                             projection column): q, k, v from the token's input, the new rows
+                             appended to the caches, eq. 2 over old and new rows, then W_O.
   * `mha_ops_reads`       -- App. B / Table 2 op and read counts, by enumerating matmuls.
   * `whisper_reads_per_token` -- the closed-form arithmetic of the Whisper table.
 
@@ -186,6 +189,30 @@ def slim_option2_rope(q, K, W_KV, h, base=10000.0):
         cols = slice(i * d_k, (i + 1) * d_k)
         out[cols] = (P[i] @ K) @ W_KV[:, cols]
     return out
+
+
+# --------------------------------------------------------------------------------------
+# the steps either side of the decode step: one generated token through the attention block
+# --------------------------------------------------------------------------------------
+def attention_block(x, K_cache, V_cache, W_Q, W_K, W_V, W_O, h, rope_base=None):
+    """One token with input row x (d,) through multi-head attention, vanilla and in fp64.
+
+    q = x W_Q, k = x W_K, v = x W_V (eq. 3-5 for one row); k and v are stored after the n rows
+    already cached and all n + 1 rows are read back (the generate-phase description under Fig. 2);
+    heads as in eq. 2; the concatenation goes through W_O (eq. 1).  With rope_base, the new token
+    sits at position n: its query and key are rotated there, cached key row t at position t.
+    Returns (y, k, v): the block output (d,) and the raw new rows."""
+    x = np.asarray(x, np.float64)
+    K_cache = np.asarray(K_cache, np.float64)
+    V_cache = np.asarray(V_cache, np.float64)
+    n = K_cache.shape[0]
+    q, k, v = x @ W_Q, x @ W_K, x @ W_V
+    K = np.vstack([K_cache, k[None, :]])
+    V = np.vstack([V_cache, v[None, :]])
+    if rope_base is not None:
+        q = rope_encode(q[None, :], h, [n], rope_base)[0]
+        K = rope_encode(K, h, np.arange(n + 1), rope_base)
+    return vanilla_decode(q, K, V, h) @ np.asarray(W_O, np.float64), k, v
 
 
 # --------------------------------------------------------------------------------------

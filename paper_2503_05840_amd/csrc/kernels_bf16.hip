@@ -193,6 +193,8 @@ __device__ __forceinline__ void project_work(const ProjArgs& a, int h, int cs, i
 
   const int lph = a.d_k / 8;
   const bool col_active = idx < lph;
+  // partial p of head h starts at ((p * H) + h) * rows; mode 2 has one row of x per sequence for all heads
+  const int hmul = a.mode == 2 ? 1 : a.H, hadd = a.mode == 2 ? 0 : h;
   const uint16_t* Wh = a.W + (size_t)h * a.d_k + idx * 8;
   const int c_lo = cs * a.crows, c_hi = min(a.rows, c_lo + a.crows);
   const int ntile = (c_hi - c_lo + TILE_ROWS - 1) / TILE_ROWS;
@@ -220,6 +222,9 @@ __device__ __forceinline__ void project_work(const ProjArgs& a, int h, int cs, i
       const int gf = prefix[b] / Qt, gl = (prefix[b + 1] - 1) / Qt;
       p0 = b + gf;
       np = gl - gf + 1;
+    } else if (a.mode == 2) {                        // plain product: "partial" b is row b of x, weight 1
+      if (lane == 0) { sm.wpid[bl][0] = 1.f; sm.pid0s[bl] = b; sm.nps[bl] = 1; }
+      continue;
     } else {
       p0 = b * a.nsplit;
       np = a.nsplit;
@@ -269,7 +274,7 @@ __device__ __forceinline__ void project_work(const ProjArgs& a, int h, int cs, i
 #pragma unroll
             for (int q = 0; q < 8; ++q) {
               const int pp = min(pb + q, np - 1);
-              const float* src = a.Cpart + ((size_t)(p0 + pp) * a.H + h) * a.rows + c;
+              const float* src = a.Cpart + ((size_t)(p0 + pp) * hmul + hadd) * a.rows + c;
               asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(x[q][0]) : "v"(src) : "memory");
               asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(x[q][1]) : "v"(src + 4) : "memory");
             }
@@ -290,7 +295,7 @@ __device__ __forceinline__ void project_work(const ProjArgs& a, int h, int cs, i
         } else {
           for (int p = 0; p < np; ++p) {
             const float wgt = sm.wpid[bl][p];
-            const float* src = a.Cpart + ((size_t)(p0 + p) * a.H + h) * a.rows + c;
+            const float* src = a.Cpart + ((size_t)(p0 + p) * hmul + hadd) * a.rows + c;
             const float4 x0 = *reinterpret_cast<const float4*>(src);
             const float4 x1 = *reinterpret_cast<const float4*>(src + 4);
             cn[0] = fmaf(wgt, x0.x, cn[0]); cn[1] = fmaf(wgt, x0.y, cn[1]);

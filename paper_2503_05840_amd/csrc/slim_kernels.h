@@ -68,7 +68,8 @@ struct ProjArgs {
   int* counters; const int* err; unsigned launch_id;
   const int32_t* seq_lens;
   int B, T, H, d_k, rows, e;
-  int NG, nsplit, mode;               // mode 0: partials laid out by the stream kernel; 1: [b][nsplit]
+  int NG, nsplit, mode;               // mode 0: partials laid out by the stream kernel; 1: [b][nsplit];
+                                      // 2: no partials, Cpart = x [B][rows] shared by all heads: out = x W
   float mscale;                       // 1 for log2-domain maxima, log2(e) for natural-log ones
   int csw, crows;                     // row splits of W across workgroups, rows per split
 };

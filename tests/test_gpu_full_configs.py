@@ -34,6 +34,21 @@ def test_config1_codellama_16k_full():
     assert e50 <= TOL["bf16"]
 
 
+def test_config1_with_rotary_keys_full():
+    """Positions up to 16383 (angles far past 2 pi at the first frequencies), one-launch mode."""
+    say("[case] config 1 full size + rotary keys (raw keys cached, q x30)")
+    k = KCase(C[1], rope_base=10000.0, q_scale=30.0, need_v=False)
+    a = k.run_slim()
+    e = k.err(a)
+    say(f"  slim rel err {e:.3e}")
+    assert e <= TOL["bf16"]
+    assert np.array_equal(a, k.run_slim())
+    eg = k.err(k.run_slim(variant=binding.VARIANT_GENERIC))
+    say(f"  slim (generic kernels) rel err {eg:.3e}")
+    assert eg <= TOL["bf16"]
+    assert k.err(k.run_slim(rope_table=None)) > 5 * TOL["bf16"]
+
+
 def test_config3_whisper_cross_attention_full():
     say("[case] config 3 full size (B=64 H=20 d=1280 T=1500 bf16)")
     k = KCase(C[3])

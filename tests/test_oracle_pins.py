@@ -392,3 +392,66 @@ def test_rope_option1_on_raw_keys_equals_vanilla_with_rotated_keys(cfg0_problem)
     assert np.abs(got - ref).max() <= 1e-10 * np.abs(ref).max()
     plain = orc.vanilla_decode(q, K, V, h)
     assert np.abs(plain - ref).max() > 1e-2 * np.abs(ref).max()   # the rotation is not a no-op here
+
+
+# ------------------------------------------------------------------------------------------
+# the whole attention block of one generated token
+# ------------------------------------------------------------------------------------------
+def _block_problem(seed, n, d, h):
+    rng = np.random.default_rng(seed)
+    W = [rng.standard_normal((d, d)) / math.sqrt(d) for _ in range(4)]
+    X = rng.standard_normal((n, d))
+    x = rng.standard_normal(d)
+    return x, X, W
+
+
+def test_block_brute_force_with_python_floats():
+    """q, k, v, the appended rows, eq. 2 with naive exp, concat, W_O -- all in loops."""
+    n, d, h = 4, 6, 2
+    x, X, (W_Q, W_K, W_V, W_O) = _block_problem(21, n, d, h)
+    d_k = d // h
+    rows = [list(r) for r in X] + [list(x)]                      # inputs of the cached rows, then the new token
+    K = [[sum(r[a] * W_K[a][c] for a in range(d)) for c in range(d)] for r in rows]
+    V = [[sum(r[a] * W_V[a][c] for a in range(d)) for c in range(d)] for r in rows]
+    q = [sum(x[a] * W_Q[a][c] for a in range(d)) for c in range(d)]
+    cat = [0.0] * d
+    for i in range(h):
+        w = [math.exp(sum(q[i * d_k + j] * K[t][i * d_k + j] for j in range(d_k)) / math.sqrt(d_k)) for t in range(n + 1)]
+        for j in range(d_k):
+            cat[i * d_k + j] = sum(w[t] * V[t][i * d_k + j] for t in range(n + 1)) / sum(w)
+    want = [sum(cat[a] * W_O[a][c] for a in range(d)) for c in range(d)]
+    y, k, v = orc.attention_block(x, X @ W_K, X @ W_V, W_Q, W_K, W_V, W_O, h)
+    np.testing.assert_allclose(y, want, rtol=1e-12)
+    np.testing.assert_allclose(k, K[n], rtol=1e-12)
+    np.testing.assert_allclose(v, V[n], rtol=1e-12)
+
+
+def test_block_with_an_empty_cache_is_two_products():
+    """No cached rows: the one weight is 1, so y = x W_V W_O whatever W_Q, W_K and positions are."""
+    x, X, (W_Q, W_K, W_V, W_O) = _block_problem(22, 0, 8, 2)
+    empty = np.zeros((0, 8))
+    for base in (None, 10000.0):
+        y, _, _ = orc.attention_block(x, empty, empty, W_Q, W_K, W_V, W_O, 2, rope_base=base)
+        np.testing.assert_allclose(y, x @ W_V @ W_O, rtol=1e-12)
+
+
+def test_block_with_zero_query_weights_averages_old_and_new_values():
+    n, d, h = 7, 8, 4
+    x, X, (W_Q, W_K, W_V, W_O) = _block_problem(23, n, d, h)
+    y, _, v = orc.attention_block(x, X @ W_K, X @ W_V, np.zeros((d, d)), W_K, W_V, W_O, h)
+    mean_v = (np.sum(X @ W_V, axis=0) + v) / (n + 1)
+    np.testing.assert_allclose(y, mean_v @ W_O, rtol=1e-12)
+
+
+def test_block_is_the_decode_step_between_its_projections():
+    """attention_block = vanilla_decode over the extended caches, then W_O; with rotary keys the new
+    token sits at position n and only the query/key side is rotated."""
+    n, d, h = 9, 16, 2
+    x, X, (W_Q, W_K, W_V, W_O) = _block_problem(24, n, d, h)
+    Xe = np.vstack([X, x[None, :]])
+    y, _, _ = orc.attention_block(x, X @ W_K, X @ W_V, W_Q, W_K, W_V, W_O, h)
+    np.testing.assert_allclose(y, orc.vanilla_decode_from_x(x @ W_Q, Xe, W_K, W_V, h) @ W_O, rtol=1e-12)
+    yr, _, _ = orc.attention_block(x, X @ W_K, X @ W_V, W_Q, W_K, W_V, W_O, h, rope_base=100.0)
+    qr = orc.rope_encode((x @ W_Q)[None, :], h, [n], 100.0)[0]
+    np.testing.assert_allclose(yr, orc.vanilla_decode_rope(qr, Xe @ W_K, Xe @ W_V, h, 100.0) @ W_O, rtol=1e-12)
+    assert np.abs(yr - y).max() > 1e-3 * np.abs(y).max()
