@@ -152,6 +152,34 @@ int slim_decode_xcache(const void* q, const void* X, const void* W_K, const void
                        void* out, int B, int H, int T, int d_model, int d_k,
                        const slim_opts* opts);
 
+/* ---- the steps either side of the decode step ------------------------------------------- */
+
+/* One generated token per sequence through the whole attention block (Fig. 1; the projection
+ * column of Table 2), slim: q = x W_Q and k = x W_K (eq. 3, 4 for one row), k stored as row
+ * seq_lens[b]-1 of the K-cache (the generate-phase description under Fig. 2), slim_decode over
+ * all seq_lens[b] rows, then the concatenated heads through W_O (eq. 1).  No W_V, no V-cache.
+ *   x      : device fp32 [B][d]            input rows of the new tokens
+ *   W_Q, W_K, W_KV, W_O : device dtype [d][d] row-major (slim_pack_weights)
+ *   Kcache : device dtype [B][t_stride][d], rows [0, seq_lens[b]-1) valid on entry; row
+ *            seq_lens[b]-1 is WRITTEN (rounded to dtype) and then read with the others
+ *   y      : device fp32 [B][d], written
+ *   T and opts->seq_lens count the rows AFTER the append (1 <= seq_lens[b] <= T <= t_stride).
+ * With opts->rope_table the new token sits at position seq_lens[b]-1: q is rotated there, the
+ * key is stored raw and rotated for the scores as in slim_decode.
+ * Scratch: slim_workspace_bytes_block(), else library-owned.  opts->stage_ms, when set, receives
+ * three figures: projections + append, decode step, output projection. */
+size_t slim_workspace_bytes_block(int B, int H, int T, int d, int dtype);
+int slim_attention_block(const void* x, const void* W_Q, const void* W_K, const void* W_KV,
+                         const void* W_O, void* Kcache, void* y, int B, int H, int T, int d,
+                         const slim_opts* opts);
+
+/* The same block the vanilla way (Table 2 row "Vanilla"): also v = x W_V (eq. 5), k and v stored
+ * in both caches (with opts->rope_table the stored key is the rotated one), vanilla_kv_decode,
+ * W_O.  The same-GPU comparison for the block. */
+int vanilla_attention_block(const void* x, const void* W_Q, const void* W_K, const void* W_V,
+                            const void* W_O, void* Kcache, void* Vcache, void* y, int B, int H,
+                            int T, int d, const slim_opts* opts);
+
 #ifdef __cplusplus
 }
 #endif

@@ -20,7 +20,7 @@ VARIANT_AUTO, VARIANT_GENERIC, VARIANT_FUSED_SPLIT, VARIANT_FUSED = 0, 1, 2, 3
 DTYPES = {"f32": SLIM_F32, "bf16": SLIM_BF16}
 
 EXPORTS = ("slim_strerror", "slim_prepare_wkv", "slim_pack_weights", "slim_rope_table", "slim_workspace_bytes",
-           "slim_workspace_bytes_xcache",
+           "slim_workspace_bytes_xcache", "slim_workspace_bytes_block", "slim_attention_block", "vanilla_attention_block",
            "slim_variant_for", "slim_decode", "vanilla_kv_decode", "slim_decode_xcache")
 VARIANT_NAMES = {1: "generic", 2: "fused_split", 3: "fused"}
 
@@ -85,6 +85,12 @@ def load():
     lib.vanilla_kv_decode.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, op]
     lib.slim_decode_xcache.restype = ci
     lib.slim_decode_xcache.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, op]
+    lib.slim_workspace_bytes_block.restype = ctypes.c_size_t
+    lib.slim_workspace_bytes_block.argtypes = [ci, ci, ci, ci, ci]
+    lib.slim_attention_block.restype = ci
+    lib.slim_attention_block.argtypes = [vp, vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, op]
+    lib.vanilla_attention_block.restype = ci
+    lib.vanilla_attention_block.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, op]
     _lib = lib
     return lib
 
@@ -135,6 +141,10 @@ def slim_workspace_bytes(B, H, T, d, dtype: str) -> int:
 
 def slim_workspace_bytes_xcache(B, H, T, d_model, d_k, dtype: str) -> int:
     return int(load().slim_workspace_bytes_xcache(B, H, T, d_model, d_k, DTYPES[dtype]))
+
+
+def slim_workspace_bytes_block(B, H, T, d, dtype: str) -> int:
+    return int(load().slim_workspace_bytes_block(B, H, T, d, DTYPES[dtype]))
 
 
 def auto_variant_name(B, H, T, d, dtype: str) -> str:
@@ -212,3 +222,25 @@ def slim_decode_xcache(q, X, W_K, W_V, out, B, H, T, d_model, d_k, dtype="bf16",
     if rc != SLIM_OK:
         raise SlimError(rc, "slim_decode_xcache")
     return out
+
+
+def slim_attention_block(x, W_Q, W_K, W_KV, W_O, Kcache, y, B, H, T, d, dtype="bf16", seq_lens=None,
+                         seq_lens_host=None, t_stride=0, workspace=None, variant=VARIANT_AUTO, stage_ms=None,
+                         rope_table=None):
+    o, keep = _opts(dtype, seq_lens, seq_lens_host, t_stride, workspace, variant, stage_ms, rope_table)
+    rc = load().slim_attention_block(_dev_ptr(x), _dev_ptr(W_Q), _dev_ptr(W_K), _dev_ptr(W_KV), _dev_ptr(W_O),
+                                     _dev_ptr(Kcache), _dev_ptr(y), B, H, T, d, ctypes.byref(o))
+    if rc != SLIM_OK:
+        raise SlimError(rc, "slim_attention_block")
+    return y
+
+
+def vanilla_attention_block(x, W_Q, W_K, W_V, W_O, Kcache, Vcache, y, B, H, T, d, dtype="bf16", seq_lens=None,
+                            seq_lens_host=None, t_stride=0, workspace=None, variant=VARIANT_AUTO, stage_ms=None,
+                            rope_table=None):
+    o, keep = _opts(dtype, seq_lens, seq_lens_host, t_stride, workspace, variant, stage_ms, rope_table)
+    rc = load().vanilla_attention_block(_dev_ptr(x), _dev_ptr(W_Q), _dev_ptr(W_K), _dev_ptr(W_V), _dev_ptr(W_O),
+                                        _dev_ptr(Kcache), _dev_ptr(Vcache), _dev_ptr(y), B, H, T, d, ctypes.byref(o))
+    if rc != SLIM_OK:
+        raise SlimError(rc, "vanilla_attention_block")
+    return y

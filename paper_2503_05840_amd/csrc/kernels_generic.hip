@@ -35,6 +35,9 @@ struct F32 {
     const float2 x = *reinterpret_cast<const float2*>(p);
     a = x.x; b = x.y;
   }
+  static __device__ __forceinline__ void store_two(elem* p, float a, float b) {
+    *reinterpret_cast<float2*>(p) = make_float2(a, b);
+  }
 };
 
 struct BF16 {
@@ -61,6 +64,10 @@ struct BF16 {
   static __device__ __forceinline__ void two(const elem* p, float& a, float& b) {
     const uint32_t x = *reinterpret_cast<const uint32_t*>(p);
     a = __uint_as_float(x << 16); b = __uint_as_float(x & 0xffff0000u);
+  }
+  static __device__ __forceinline__ void store_two(elem* p, float a, float b) {   // round to nearest even
+    const uint32_t lo = __builtin_bit_cast(uint16_t, (__bf16)a), hi = __builtin_bit_cast(uint16_t, (__bf16)b);
+    *reinterpret_cast<uint32_t*>(p) = lo | (hi << 16);
   }
 };
 
@@ -355,6 +362,43 @@ __global__ __launch_bounds__(256) void project_kernel(const float* __restrict__ 
 }
 
 // ------------------------------------------------------------------------------------------------
+// append: the new token's projected key (and value) row of every sequence goes into the cache at
+// row len_b - 1 (the generate-phase description under Fig. 2).  One thread per adjacent column pair.
+// With a rotary table the token sits at position len_b - 1: its query is rotated there in place,
+// and its key too when the cache stores rotated keys (vanilla); a slim cache keeps the raw key.
+// ------------------------------------------------------------------------------------------------
+template <class ET>
+__global__ __launch_bounds__(256) void append_kernel(
+    const float* __restrict__ knew, const float* __restrict__ vnew, typename ET::elem* __restrict__ K,
+    typename ET::elem* __restrict__ V, long bstride, const int32_t* __restrict__ seq_lens, int T, int d,
+    int d_k, const float* __restrict__ rope, float* __restrict__ q, int rotate_k) {
+  const int b = blockIdx.y;
+  const int col = (blockIdx.x * 256 + threadIdx.x) * 2;
+  const int len = seq_len_of(seq_lens, b, T);
+  if (col >= d || len < 1) return;
+  const int pos = len - 1;
+  float k1 = knew[(long)b * d + col], k2 = knew[(long)b * d + col + 1];
+  if (rope) {
+    const float* cs = rope + ((size_t)pos * (d_k / 2) + (col % d_k) / 2) * 2;
+    const float c = cs[0], s = cs[1];
+    const float q1 = q[(long)b * d + col], q2 = q[(long)b * d + col + 1];
+    q[(long)b * d + col] = fmaf(q1, c, q2 * s);
+    q[(long)b * d + col + 1] = fmaf(q2, c, -q1 * s);
+    if (rotate_k) {
+      const float r1 = fmaf(k1, c, k2 * s), r2 = fmaf(k2, c, -k1 * s);
+      k1 = r1; k2 = r2;
+    }
+  }
+  ET::store_two(K + b * bstride + (long)pos * d + col, k1, k2);
+  if (vnew) ET::store_two(V + b * bstride + (long)pos * d + col, vnew[(long)b * d + col], vnew[(long)b * d + col + 1]);
+}
+
+__global__ __launch_bounds__(256) void zero_ints_kernel(int* __restrict__ p, int n) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n) p[i] = 0;
+}
+
+// ------------------------------------------------------------------------------------------------
 // vanilla K+V decode (flash-decoding layout): one wave per (b, split, head); 16 lanes span the
 // head's d_k columns in 16-byte vectors (NPASS vectors per lane), the 4 lane groups take
 // alternating rows with their own running (m, l, acc), merged at the end.
@@ -572,6 +616,22 @@ void launch_project(int dtype, const float* Cn, const void* W, int rows, int e, 
     hipLaunchKernelGGL(project_kernel<BF16>, grid, dim3(256), 0, st, Cn, (const uint16_t*)W, rows, e, H, d_k, out, B);
   else
     hipLaunchKernelGGL(project_kernel<F32>, grid, dim3(256), 0, st, Cn, (const float*)W, rows, e, H, d_k, out, B);
+}
+
+void launch_append(int dtype, const float* knew, const float* vnew, void* K, void* V, long bstride,
+                   const int32_t* seq_lens, int T, int d, int d_k, const float* rope, float* q, int rotate_k,
+                   int B, hipStream_t st) {
+  dim3 grid((d / 2 + 255) / 256, B);
+  if (dtype == DT_BF16)
+    hipLaunchKernelGGL(append_kernel<BF16>, grid, dim3(256), 0, st, knew, vnew, (uint16_t*)K, (uint16_t*)V,
+                       bstride, seq_lens, T, d, d_k, rope, q, rotate_k);
+  else
+    hipLaunchKernelGGL(append_kernel<F32>, grid, dim3(256), 0, st, knew, vnew, (float*)K, (float*)V,
+                       bstride, seq_lens, T, d, d_k, rope, q, rotate_k);
+}
+
+void launch_zero_ints(int* p, int n, hipStream_t st) {
+  hipLaunchKernelGGL(zero_ints_kernel, dim3((n + 255) / 256), dim3(256), 0, st, p, n);
 }
 
 void launch_vanilla(int dtype, const float* q, const void* K, const void* V, long bstride,

@@ -372,3 +372,117 @@ extern "C" int slim_decode_xcache(const void* q, const void* X, const void* W_K,
   tm.finish();
   return launch_status();
 }
+
+// ---- the steps either side of the decode step ----------------------------------------------------
+namespace {
+
+struct BlockBufs { size_t off_q, off_k, off_v, off_attn, total; };
+
+BlockBufs block_layout(const Plan& p, int B, int d) {
+  BlockBufs b;
+  size_t o = p.total;
+  const size_t row = up(sizeof(float) * (size_t)B * d);
+  b.off_q = o; o += row;
+  b.off_k = o; o += row;
+  b.off_v = o; o += row;
+  b.off_attn = o; o += row;
+  b.total = o;
+  return b;
+}
+
+// out [B][d] = x [B][d] W [d][d]
+void dense(bool fast, int dtype, const float* x, const void* W, float* out, int B, int H, int d, char* ws,
+           const Plan& p, hipStream_t st) {
+  if (!fast) {
+    launch_project(dtype, x, W, d, d, 1, d, out, B, st);       // one "head" as wide as the matrix
+    return;
+  }
+  ProjArgs pa{};
+  pa.Cpart = x; pa.W = (const uint16_t*)W; pa.out = out; pa.outpart = (float*)(ws + p.off_outpart);
+  pa.counters = (int*)(ws + p.off_ctrl);
+  pa.B = B; pa.T = 1; pa.H = H; pa.d_k = d / H; pa.rows = d; pa.e = d;
+  pa.nsplit = 1; pa.mode = 2; pa.mscale = 1.0f; pa.csw = p.csw;
+  launch_project_mfma(pa, st);
+}
+
+struct BlockCall {
+  const void *x, *W_Q, *W_K, *W_V, *W_second, *W_O;   // W_second: W_KV (slim) or unused (vanilla)
+  void *Kcache, *Vcache, *y;
+};
+
+int attention_block(bool slim_path, const BlockCall& c, int B, int H, int T, int d, const slim_opts* o) {
+  if (!c.x || !c.W_Q || !c.W_K || !c.W_O || !c.Kcache || !c.y) return SLIM_ERR_ARG;
+  if (slim_path ? !c.W_second : (!c.W_V || !c.Vcache)) return SLIM_ERR_ARG;
+  if (H < 1 || d < 1 || d % H != 0) return SLIM_ERR_SHAPE;
+  const int d_k = d / H;
+  int dtype; long t_stride;
+  if (int rc = check_common(B, H, T, d, d_k, d, o, &dtype, &t_stride)) return rc;
+  if (d_k & 1) return SLIM_ERR_SHAPE;
+  if (!slim_path && d_k / vec_elems(dtype) > 32) return SLIM_ERR_SHAPE;
+  const void* ptrs[] = {c.x, c.W_Q, c.W_K, c.W_V, c.W_second, c.W_O, c.Kcache, c.Vcache, c.y, o ? o->rope_table : nullptr};
+  for (const void* q : ptrs) if (q && misaligned(q)) return SLIM_ERR_ALIGN;
+  const Plan p = make_plan(B, H, T, d, d);
+  const BlockBufs bb = block_layout(p, B, d);
+  char* ws;
+  if (int rc = get_workspace(o, bb.total, &ws)) return rc;
+  hipStream_t st = o ? (hipStream_t)o->stream : nullptr;
+  const int32_t* lens = o ? o->seq_lens : nullptr;
+  const float* rope = o ? o->rope_table : nullptr;
+  float* q = (float*)(ws + bb.off_q);
+  float* knew = (float*)(ws + bb.off_k);
+  float* vnew = (float*)(ws + bb.off_v);
+  float* attn = (float*)(ws + bb.off_attn);
+  const int variant = pick_variant(o ? o->variant : SLIM_VARIANT_AUTO, B, H, T, d, dtype);
+  const bool fast = variant != SLIM_VARIANT_GENERIC;
+
+  StageTimer tm(o, st);
+  if (fast) launch_zero_ints((int*)(ws + p.off_ctrl), CTRL_INTS / 2, st);   // arrival counters of the products
+  dense(fast, dtype, (const float*)c.x, c.W_Q, q, B, H, d, ws, p, st);
+  dense(fast, dtype, (const float*)c.x, c.W_K, knew, B, H, d, ws, p, st);
+  if (!slim_path) dense(fast, dtype, (const float*)c.x, c.W_V, vnew, B, H, d, ws, p, st);
+  launch_append(dtype, knew, slim_path ? nullptr : vnew, c.Kcache, slim_path ? nullptr : c.Vcache,
+                t_stride * d, lens, T, d, d_k, rope, q, slim_path ? 0 : 1, B, st);
+  if (int rc = launch_status()) return rc;
+  tm.mark();
+
+  slim_opts inner = o ? *o : slim_opts{};
+  inner.dtype = dtype;
+  inner.workspace = ws;
+  inner.workspace_bytes = p.total;
+  inner.stage_ms = nullptr;
+  int rc;
+  if (slim_path) {
+    rc = slim_decode(q, c.Kcache, c.W_second, attn, B, H, T, d, &inner);
+  } else {
+    inner.rope_table = nullptr;                       // the cache already holds the rotated keys
+    rc = vanilla_kv_decode(q, c.Kcache, c.Vcache, attn, B, H, T, d, &inner);
+  }
+  if (rc) return rc;
+  tm.mark();
+  dense(fast, dtype, attn, c.W_O, (float*)c.y, B, H, d, ws, p, st);
+  tm.mark();
+  tm.finish();
+  return launch_status();
+}
+
+}  // namespace
+
+extern "C" size_t slim_workspace_bytes_block(int B, int H, int T, int d, int dtype) {
+  if (B < 1 || H < 1 || T < 1 || d < 1) return 0;
+  (void)dtype;
+  return block_layout(make_plan(B, H, T, d, d), B, d).total;
+}
+
+extern "C" int slim_attention_block(const void* x, const void* W_Q, const void* W_K, const void* W_KV,
+                                    const void* W_O, void* Kcache, void* y, int B, int H, int T, int d,
+                                    const slim_opts* o) {
+  BlockCall c{x, W_Q, W_K, nullptr, W_KV, W_O, Kcache, nullptr, y};
+  return attention_block(true, c, B, H, T, d, o);
+}
+
+extern "C" int vanilla_attention_block(const void* x, const void* W_Q, const void* W_K, const void* W_V,
+                                       const void* W_O, void* Kcache, void* Vcache, void* y, int B, int H,
+                                       int T, int d, const slim_opts* o) {
+  BlockCall c{x, W_Q, W_K, W_V, nullptr, W_O, Kcache, Vcache, y};
+  return attention_block(false, c, B, H, T, d, o);
+}

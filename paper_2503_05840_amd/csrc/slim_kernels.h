@@ -40,6 +40,13 @@ void launch_combine(const float* Cpart, const float* mpart, const float* lpart, 
 void launch_project(int dtype, const float* Cn, const void* W, int rows, int e, int H, int d_k,
                     float* out, int B, hipStream_t st);
 
+// New token rows into the caches at row len_b - 1: K <- knew (rotated to that position when rope and
+// rotate_k), V <- vnew (nullable: no V-cache); with rope, q [B][d] is rotated in place as well.
+void launch_append(int dtype, const float* knew, const float* vnew, void* K, void* V, long bstride,
+                   const int32_t* seq_lens, int T, int d, int d_k, const float* rope, float* q, int rotate_k,
+                   int B, hipStream_t st);
+void launch_zero_ints(int* p, int n, hipStream_t st);
+
 // Vanilla K+V decode: partial (m, l, acc) per (b, split, head) then a merge.
 void launch_vanilla(int dtype, const float* q, const void* K, const void* V, long bstride,
                     const int32_t* seq_lens, int T, int H, int d_k, int nsplit, float* acc,

@@ -184,6 +184,13 @@ def make_problem(cfg: Config, keep: set | None = None) -> Problem:
     return Problem(cfg, w, seqs, q)
 
 
+def make_w_o(cfg: Config) -> np.ndarray:
+    """Output projection W_O ~ N(0, 1/e), (e, d), for the whole-block workloads.  Drawn from a
+    stream of its own so that the decode-step inputs above keep their values."""
+    rng = np.random.default_rng([SEED_BASE + cfg.index, 1])
+    return rng.standard_normal((cfg.e, cfg.d)) / np.sqrt(cfg.e)
+
+
 def project_cache(X: np.ndarray, W: np.ndarray) -> np.ndarray:
     """Cache construction (the prompt phase, which lies outside the decode path): the rows
     the decode step will read, K = X W_K, as a plain fp64 product."""

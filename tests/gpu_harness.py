@@ -182,3 +182,83 @@ class XCase:
         rows = self.oracle_rows
         assert np.isfinite(out).all(), "non-finite output"
         return head_rel_err(out[rows], self.ref[rows], self.cfg.H)
+
+
+def row_rel_err(out: np.ndarray, ref: np.ndarray) -> float:
+    """max over rows of ||out - ref||_inf / ||ref||_inf."""
+    return float((np.abs(out.astype(np.float64) - ref).max(axis=1) / np.abs(ref).max(axis=1)).max())
+
+
+class BlockCase:
+    """One generated token per sequence through the whole attention block: the config's lengths
+    count the rows after the append, so the caches hold lengths[b] - 1 old rows and the kernels
+    write row lengths[b] - 1.  q_gain scales W_Q (peakier weights)."""
+
+    def __init__(self, cfg: synth.Config, rope_base=None, q_gain: float = 1.0, t_stride: int = 0):
+        import torch
+        self.cfg, self.rope_base = cfg, rope_base
+        p = synth.make_problem(cfg)
+        B, T, d = cfg.B, cfg.T, cfg.d
+        W_O = synth.make_w_o(cfg)
+        W_Q = p.w.W_Q * q_gain
+        self.lens = p.lengths
+        ts = self.t_stride = t_stride or T
+        el = np.float32 if cfg.dtype == "f32" else np.uint16
+        hole = np.float32("nan") if cfg.dtype == "f32" else np.uint16(0x7FC0)     # NaN where the new row goes
+        Kh = np.full((B, ts, d), hole, dtype=el)
+        Krh = np.full((B, ts, d), hole, dtype=el)
+        Vh = np.full((B, ts, d), hole, dtype=el)
+        self.ref = np.empty((B, d))
+        self.k_new = np.empty((B, d))
+        self.v_new = np.empty((B, d))
+        for b, sq in enumerate(p.seqs):
+            n = int(self.lens[b]) - 1
+            K = orc_project(sq.X[:n], p.w.W_K)
+            V = orc_project(sq.X[:n], p.w.W_V)
+            self.ref[b], self.k_new[b], self.v_new[b] = orc.attention_block(
+                sq.x, K, V, W_Q, p.w.W_K, p.w.W_V, W_O, cfg.H, rope_base)
+            Kh[b, :n] = synth.to_storage(K, cfg.dtype)
+            Vh[b, :n] = synth.to_storage(V, cfg.dtype)
+            Krh[b, :n] = synth.to_storage(orc.rope_encode(K, cfg.H, np.arange(n), rope_base), cfg.dtype) if rope_base else Kh[b, :n]
+            if rope_base:                                  # what a vanilla cache stores for the new token
+                self.k_new_rot = getattr(self, "k_new_rot", np.empty((B, d)))
+                self.k_new_rot[b] = orc.rope_encode(self.k_new[b][None, :], cfg.H, [n], rope_base)[0]
+        wkv, _ = binding.slim_prepare_wkv(p.w.W_K, p.w.W_V)
+        pack = lambda W: to_device(binding.slim_pack_weights(W, cfg.dtype))
+        self.Wq, self.Wk, self.Wv, self.Wo, self.Wkv = pack(W_Q), pack(p.w.W_K), pack(p.w.W_V), pack(W_O), pack(wkv)
+        self.K, self.K_rot, self.V = to_device(Kh), to_device(Krh), to_device(Vh)
+        self.x = to_device(np.stack([sq.x for sq in p.seqs]).astype(np.float32))
+        self.lens_dev = torch.from_numpy(self.lens).cuda()
+        self.rope_table = to_device(binding.slim_rope_table(T, cfg.d_k, rope_base)) if rope_base else None
+
+    def _kw(self, **kw):
+        d = dict(dtype=self.cfg.dtype, t_stride=self.t_stride, seq_lens=self.lens_dev, seq_lens_host=self.lens)
+        if self.rope_table is not None:
+            d["rope_table"] = self.rope_table
+        d.update(kw)
+        return d
+
+    def _new_rows(self, cache):
+        """The rows the call wrote, as fp64 (B, d)."""
+        import torch
+        idx = torch.from_numpy(self.lens.astype(np.int64) - 1).cuda()
+        rows = cache[torch.arange(self.cfg.B, device="cuda"), idx]
+        return rows.float().cpu().numpy().astype(np.float64)
+
+    def run_slim(self, **kw):
+        import torch
+        c = self.cfg
+        y = torch.full((c.B, c.d), float("nan"), device="cuda", dtype=torch.float32)
+        binding.slim_attention_block(self.x, self.Wq, self.Wk, self.Wkv, self.Wo, self.K, y, c.B, c.H, c.T, c.d,
+                                     **self._kw(**kw))
+        torch.cuda.synchronize()
+        return y.cpu().numpy(), self._new_rows(self.K)
+
+    def run_vanilla(self, **kw):
+        import torch
+        c = self.cfg
+        y = torch.full((c.B, c.d), float("nan"), device="cuda", dtype=torch.float32)
+        binding.vanilla_attention_block(self.x, self.Wq, self.Wk, self.Wv, self.Wo, self.K_rot, self.V, y,
+                                        c.B, c.H, c.T, c.d, **self._kw(**kw))
+        torch.cuda.synchronize()
+        return y.cpu().numpy(), self._new_rows(self.K_rot), self._new_rows(self.V)

@@ -88,3 +88,20 @@ def test_config4_t5_xcache_sampled():
     e = x.err(out)
     say(f"  xcache rel err {e:.3e}")
     assert e <= TOL["bf16"]
+
+
+def test_config1_whole_attention_block_full():
+    """The steps either side of the decode step at config 1's size: q and k projections, append as row
+    16383, decode over 16384 rows, W_O; slim and vanilla, with rotary keys."""
+    from gpu_harness import BlockCase, row_rel_err
+    say("[case] config 1 full size, whole attention block + rotary keys (W_Q x10)")
+    k = BlockCase(C[1], rope_base=10000.0, q_gain=10.0)
+    y, krow = k.run_slim()
+    e, ek = row_rel_err(y, k.ref), row_rel_err(krow, k.k_new)
+    say(f"  slim block rel err {e:.3e}, appended key row {ek:.3e}")
+    assert e <= TOL["bf16"] and ek <= TOL["bf16"]
+    y, krow, vrow = k.run_vanilla()
+    e = row_rel_err(y, k.ref)
+    say(f"  vanilla block rel err {e:.3e}")
+    assert e <= TOL["bf16"]
+    assert row_rel_err(krow, k.k_new_rot) <= TOL["bf16"] and row_rel_err(vrow, k.v_new) <= TOL["bf16"]
