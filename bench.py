@@ -146,6 +146,118 @@ def bench_xcache(args, cfg, torch, binding, synth):
     print(json.dumps(result), flush=True)
 
 
+def bench_block(args, cfg, torch, binding, synth):
+    """--block: one generated token per sequence through the whole attention block
+    (slim_attention_block: q and k projections, append, decode step, W_O) against
+    vanilla_attention_block (q, k, v projections, append to both caches, K+V decode, W_O)."""
+    B, H, T, d, d_k = cfg.B, cfg.H, cfg.T, cfg.d, cfg.d_k
+    es = 2 if cfg.dtype == "bf16" else 4
+    log(f"[bench] building inputs for the attention block on config {cfg.index} ({cfg.name}) ...")
+    p = synth.make_problem(cfg)
+    lens = p.lengths                                   # rows after the append
+    W_O = synth.make_w_o(cfg)
+    el = np.uint16 if cfg.dtype == "bf16" else np.float32
+    Kh = np.zeros((B, T, d), dtype=el)
+    Vh = np.zeros((B, T, d), dtype=el)
+    K64 = V64 = None
+    for b, sq in enumerate(p.seqs):
+        n = int(lens[b]) - 1
+        Kb = synth.project_cache(sq.X[:n], p.w.W_K)
+        Vb = synth.project_cache(sq.X[:n], p.w.W_V)
+        Kh[b, :n] = synth.to_storage(Kb, cfg.dtype)
+        Vh[b, :n] = synth.to_storage(Vb, cfg.dtype)
+        if b == 0:
+            K64, V64 = Kb, Vb
+        sq.X = None
+    wkv, _ = binding.slim_prepare_wkv(p.w.W_K, p.w.W_V)
+    to_device = binding.to_device
+    pack = lambda W: to_device(binding.slim_pack_weights(W, cfg.dtype))
+    ncopies = args.copies or max(2, int(np.ceil(512e6 / Kh.nbytes)) + 1)
+    Ks = [to_device(Kh) for _ in range(ncopies)]
+    Vs = [to_device(Vh) for _ in range(ncopies)]
+    # the weights rotate too: at small batch they are as many bytes as the cache
+    wcopies = max(2, int(np.ceil(512e6 / (4.0 * d * d * es))) + 1)
+    Wq, Wk, Wv, Wo, Wkv = ([pack(W) for _ in range(wcopies)] for W in (p.w.W_Q, p.w.W_K, p.w.W_V, W_O, wkv))
+    x = to_device(np.stack([sq.x for sq in p.seqs]).astype(np.float32))
+    y = torch.zeros((B, d), device="cuda", dtype=torch.float32)
+    y_v = torch.zeros_like(y)
+    ws = torch.empty(binding.slim_workspace_bytes_block(B, H, T, d, cfg.dtype), dtype=torch.uint8, device="cuda")
+    kw = dict(dtype=cfg.dtype, workspace=ws)
+    if bool((lens != T).any()):
+        kw.update(seq_lens=torch.from_numpy(lens).cuda(), seq_lens_host=lens)
+    if args.rope:
+        kw["rope_table"] = to_device(binding.slim_rope_table(T, d_k, 10000.0))
+
+    def slim(i, **extra):
+        j = i % wcopies
+        binding.slim_attention_block(x, Wq[j], Wk[j], Wkv[j], Wo[j], Ks[i % ncopies], y, B, H, T, d, **kw, **extra)
+
+    def vanilla(i, **extra):
+        j = i % wcopies
+        binding.vanilla_attention_block(x, Wq[j], Wk[j], Wv[j], Wo[j], Ks[i % ncopies], Vs[i % ncopies], y_v,
+                                        B, H, T, d, **kw, **extra)
+
+    log("[bench] timing slim_attention_block ...")
+    ms_slim = timed(torch, slim, args.steps, args.warmup)
+    log("[bench] timing vanilla_attention_block ...")
+    ms_van = timed(torch, vanilla, args.steps, args.warmup)
+    stage = binding.new_stage_buffer()
+    acc, vacc = np.zeros(3), np.zeros(3)
+    for i in range(args.steps):
+        slim(i, stage_ms=stage)
+        acc += np.array(list(stage))[:3]
+        vanilla(i, stage_ms=stage)
+        vacc += np.array(list(stage))[:3]
+    acc /= args.steps
+    vacc /= args.steps
+    names = ["projections_in + append", "decode step", "projection_out"]
+    k_bytes = float(lens.astype(np.int64).sum()) * d * es
+    w_bytes = float(d) * d * es
+    alg_bytes = k_bytes + 4 * w_bytes                  # K once, W_Q, W_K, W_KV, W_O once
+    achieved = alg_bytes / (ms_slim * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": "whole block (all launches of one slim_attention_block call)",
+                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None, "algorithmic_bytes": alg_bytes,
+                "kernel_ms": round(ms_slim, 5),
+                "stage_ms": {n: round(float(acc[i]), 5) for i, n in enumerate(names)},
+                "vanilla_stage_ms": {n: round(float(vacc[i]), 5) for i, n in enumerate(names)}}
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import mha_oracle as orc
+        log("[bench] timing the CPU oracle (attention_block on sequence 0, fp64 K and V resident) ...")
+        x0 = p.seqs[0].x
+        base = 10000.0 if args.rope else None
+        ref0, _, _ = orc.attention_block(x0, K64, V64, p.w.W_Q, p.w.W_K, p.w.W_V, W_O, H, base)
+        slim(0)
+        torch.cuda.synchronize()
+        got0 = y[0].cpu().numpy().astype(np.float64)
+        err = float(np.abs(got0 - ref0).max() / np.abs(ref0).max())
+        reps, t0c, c0 = 0, time.perf_counter(), os.times()
+        while reps < 3 or (time.perf_counter() - t0c < 10.0 and reps < 200):
+            orc.attention_block(x0, K64, V64, p.w.W_Q, p.w.W_K, p.w.W_V, W_O, H, base)
+            reps += 1
+        wall = time.perf_counter() - t0c
+        c1 = os.times()
+        busy = (c1.user - c0.user) + (c1.system - c0.system)
+        cpu = {"value": round(reps / wall, 3), "unit": "tokens/s", "cores": max(1, int(round(busy / wall))),
+               "kind": "oracle", "host_cores": os.cpu_count(),
+               "sample": f"sequence 0 of config {cfg.index} ({int(lens[0]) - 1} cached rows x {d}), {reps} repeats of the fp64 attention block",
+               "gpu_max_rel_err_vs_oracle_seq0": float(f"{err:.3e}")}
+    result = {
+        "metric": "decode tokens/s (one whole attention block per token: projections, append, K-cache-only decode step, W_O) vs the vanilla K+V block, 1 GPU",
+        "value": round(B / (ms_slim * 1e-3), 2), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_slim, 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"configs[{cfg.index}] {cfg.name} + whole attention block" + (" + rotary keys" if args.rope else ""),
+                   "B": B, "H": H, "d": d, "d_k": d_k, "T": T, "sum_len": int(lens.sum()),
+                   "k_cache_copies_rotated": ncopies, "weight_copies_rotated": wcopies},
+        "vanilla_block_ms_per_step": round(ms_van, 5), "speedup_vs_vanilla_block": round(ms_van / ms_slim, 3),
+        "bytes_ratio_vanilla_over_slim": round((2 * k_bytes + 4 * w_bytes) / alg_bytes, 3),
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    print(json.dumps(result), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -157,6 +269,8 @@ def main():
     ap.add_argument("--copies", type=int, default=0, help="K-cache copies to rotate over (0 = enough to exceed 512 MB)")
     ap.add_argument("--rope", action="store_true",
                     help="keys carry rotary positions: slim_decode rotates the raw cached keys for the scores (K-cache configs)")
+    ap.add_argument("--block", action="store_true",
+                    help="time the whole attention block (slim_attention_block vs vanilla_attention_block) instead of the decode step")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a few plain 128 MiB device copies (a kernel of known traffic, for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -171,7 +285,11 @@ def main():
     binding.load()
     cfg = synth.CONFIGS[args.config]
     if cfg.kind == "xcache":
+        if args.rope or args.block:
+            sys.exit("bench.py: --rope and --block apply to the K-cache configs (0-3)")
         return bench_xcache(args, cfg, torch, binding, synth)
+    if args.block:
+        return bench_block(args, cfg, torch, binding, synth)
     B, H, T, d, d_k = cfg.B, cfg.H, cfg.T, cfg.d, cfg.d_k
     es = 2 if cfg.dtype == "bf16" else 4
     log(f"[bench] building inputs for config {cfg.index} ({cfg.name}) ...")

@@ -181,9 +181,17 @@ __device__ __forceinline__ int ld_err(const int* p) {
 // `red`: 64 KB of LDS for the cross-wave sum.
 // `after_w_issue` runs (all threads) once the first tile of W is in flight and before any partial
 // is read: the place to build the tile prefix, or to wait for the other workgroups' partials.
-template <int NBT, bool COH, class Hook>
-__device__ __forceinline__ void project_work(const ProjArgs& a, int h, int cs, int bz, const int* prefix,
+// DENSE: plain products out_m = x W_m for up to three matrices that share x (ProjArgs::Wm); hx counts
+// (matrix, head) column blocks.  The result leaves as fp32, or -- the new token's rows -- rotated to
+// the append position and/or stored into the caches (ProjArgs::role).
+template <int NBT, bool COH, bool DENSE, class Hook>
+__device__ __forceinline__ void project_work(const ProjArgs& a, int hx, int cs, int bz, const int* prefix,
                                              ProjShared<NBT>& sm, float* red, Hook&& after_w_issue) {
+  const int mtx = DENSE ? hx / a.H : 0;
+  const int h = DENSE ? hx - mtx * a.H : hx;
+  const uint16_t* const Wmat = DENSE ? a.Wm[mtx] : a.W;
+  float* const outp = DENSE ? a.outm[mtx] : a.out;
+  float* const outpart = DENSE ? a.outpart + (size_t)mtx * a.csw * a.B * a.e : a.outpart;
   const int bbase = bz * 16 * NBT;
   const int nb = min(16 * NBT, a.B - bbase);
   constexpr int NW = 8, NTHR = 512;
@@ -191,11 +199,12 @@ __device__ __forceinline__ void project_work(const ProjArgs& a, int h, int cs, i
   const int idx = lane & 15, rg = lane >> 4;
   const int n = idx, kg = rg;
 
+  const int nhx = DENSE ? a.H * a.nmat : a.H;          // arrival counters per batch chunk
   const int lph = a.d_k / 8;
   const bool col_active = idx < lph;
-  // partial p of head h starts at ((p * H) + h) * rows; mode 2 has one row of x per sequence for all heads
-  const int hmul = a.mode == 2 ? 1 : a.H, hadd = a.mode == 2 ? 0 : h;
-  const uint16_t* Wh = a.W + (size_t)h * a.d_k + idx * 8;
+  // partial p of head h starts at ((p * H) + h) * rows; DENSE has one row of x per sequence for all heads
+  const int hmul = DENSE ? 1 : a.H, hadd = DENSE ? 0 : h;
+  const uint16_t* Wh = Wmat + (size_t)h * a.d_k + idx * 8;
   const int c_lo = cs * a.crows, c_hi = min(a.rows, c_lo + a.crows);
   const int ntile = (c_hi - c_lo + TILE_ROWS - 1) / TILE_ROWS;
   auto load_w = [&](u32x4 (&wt)[8], int ct) {
@@ -216,15 +225,16 @@ __device__ __forceinline__ void project_work(const ProjArgs& a, int h, int cs, i
   for (int bl = w; bl < nb; bl += NW) {              // one wave per sequence, one lane per partial
     const int b = bbase + bl;
     int p0, np;
+    if constexpr (DENSE) {                           // "partial" b is row b of x, weight 1
+      if (lane == 0) { sm.wpid[bl][0] = 1.f; sm.pid0s[bl] = b; sm.nps[bl] = 1; }
+      continue;
+    }
     if (a.mode == 0) {
       const int VT = prefix[a.B];
       const int Qt = (VT + a.NG - 1) / a.NG;
       const int gf = prefix[b] / Qt, gl = (prefix[b + 1] - 1) / Qt;
       p0 = b + gf;
       np = gl - gf + 1;
-    } else if (a.mode == 2) {                        // plain product: "partial" b is row b of x, weight 1
-      if (lane == 0) { sm.wpid[bl][0] = 1.f; sm.pid0s[bl] = b; sm.nps[bl] = 1; }
-      continue;
     } else {
       p0 = b * a.nsplit;
       np = a.nsplit;
@@ -354,11 +364,34 @@ __device__ __forceinline__ void project_work(const ProjArgs& a, int h, int cs, i
     __syncthreads();
   }
 
+  // One finished output element (sequence bbase + bl, column j of the head); `other` is column j ^ 1.
+  auto emit = [&](int bl, int j, float val, float other, bool bad) {
+    const size_t b = (size_t)(bbase + bl);
+    const int col = h * a.d_k + j;
+    if constexpr (!DENSE) {
+      outp[b * a.e + col] = bad ? NAN : val;
+    } else {
+      const int role = a.role[mtx];
+      if (role == 0) { outp[b * a.e + col] = val; return; }
+      // the new token of sequence b sits at row / position len_b - 1
+      const int pos = seq_len_of(a.seq_lens, (int)b, a.T) - 1;
+      if (pos < 0) return;
+      float r = val;
+      if (a.rope && (role == 1 || (role == 2 && a.rotate_k))) {
+        const float* cs = a.rope + ((size_t)pos * (a.d_k / 2) + j / 2) * 2;
+        r = (j & 1) ? fmaf(val, cs[0], -other * cs[1]) : fmaf(val, cs[0], other * cs[1]);
+      }
+      if (role == 1) { outp[b * a.e + col] = r; return; }
+      uint16_t* dst = (role == 2 ? a.Kc : a.Vc) + b * a.c_bstride + (size_t)pos * a.e + col;
+      *dst = __builtin_bit_cast(uint16_t, (__bf16)r);
+    }
+  };
+
   if (a.csw == 1) {
     const bool bad = a.err && ld_err<COH>(a.err) == (int)a.launch_id;      // the stream kernel gave up waiting
     for (int v = tid; v < nb * a.d_k; v += NTHR) {
       const int bl = v / a.d_k, j = v % a.d_k;
-      a.out[(size_t)(bbase + bl) * a.e + h * a.d_k + j] = bad ? NAN : sm.obuf[bl][j];
+      emit(bl, j, sm.obuf[bl][j], sm.obuf[bl][j ^ 1], bad);
     }
     return;
   }
@@ -368,19 +401,21 @@ __device__ __forceinline__ void project_work(const ProjArgs& a, int h, int cs, i
   // them with device-coherent loads.
   for (int v = tid; v < nb * a.d_k; v += NTHR) {
     const int bl = v / a.d_k, j = v % a.d_k;
-    float* dst = &a.outpart[((size_t)cs * a.B + bbase + bl) * a.e + h * a.d_k + j];
+    float* dst = &outpart[((size_t)cs * a.B + bbase + bl) * a.e + h * a.d_k + j];
     asm volatile("global_store_dword %0, %1, off sc0 sc1" : : "v"(dst), "v"(sm.obuf[bl][j]) : "memory");
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
   if (tid == 0) {
-    const int old = __hip_atomic_fetch_add(&a.counters[bz * a.H + h], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const int old = __hip_atomic_fetch_add(&a.counters[bz * nhx + hx], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     sm.is_last = (old == a.csw - 1);
   }
   __syncthreads();
   if (!sm.is_last) return;
   const bool bad = a.err && __hip_atomic_load(a.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (int)a.launch_id;
-  for (int v = tid; v < nb * a.d_k; v += NTHR) {
+  for (int v0 = 0; v0 < nb * a.d_k; v0 += NTHR) {
+    if (v0 + (tid & ~63) >= nb * a.d_k) break;           // (whole waves: the columns of a pair sit in neighbour lanes)
+    const int v = min(v0 + tid, nb * a.d_k - 1);
     const int bl = v / a.d_k, j = v % a.d_k;
     float sum = 0.f;
     for (int s0 = 0; s0 < a.csw; s0 += 8) {
@@ -388,7 +423,7 @@ __device__ __forceinline__ void project_work(const ProjArgs& a, int h, int cs, i
 #pragma unroll
       for (int q = 0; q < 8; ++q) {
         const int sp = min(s0 + q, a.csw - 1);
-        const float* src = &a.outpart[((size_t)sp * a.B + bbase + bl) * a.e + h * a.d_k + j];
+        const float* src = &outpart[((size_t)sp * a.B + bbase + bl) * a.e + h * a.d_k + j];
         asm volatile("global_load_dword %0, %1, off sc1" : "=v"(part[q]) : "v"(src) : "memory");
       }
       asm volatile("s_waitcnt vmcnt(0)" : "+v"(part[0]), "+v"(part[1]), "+v"(part[2]), "+v"(part[3]),
@@ -396,18 +431,19 @@ __device__ __forceinline__ void project_work(const ProjArgs& a, int h, int cs, i
 #pragma unroll
       for (int q = 0; q < 8; ++q) if (s0 + q < a.csw) sum += part[q];
     }
-    a.out[(size_t)(bbase + bl) * a.e + h * a.d_k + j] = bad ? NAN : sum;    // NaN: the stream kernel gave up waiting
+    const float other = DENSE ? __shfl_xor(sum, 1) : 0.f;
+    if (v0 + tid < nb * a.d_k) emit(bl, j, sum, other, bad);               // NaN: the stream kernel gave up waiting
   }
-  if (tid == 0) a.counters[bz * a.H + h] = 0;
+  if (tid == 0) a.counters[bz * nhx + hx] = 0;
 }
 
-template <int NBT>
+template <int NBT, bool DENSE>
 __global__ __launch_bounds__(512) void project_mfma_kernel(const ProjArgs a) {
   __shared__ int prefix[FUSED_MAX_B + 1];
   __shared__ ProjShared<NBT> sm;
   __shared__ float red[8 * 8 * 4 * 64];
-  project_work<NBT, false>(a, blockIdx.x, blockIdx.y, blockIdx.z, prefix, sm, red, [&]() {
-    if (a.mode == 0) build_tile_prefix(prefix, a.seq_lens, a.B, a.T);
+  project_work<NBT, false, DENSE>(a, blockIdx.x, blockIdx.y, blockIdx.z, prefix, sm, red, [&]() {
+    if (!DENSE && a.mode == 0) build_tile_prefix(prefix, a.seq_lens, a.B, a.T);
   });
 }
 
@@ -979,7 +1015,7 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
   if (wg >= a.proj.H * a.proj.csw) return;
   // (everything of the stream phase is over in this workgroup: its LDS is reused)
   ProjShared<1>& psm = *reinterpret_cast<ProjShared<1>*>(sbuf);
-  project_work<1, true>(a.proj, wg / a.proj.csw, wg % a.proj.csw, 0, prefix, psm, red, [&]() {
+  project_work<1, true, false>(a.proj, wg / a.proj.csw, wg % a.proj.csw, 0, prefix, psm, red, [&]() {
     // every workgroup's partials must be out: all arrival flags carry this launch's id
     if (wu == 0) {
       int spins = 0;
@@ -1122,9 +1158,24 @@ void launch_project_mfma(ProjArgs a, hipStream_t st) {
   const int nbt = proj_batch_tiles(a.B, a.rows, a.e);
   a.crows = proj_rows_per_split(a.rows, a.csw);
   dim3 grid(a.H, a.csw, (a.B + 16 * nbt - 1) / (16 * nbt)), block(512);
-  if (nbt == 1) hipLaunchKernelGGL(project_mfma_kernel<1>, grid, block, 0, st, a);
-  else if (nbt == 2) hipLaunchKernelGGL(project_mfma_kernel<2>, grid, block, 0, st, a);
-  else hipLaunchKernelGGL(project_mfma_kernel<4>, grid, block, 0, st, a);
+  if (nbt == 1) hipLaunchKernelGGL((project_mfma_kernel<1, false>), grid, block, 0, st, a);
+  else if (nbt == 2) hipLaunchKernelGGL((project_mfma_kernel<2, false>), grid, block, 0, st, a);
+  else hipLaunchKernelGGL((project_mfma_kernel<4, false>), grid, block, 0, st, a);
+}
+
+// out_m = x W_m for a.nmat matrices in one launch (a.Cpart = x, a.csw from dense_row_splits).
+void launch_dense_mfma(ProjArgs a, hipStream_t st) {
+  const int nbt = proj_batch_tiles(a.B, a.rows, a.e);
+  a.crows = proj_rows_per_split(a.rows, a.csw);
+  a.mode = 2;
+  dim3 grid(a.H * a.nmat, a.csw, (a.B + 16 * nbt - 1) / (16 * nbt)), block(512);
+  if (nbt == 1) hipLaunchKernelGGL((project_mfma_kernel<1, true>), grid, block, 0, st, a);
+  else if (nbt == 2) hipLaunchKernelGGL((project_mfma_kernel<2, true>), grid, block, 0, st, a);
+  else hipLaunchKernelGGL((project_mfma_kernel<4, true>), grid, block, 0, st, a);
+}
+
+int dense_row_splits(int H, int nmat, int rows, int e, int B) {
+  return proj_row_splits(H * nmat, rows, e, B);
 }
 
 }  // namespace slim

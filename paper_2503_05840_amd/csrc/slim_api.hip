@@ -376,9 +376,9 @@ extern "C" int slim_decode_xcache(const void* q, const void* X, const void* W_K,
 // ---- the steps either side of the decode step ----------------------------------------------------
 namespace {
 
-struct BlockBufs { size_t off_q, off_k, off_v, off_attn, total; };
+struct BlockBufs { size_t off_q, off_k, off_v, off_attn, off_dpart, total; };
 
-BlockBufs block_layout(const Plan& p, int B, int d) {
+BlockBufs block_layout(const Plan& p, int B, int H, int d) {
   BlockBufs b;
   size_t o = p.total;
   const size_t row = up(sizeof(float) * (size_t)B * d);
@@ -386,23 +386,10 @@ BlockBufs block_layout(const Plan& p, int B, int d) {
   b.off_k = o; o += row;
   b.off_v = o; o += row;
   b.off_attn = o; o += row;
+  // partial sums of the dense products: up to three matrices, each with at most the row splits of one
+  b.off_dpart = o; o += up(sizeof(float) * 3 * (size_t)proj_row_splits(H, d, d, B) * B * d);
   b.total = o;
   return b;
-}
-
-// out [B][d] = x [B][d] W [d][d]
-void dense(bool fast, int dtype, const float* x, const void* W, float* out, int B, int H, int d, char* ws,
-           const Plan& p, hipStream_t st) {
-  if (!fast) {
-    launch_project(dtype, x, W, d, d, 1, d, out, B, st);       // one "head" as wide as the matrix
-    return;
-  }
-  ProjArgs pa{};
-  pa.Cpart = x; pa.W = (const uint16_t*)W; pa.out = out; pa.outpart = (float*)(ws + p.off_outpart);
-  pa.counters = (int*)(ws + p.off_ctrl);
-  pa.B = B; pa.T = 1; pa.H = H; pa.d_k = d / H; pa.rows = d; pa.e = d;
-  pa.nsplit = 1; pa.mode = 2; pa.mscale = 1.0f; pa.csw = p.csw;
-  launch_project_mfma(pa, st);
 }
 
 struct BlockCall {
@@ -422,7 +409,7 @@ int attention_block(bool slim_path, const BlockCall& c, int B, int H, int T, int
   const void* ptrs[] = {c.x, c.W_Q, c.W_K, c.W_V, c.W_second, c.W_O, c.Kcache, c.Vcache, c.y, o ? o->rope_table : nullptr};
   for (const void* q : ptrs) if (q && misaligned(q)) return SLIM_ERR_ALIGN;
   const Plan p = make_plan(B, H, T, d, d);
-  const BlockBufs bb = block_layout(p, B, d);
+  const BlockBufs bb = block_layout(p, B, H, d);
   char* ws;
   if (int rc = get_workspace(o, bb.total, &ws)) return rc;
   hipStream_t st = o ? (hipStream_t)o->stream : nullptr;
@@ -433,15 +420,33 @@ int attention_block(bool slim_path, const BlockCall& c, int B, int H, int T, int
   float* vnew = (float*)(ws + bb.off_v);
   float* attn = (float*)(ws + bb.off_attn);
   const int variant = pick_variant(o ? o->variant : SLIM_VARIANT_AUTO, B, H, T, d, dtype);
-  const bool fast = variant != SLIM_VARIANT_GENERIC;
+  // the MFMA products count arrivals per (matrix, head, batch chunk)
+  const int zb = (B + 15) / 16;
+  const int nmat = slim_path ? 2 : 3;
+  const bool fast = variant != SLIM_VARIANT_GENERIC && H * nmat * zb < CTRL_INTS / 2;
+  ProjArgs pa{};
+  pa.Cpart = (const float*)c.x; pa.outpart = (float*)(ws + bb.off_dpart); pa.counters = (int*)(ws + p.off_ctrl);
+  pa.seq_lens = lens; pa.B = B; pa.T = T; pa.H = H; pa.d_k = d_k; pa.rows = d; pa.e = d;
+  pa.nsplit = 1; pa.mscale = 1.0f;
 
   StageTimer tm(o, st);
-  if (fast) launch_zero_ints((int*)(ws + p.off_ctrl), CTRL_INTS / 2, st);   // arrival counters of the products
-  dense(fast, dtype, (const float*)c.x, c.W_Q, q, B, H, d, ws, p, st);
-  dense(fast, dtype, (const float*)c.x, c.W_K, knew, B, H, d, ws, p, st);
-  if (!slim_path) dense(fast, dtype, (const float*)c.x, c.W_V, vnew, B, H, d, ws, p, st);
-  launch_append(dtype, knew, slim_path ? nullptr : vnew, c.Kcache, slim_path ? nullptr : c.Vcache,
-                t_stride * d, lens, T, d, d_k, rope, q, slim_path ? 0 : 1, B, st);
+  if (fast) {
+    // q, k (and v) in one launch; the new rows go straight into the caches
+    launch_zero_ints(pa.counters, CTRL_INTS / 2, st);
+    pa.nmat = nmat; pa.csw = dense_row_splits(H, nmat, d, d, B);
+    pa.Wm[0] = (const uint16_t*)c.W_Q; pa.outm[0] = q; pa.role[0] = 1;
+    pa.Wm[1] = (const uint16_t*)c.W_K; pa.outm[1] = nullptr; pa.role[1] = 2;
+    pa.Wm[2] = (const uint16_t*)c.W_V; pa.outm[2] = nullptr; pa.role[2] = 3;
+    pa.Kc = (uint16_t*)c.Kcache; pa.Vc = (uint16_t*)c.Vcache; pa.c_bstride = t_stride * d;
+    pa.rope = rope; pa.rotate_k = slim_path ? 0 : 1;
+    launch_dense_mfma(pa, st);
+  } else {
+    launch_project(dtype, (const float*)c.x, c.W_Q, d, d, 1, d, q, B, st);      // one "head" as wide as the matrix
+    launch_project(dtype, (const float*)c.x, c.W_K, d, d, 1, d, knew, B, st);
+    if (!slim_path) launch_project(dtype, (const float*)c.x, c.W_V, d, d, 1, d, vnew, B, st);
+    launch_append(dtype, knew, slim_path ? nullptr : vnew, c.Kcache, slim_path ? nullptr : c.Vcache,
+                  t_stride * d, lens, T, d, d_k, rope, q, slim_path ? 0 : 1, B, st);
+  }
   if (int rc = launch_status()) return rc;
   tm.mark();
 
@@ -459,7 +464,13 @@ int attention_block(bool slim_path, const BlockCall& c, int B, int H, int T, int
   }
   if (rc) return rc;
   tm.mark();
-  dense(fast, dtype, attn, c.W_O, (float*)c.y, B, H, d, ws, p, st);
+  if (fast) {
+    pa.Cpart = attn; pa.nmat = 1; pa.csw = dense_row_splits(H, 1, d, d, B);
+    pa.Wm[0] = (const uint16_t*)c.W_O; pa.outm[0] = (float*)c.y; pa.role[0] = 0;
+    launch_dense_mfma(pa, st);
+  } else {
+    launch_project(dtype, attn, c.W_O, d, d, 1, d, (float*)c.y, B, st);
+  }
   tm.mark();
   tm.finish();
   return launch_status();
@@ -470,7 +481,7 @@ int attention_block(bool slim_path, const BlockCall& c, int B, int H, int T, int
 extern "C" size_t slim_workspace_bytes_block(int B, int H, int T, int d, int dtype) {
   if (B < 1 || H < 1 || T < 1 || d < 1) return 0;
   (void)dtype;
-  return block_layout(make_plan(B, H, T, d, d), B, d).total;
+  return block_layout(make_plan(B, H, T, d, d), B, H, d).total;
 }
 
 extern "C" int slim_attention_block(const void* x, const void* W_Q, const void* W_K, const void* W_KV,

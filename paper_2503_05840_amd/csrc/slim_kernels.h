@@ -75,10 +75,17 @@ struct ProjArgs {
   int* counters; const int* err; unsigned launch_id;
   const int32_t* seq_lens;
   int B, T, H, d_k, rows, e;
-  int NG, nsplit, mode;               // mode 0: partials laid out by the stream kernel; 1: [b][nsplit];
-                                      // 2: no partials, Cpart = x [B][rows] shared by all heads: out = x W
+  int NG, nsplit, mode;               // mode 0: partials laid out by the stream kernel; 1: [b][nsplit]
   float mscale;                       // 1 for log2-domain maxima, log2(e) for natural-log ones
   int csw, crows;                     // row splits of W across workgroups, rows per split
+  // Dense products (launch_dense_mfma): Cpart = x [B][rows], out_m = x W_m for nmat matrices.
+  // role 0: fp32 result.  The new token's rows (it sits at row / position seq_lens[b] - 1):
+  // role 1: query, fp32, rotated to that position when rope is set; role 2: key row into Kc (rotated
+  // when rope and rotate_k); role 3: value row into Vc.
+  int nmat;
+  const uint16_t* Wm[3]; float* outm[3]; int role[3];
+  uint16_t* Kc; uint16_t* Vc; long c_bstride;
+  const float* rope; int rotate_k;
 };
 
 struct FusedArgs {
@@ -118,6 +125,8 @@ int proj_batch_tiles(int B, int rows, int e);
 int proj_row_splits(int H, int rows, int e, int B);
 int proj_rows_per_split(int rows, int csw);
 void launch_project_mfma(ProjArgs a, hipStream_t st);
+int dense_row_splits(int H, int nmat, int rows, int e, int B);
+void launch_dense_mfma(ProjArgs a, hipStream_t st);
 
 // ---- bf16 fast path of the X-cache scheme (kernels_xcache.hip) -------------------------------------
 bool xcache_fast_ok(int dtype, int H, int d_model, int d_k);
