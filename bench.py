@@ -132,7 +132,7 @@ def bench_xcache(args, cfg, torch, binding, synth):
                "gpu_max_rel_err_vs_oracle_seq0": float(f"{err:.3e}")}
     x_bytes = float(B) * T * dm * 2
     result = {
-        "metric": "decode tokens/s (one attention layer step, X-cache, e > d_model), 1 GPU",
+        "metric": "decode tokens/s (one attention layer step, X-cache: K and V never stored), 1 GPU",
         "value": round(B / (ms * 1e-3), 2), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms, 5), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
@@ -269,6 +269,9 @@ def main():
     ap.add_argument("--copies", type=int, default=0, help="K-cache copies to rotate over (0 = enough to exceed 512 MB)")
     ap.add_argument("--rope", action="store_true",
                     help="keys carry rotary positions: slim_decode rotates the raw cached keys for the scores (K-cache configs)")
+    ap.add_argument("--ecache", action="store_true",
+                    help="config 3 only: the cross-attention layer reads the encoder output E through slim_decode_xcache "
+                         "(option 2 of the encoder-decoder section) instead of a cross K-cache")
     ap.add_argument("--block", action="store_true",
                     help="time the whole attention block (slim_attention_block vs vanilla_attention_block) instead of the decode step")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -284,6 +287,10 @@ def main():
         sys.exit("bench.py: no GPU visible")
     binding.load()
     cfg = synth.CONFIGS[args.config]
+    if args.ecache:
+        if args.config != 3:
+            sys.exit("bench.py: --ecache applies to config 3 (the encoder-decoder cross-attention shape)")
+        cfg = synth.scaled(cfg, kind="xcache", name=cfg.name + " as E-cache (option 2)")
     if cfg.kind == "xcache":
         if args.rope or args.block:
             sys.exit("bench.py: --rope and --block apply to the K-cache configs (0-3)")

@@ -106,15 +106,19 @@ __global__ __launch_bounds__(512) void xq_tilde_kernel(const float* q, const uin
 
 // ------------------------------------------------------------------------------------------------
 // s[b][h][t] = scale * sum_c X[b][t][c] q~[b][h][c]       (scale = log2(e) / sqrt(d_k))
-// grid (row chunks of nblk x 256, ceil(H / 32), B).  The workgroup keeps q~ of its 32 heads in LDS as bf16
-// hi + lo (B operands); a wave owns 32 rows of X per block (A operands straight from global memory).
+// grid (row chunks of nblk x 256, ceil(H / HG), B), HG = 16 HT heads per workgroup (HT = 2 unless q~ of 32
+// heads does not fit LDS).  The workgroup keeps q~ of its heads in LDS as bf16 hi + lo (B operands); a wave
+// owns 32 rows of X per block (A operands straight from global memory).
 // ------------------------------------------------------------------------------------------------
 constexpr int XS_PAD = 8;   // bf16 elements of padding per q~ row in LDS (spreads the rows over the banks)
+constexpr size_t XS_LDS_MAX = 150 * 1024;
 
+template <int HT>
 __global__ __launch_bounds__(512) void xscores_kernel(const float* qt, const uint16_t* X, long x_bstride,
                                                       const int32_t* seq_lens, int T, int H, int dm, float scale,
                                                       float* S, int nblk) {
-  extern __shared__ __align__(16) uint16_t qs[];                    // [2][32][dm + XS_PAD]
+  extern __shared__ __align__(16) uint16_t qs[];                    // [2][HG][dm + XS_PAD]
+  constexpr int HG = 16 * HT;
   const int b = blockIdx.z, hg = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int n = lane & 15, kq = lane >> 4;
@@ -124,9 +128,9 @@ __global__ __launch_bounds__(512) void xscores_kernel(const float* qt, const uin
   if (row_base >= len) return;                        // (workgroup-uniform) nothing to score here
   {
     const int dm8 = dm >> 3;
-    for (int v = tid; v < 32 * dm8; v += 512) {       // 8 columns per item
+    for (int v = tid; v < HG * dm8; v += 512) {       // 8 columns per item
       const int hd = v / dm8, c = (v - hd * dm8) * 8;
-      const int h = hg * 32 + hd;
+      const int h = hg * HG + hd;
       float x[8];
       if (h < H) {
         const float* src = qt + ((size_t)b * H + h) * dm + c;
@@ -140,7 +144,7 @@ __global__ __launch_bounds__(512) void xscores_kernel(const float* qt, const uin
       bf16x8 hi, lo;
       split_hi_lo(x, hi, lo);
       *reinterpret_cast<bf16x8*>(&qs[hd * pitch + c]) = hi;
-      *reinterpret_cast<bf16x8*>(&qs[(32 + hd) * pitch + c]) = lo;
+      *reinterpret_cast<bf16x8*>(&qs[(HG + hd) * pitch + c]) = lo;
     }
   }
   __syncthreads();
@@ -159,15 +163,15 @@ __global__ __launch_bounds__(512) void xscores_kernel(const float* qt, const uin
       for (int u = 0; u < KH; ++u) a[rb][u] = *reinterpret_cast<const u32x4*>(xrow + min(kbase + u, nks - 1) * 32);
     }
   };
-  auto mma_part = [&](const u32x4 (&a)[2][KH], int kbase, f32x4 (&acc)[2][2]) {
+  auto mma_part = [&](const u32x4 (&a)[2][KH], int kbase, f32x4 (&acc)[2][HT]) {
 #pragma unroll
     for (int u = 0; u < KH; ++u) {
       if (kbase + u >= nks) break;
       const int coff = (kbase + u) * 32 + kq * 8;
 #pragma unroll
-      for (int ht = 0; ht < 2; ++ht) {
+      for (int ht = 0; ht < HT; ++ht) {
         const bf16x8 bh = *reinterpret_cast<const bf16x8*>(&qs[(ht * 16 + n) * pitch + coff]);
-        const bf16x8 bl = *reinterpret_cast<const bf16x8*>(&qs[(32 + ht * 16 + n) * pitch + coff]);
+        const bf16x8 bl = *reinterpret_cast<const bf16x8*>(&qs[(HG + ht * 16 + n) * pitch + coff]);
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb) {
           const bf16x8 a8 = __builtin_bit_cast(bf16x8, a[rb][u]);
@@ -180,19 +184,19 @@ __global__ __launch_bounds__(512) void xscores_kernel(const float* qt, const uin
   const int nparts = (nks + KH - 1) / KH;              // parts per block
   const int nb_here = min(nblk, (len - row_base + 255) / 256);
   const int total = nb_here * nparts;                  // parts this wave goes through
-  f32x4 acc[2][2];
+  f32x4 acc[2][HT];
 #pragma unroll
   for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-    for (int ht = 0; ht < 2; ++ht) acc[rb][ht] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int ht = 0; ht < HT; ++ht) acc[rb][ht] = f32x4{0.f, 0.f, 0.f, 0.f};
   auto flush = [&](int part) {                         // last part of a block: write its scores
     if ((part + 1) % nparts != 0) return;
     const int t0 = row_base + (part / nparts) * 256 + w * 32;
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-      for (int ht = 0; ht < 2; ++ht) {
-        const int h = hg * 32 + ht * 16 + n;           // D: column n = head, rows kq*4 + r
+      for (int ht = 0; ht < HT; ++ht) {
+        const int h = hg * HG + ht * 16 + n;           // D: column n = head, rows kq*4 + r
         if (h < H) {
           float* dst = S + ((size_t)b * H + h) * T + t0 + rb * 16 + kq * 4;
 #pragma unroll
@@ -348,7 +352,7 @@ __global__ __launch_bounds__(512) void xweighted_kernel(const float* S, const ui
 
 bool xcache_fast_ok(int dtype, int H, int d_model, int d_k) {
   return dtype == DT_BF16 && d_model % 128 == 0 && d_k % 32 == 0 && d_k >= 32 && H >= 1 &&
-         (size_t)2 * 32 * (d_model + XS_PAD) * 2 <= 150 * 1024;
+         (size_t)2 * 16 * (d_model + XS_PAD) * 2 <= XS_LDS_MAX;
 }
 
 int xcache_splits(int B, int H, int T, int d_model) {
@@ -369,19 +373,27 @@ void launch_xq_tilde(const float* q, const void* Wk, float* qt, int B, int H, in
 
 void launch_xscores(const float* qt, const void* X, long x_bstride, const int32_t* seq_lens, int T, int H,
                     int d_model, float scale, float* S, int B, hipStream_t st) {
+  // 32 heads per workgroup when their q~ fits LDS (and there are more than 16), else 16
+  const bool wide = H > 16 && (size_t)2 * 32 * (d_model + XS_PAD) * sizeof(uint16_t) <= XS_LDS_MAX;
+  const int HG = wide ? 32 : 16;
   // blocks of 256 rows per workgroup: about one workgroup per CU (the q~ operands are staged per workgroup)
-  const int blocks = (T + 255) / 256, per = ((H + 31) / 32) * B;
+  const int blocks = (T + 255) / 256, per = ((H + HG - 1) / HG) * B;
   int nblk = (blocks * per + 255) / 256;
   if (nblk < 1) nblk = 1;
-  dim3 grid((blocks + nblk - 1) / nblk, (H + 31) / 32, B);
-  const size_t lds = (size_t)2 * 32 * (d_model + XS_PAD) * sizeof(uint16_t);
+  dim3 grid((blocks + nblk - 1) / nblk, (H + HG - 1) / HG, B);
+  const size_t lds = (size_t)2 * HG * (d_model + XS_PAD) * sizeof(uint16_t);
   static bool raised = false;
   if (!raised) {
-    (void)hipFuncSetAttribute((const void*)xscores_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
+    (void)hipFuncSetAttribute((const void*)xscores_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)XS_LDS_MAX);
+    (void)hipFuncSetAttribute((const void*)xscores_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)XS_LDS_MAX);
     raised = true;
   }
-  hipLaunchKernelGGL(xscores_kernel, grid, dim3(512), lds, st, qt, (const uint16_t*)X, x_bstride, seq_lens, T, H,
-                     d_model, scale, S, nblk);
+  if (wide)
+    hipLaunchKernelGGL(xscores_kernel<2>, grid, dim3(512), lds, st, qt, (const uint16_t*)X, x_bstride, seq_lens, T, H,
+                       d_model, scale, S, nblk);
+  else
+    hipLaunchKernelGGL(xscores_kernel<1>, grid, dim3(512), lds, st, qt, (const uint16_t*)X, x_bstride, seq_lens, T, H,
+                       d_model, scale, S, nblk);
 }
 
 void launch_xweighted(const float* S, const void* X, long x_bstride, const int32_t* seq_lens, int T, int H,

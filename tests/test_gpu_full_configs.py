@@ -105,3 +105,19 @@ def test_config1_whole_attention_block_full():
     say(f"  vanilla block rel err {e:.3e}")
     assert e <= TOL["bf16"]
     assert row_rel_err(krow, k.k_new_rot) <= TOL["bf16"] and row_rel_err(vrow, k.v_new) <= TOL["bf16"]
+
+
+def test_config3_as_encoder_cache_sampled():
+    """Option 2 of the encoder-decoder section at config 3's size: the cross-attention layer reads the
+    encoder output E (B x 1500 x 1280) through slim_decode_xcache; no cross K or V cache exists."""
+    cfg = synth.scaled(C[3], kind="xcache")
+    say("[case] config 3 as E-cache (B=64 H=20 d=1280 T=1500); oracle on sequences 0, 21 and 63")
+    x = XCase(cfg, oracle_seqs={0, 21, 63})
+    out = x.run()
+    e = x.err(out)
+    say(f"  E-cache rel err {e:.3e}")
+    assert e <= TOL["bf16"]
+    g = x.run(variant=binding.VARIANT_GENERIC)
+    cross = head_rel_err(out, g.astype(np.float64), cfg.H)          # all 64 sequences, kernel vs kernel
+    say(f"  MFMA path vs plain kernels over the whole batch: {cross:.3e}")
+    assert cross <= TOL["bf16"]
