@@ -62,6 +62,15 @@ const char* slim_strerror(int code);
  * SLIM_ERR_ILLCOND (Wkv written) when the estimate is below 1e-12. */
 int slim_prepare_wkv(const double* Wk, const double* Wv, double* Wkv, int d, double* rcond_out);
 
+/* Non-square projections, option 1 of that section: W_K is d x e with e > d; its right inverse
+ * W_K^T (W_K W_K^T)^{-1} gives  W_KV = W_K^T (W_K W_K^T)^{-1} W_V  (e x e), and (X W_K) W_KV = X W_V.
+ * The decode step is then slim_decode on the e-wide K-cache with this e x e matrix (its `d` := e).
+ *   Wk, Wv : host fp64 row-major [d][e];  Wkv : host fp64 row-major [e][e], written
+ *   rcond_out: nullable; reciprocal condition estimate of W_K W_K^T (the square of W_K's)
+ * Errors as slim_prepare_wkv; SLIM_ERR_SHAPE when e < d. */
+int slim_prepare_wkv_nonsquare(const double* Wk, const double* Wv, double* Wkv, int d, int e,
+                               double* rcond_out);
+
 /* Cast a host fp64 row-major rows x cols matrix to the device element type (round to
  * nearest even, via fp32 for bf16), same row-major layout.  This is the form `W_KV`
  * (d x d) and the X-cache weights (d_model x e) are handed to the decode calls; the

@@ -13,6 +13,8 @@ What it computes (row-vector convention, W[in][out], head i = column block
                              concat(head_1..head_h) before W_O.  This is the reference
                              result; slim attention reaches exactly this result.
   * `wkv_by_inverse`      -- eq. 6 / App. A:  W_KV = inv(W_K) W_V in fp64.
+  * `wkv_right_inverse`   -- non-square section, option 1: W_KV from the right inverse of a
+                             d x e W_K.
   * `slim_option1/2`      -- the two evaluation orders of eq. 7, in fp64, used only to pin
                              the identity the GPU path relies on.
   * `xcache_decode_absorbed` -- the X-cache scheme of the non-square section (Fig. 4):
@@ -95,6 +97,14 @@ def vanilla_decode_from_x(x_q: np.ndarray, X: np.ndarray, W_K: np.ndarray, W_V: 
 def wkv_by_inverse(W_K: np.ndarray, W_V: np.ndarray) -> np.ndarray:
     """W_KV = W_K^{-1} W_V (eq. 6), the route App. A takes: explicit inverse, fp64."""
     return np.linalg.inv(np.asarray(W_K, np.float64)) @ np.asarray(W_V, np.float64)
+
+
+def wkv_right_inverse(W_K: np.ndarray, W_V: np.ndarray) -> np.ndarray:
+    """Non-square section, option 1: for W_K (d x e, e > d) the right inverse is
+    W_K^T (W_K W_K^T)^{-1}, so W_KV = W_K^T (W_K W_K^T)^{-1} W_V (e x e).  Written as printed:
+    an explicit inverse of the d x d term, fp64."""
+    W_K = np.asarray(W_K, np.float64)
+    return W_K.T @ np.linalg.inv(W_K @ W_K.T) @ np.asarray(W_V, np.float64)
 
 
 def slim_option1(q, K, W_KV, h):

@@ -19,7 +19,7 @@ SLIM_F32, SLIM_BF16 = 0, 1
 VARIANT_AUTO, VARIANT_GENERIC, VARIANT_FUSED_SPLIT, VARIANT_FUSED = 0, 1, 2, 3
 DTYPES = {"f32": SLIM_F32, "bf16": SLIM_BF16}
 
-EXPORTS = ("slim_strerror", "slim_prepare_wkv", "slim_pack_weights", "slim_rope_table", "slim_workspace_bytes",
+EXPORTS = ("slim_strerror", "slim_prepare_wkv", "slim_prepare_wkv_nonsquare", "slim_pack_weights", "slim_rope_table", "slim_workspace_bytes",
            "slim_workspace_bytes_xcache", "slim_workspace_bytes_block", "slim_attention_block", "vanilla_attention_block",
            "slim_variant_for", "slim_decode", "vanilla_kv_decode", "slim_decode_xcache")
 VARIANT_NAMES = {1: "generic", 2: "fused_split", 3: "fused"}
@@ -68,6 +68,8 @@ def load():
     lib.slim_strerror.argtypes = [ci]
     lib.slim_prepare_wkv.restype = ci
     lib.slim_prepare_wkv.argtypes = [vp, vp, vp, ci, cd]
+    lib.slim_prepare_wkv_nonsquare.restype = ci
+    lib.slim_prepare_wkv_nonsquare.argtypes = [vp, vp, vp, ci, ci, cd]
     lib.slim_pack_weights.restype = ci
     lib.slim_pack_weights.argtypes = [vp, vp, ci, ci, ci]
     lib.slim_rope_table.restype = ci
@@ -112,6 +114,22 @@ def slim_prepare_wkv(W_K: np.ndarray, W_V: np.ndarray, allow_illcond: bool = Fal
     rc = load().slim_prepare_wkv(W_K.ctypes.data, W_V.ctypes.data, out.ctypes.data, d, ctypes.byref(rcond))
     if rc != SLIM_OK and not (allow_illcond and rc == -7):
         raise SlimError(rc, "slim_prepare_wkv")
+    return out, rcond.value
+
+
+def slim_prepare_wkv_nonsquare(W_K: np.ndarray, W_V: np.ndarray):
+    """W_KV = W_K^T (W_K W_K^T)^{-1} W_V (e x e) for d x e projections, fp64 on the host.
+    Returns (W_KV, rcond of W_K W_K^T)."""
+    W_K = np.ascontiguousarray(W_K, dtype=np.float64)
+    W_V = np.ascontiguousarray(W_V, dtype=np.float64)
+    d, e = W_K.shape
+    if W_V.shape != (d, e):
+        raise ValueError("W_K and W_V must have the same d x e shape")
+    out = np.empty((e, e), dtype=np.float64)
+    rcond = ctypes.c_double(0.0)
+    rc = load().slim_prepare_wkv_nonsquare(W_K.ctypes.data, W_V.ctypes.data, out.ctypes.data, d, e, ctypes.byref(rcond))
+    if rc != SLIM_OK:
+        raise SlimError(rc, "slim_prepare_wkv_nonsquare")
     return out, rcond.value
 
 

@@ -145,28 +145,30 @@ double inverse_one_norm_estimate(const LU& f) {
 
 }  // namespace
 
-extern "C" int slim_prepare_wkv(const double* Wk, const double* Wv, double* Wkv, int d,
-                                double* rcond_out) {
-  if (!Wk || !Wv || !Wkv) return SLIM_ERR_ARG;
-  if (d < 1) return SLIM_ERR_SHAPE;
-  const long dd = (long)d * d;
+namespace {
+
+// X = A^{-1} B for A (d x d) and B, X (d x nr), row-major; see the header comment of this file.
+int lu_solve(const double* Wk, const double* Wv, double* Wkv, int d, int nr, double* rcond_out) {
+  const long dd = (long)d * d, dn = (long)d * nr;
 
   LU f;
   f.d = d;
   f.a.assign(Wk, Wk + dd);
   f.perm.resize(d);
   for (int i = 0; i < d; ++i) f.perm[i] = i;
-  std::vector<double> b(Wv, Wv + dd);
+  std::vector<double> b(Wv, Wv + dn);
 
   double amax = 0.0, anorm1 = 0.0;
   {
     std::vector<double> colsum(d, 0.0);
     for (long i = 0; i < dd; ++i) {
       const double v = f.a[i];
-      if (!std::isfinite(v) || !std::isfinite(b[i])) return SLIM_ERR_SINGULAR;
+      if (!std::isfinite(v)) return SLIM_ERR_SINGULAR;
       amax = std::max(amax, std::fabs(v));
       colsum[i % d] += std::fabs(v);
     }
+    for (long i = 0; i < dn; ++i)
+      if (!std::isfinite(b[i])) return SLIM_ERR_SINGULAR;
     for (double s : colsum) anorm1 = std::max(anorm1, s);
   }
   const double tiny = 2.220446049250313e-16 * d * amax;
@@ -187,7 +189,7 @@ extern "C" int slim_prepare_wkv(const double* Wk, const double* Wv, double* Wkv,
       if (!(best > tiny)) return SLIM_ERR_SINGULAR;
       if (p != j) {
         std::swap_ranges(A + (long)j * d, A + (long)j * d + d, A + (long)p * d);
-        std::swap_ranges(Bm + (long)j * d, Bm + (long)j * d + d, Bm + (long)p * d);
+        std::swap_ranges(Bm + (long)j * nr, Bm + (long)j * nr + nr, Bm + (long)p * nr);
         std::swap(f.perm[j], f.perm[p]);
       }
       const double inv = 1.0 / A[(long)j * d + j];
@@ -204,20 +206,20 @@ extern "C" int slim_prepare_wkv(const double* Wk, const double* Wv, double* Wkv,
     // --- row block: [A12 | B1] := L11^{-1} [A12 | B1]  (unit lower, rows k0..k1) ------------
     for (int i = k0 + 1; i < k1; ++i) {
       double* arow = A + (long)i * d;
-      double* brow = Bm + (long)i * d;
+      double* brow = Bm + (long)i * nr;
       for (int j = k0; j < i; ++j) {
         const double l = arow[j];
         const double* ar = A + (long)j * d;
-        const double* br = Bm + (long)j * d;
+        const double* br = Bm + (long)j * nr;
         for (int c = k1; c < d; ++c) arow[c] -= l * ar[c];
-        for (int c = 0; c < d; ++c) brow[c] -= l * br[c];
+        for (int c = 0; c < nr; ++c) brow[c] -= l * br[c];
       }
     }
     // --- trailing update: A22 -= A21 A12 ; B2 -= A21 B1 --------------------------------------
     parallel_rows(k1, d, 16, [&](int a, int e) {
       if (d - k1 > 0)
         rank_update(A + k1, d, A + k0, d, A + (long)k0 * d + k1, d, a, e, kb, d - k1);
-      rank_update(Bm, d, A + k0, d, Bm + (long)k0 * d, d, a, e, kb, d);
+      rank_update(Bm, nr, A + k0, d, Bm + (long)k0 * nr, nr, a, e, kb, nr);
     });
   }
 
@@ -226,25 +228,71 @@ extern "C" int slim_prepare_wkv(const double* Wk, const double* Wv, double* Wkv,
     const int k0 = std::max(0, k1 - NB);
     const int kb = k1 - k0;
     for (int j = k1 - 1; j >= k0; --j) {
-      double* brow = Bm + (long)j * d;
+      double* brow = Bm + (long)j * nr;
       const double inv = 1.0 / A[(long)j * d + j];
-      for (int c = 0; c < d; ++c) brow[c] *= inv;
+      for (int c = 0; c < nr; ++c) brow[c] *= inv;
       for (int i = k0; i < j; ++i) {
         const double u = A[(long)i * d + j];
-        double* bi = Bm + (long)i * d;
-        for (int c = 0; c < d; ++c) bi[c] -= u * brow[c];
+        double* bi = Bm + (long)i * nr;
+        for (int c = 0; c < nr; ++c) bi[c] -= u * brow[c];
       }
     }
     parallel_rows(0, k0, 16, [&](int a, int e) {
-      rank_update(Bm, d, A + k0, d, Bm + (long)k0 * d, d, a, e, kb, d);
+      rank_update(Bm, nr, A + k0, d, Bm + (long)k0 * nr, nr, a, e, kb, nr);
     });
   }
-  std::memcpy(Wkv, Bm, sizeof(double) * dd);
+  std::memcpy(Wkv, Bm, sizeof(double) * dn);
 
   const double inv_norm = inverse_one_norm_estimate(f);
   const double rcond = (anorm1 > 0 && inv_norm > 0) ? 1.0 / (anorm1 * inv_norm) : 0.0;
   if (rcond_out) *rcond_out = rcond;
   return rcond < 1e-12 ? SLIM_ERR_ILLCOND : SLIM_OK;
+}
+
+}  // namespace
+
+extern "C" int slim_prepare_wkv(const double* Wk, const double* Wv, double* Wkv, int d,
+                                double* rcond_out) {
+  if (!Wk || !Wv || !Wkv) return SLIM_ERR_ARG;
+  if (d < 1) return SLIM_ERR_SHAPE;
+  return lu_solve(Wk, Wv, Wkv, d, d, rcond_out);
+}
+
+// Non-square projections, option 1: W_K is d x e with e > d and has no inverse, but the right
+// inverse W_K^T (W_K W_K^T)^{-1} gives W_KV = W_K^T (W_K W_K^T)^{-1} W_V (e x e) with
+// (X W_K) W_KV = X W_V exactly.  G = W_K W_K^T is formed in fp64, G Z = W_V is solved with the same
+// LU (d x e right-hand sides), and W_KV = W_K^T Z.
+extern "C" int slim_prepare_wkv_nonsquare(const double* Wk, const double* Wv, double* Wkv, int d, int e,
+                                          double* rcond_out) {
+  if (!Wk || !Wv || !Wkv) return SLIM_ERR_ARG;
+  if (d < 1 || e < d) return SLIM_ERR_SHAPE;
+  std::vector<double> G((size_t)d * d), Z((size_t)d * e);
+  parallel_rows(0, d, 8, [&](int a, int b) {
+    for (int i = a; i < b; ++i)
+      for (int j = 0; j <= i; ++j) {
+        const double* ri = Wk + (size_t)i * e;
+        const double* rj = Wk + (size_t)j * e;
+        double s = 0.0;
+        for (int c = 0; c < e; ++c) s += ri[c] * rj[c];
+        G[(size_t)i * d + j] = s;
+      }
+  });
+  for (int i = 0; i < d; ++i)
+    for (int j = i + 1; j < d; ++j) G[(size_t)i * d + j] = G[(size_t)j * d + i];
+  const int rc = lu_solve(G.data(), Wv, Z.data(), d, e, rcond_out);
+  if (rc != SLIM_OK && rc != SLIM_ERR_ILLCOND) return rc;
+  parallel_rows(0, e, 8, [&](int a, int b) {
+    for (int i = a; i < b; ++i) {                       // row i of W_KV = sum_k W_K[k][i] Z[k][:]
+      double* out = Wkv + (size_t)i * e;
+      for (int c = 0; c < e; ++c) out[c] = 0.0;
+      for (int k = 0; k < d; ++k) {
+        const double w = Wk[(size_t)k * e + i];
+        const double* z = Z.data() + (size_t)k * e;
+        for (int c = 0; c < e; ++c) out[c] += w * z[c];
+      }
+    }
+  });
+  return rc;
 }
 
 extern "C" int slim_pack_weights(const double* W, void* dst_host, int rows, int cols, int dtype) {

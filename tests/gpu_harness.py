@@ -262,3 +262,47 @@ class BlockCase:
                                         c.B, c.H, c.T, c.d, **self._kw(**kw))
         torch.cuda.synchronize()
         return y.cpu().numpy(), self._new_rows(self.K_rot), self._new_rows(self.V)
+
+
+class NonSquareCase:
+    """Non-square projections, option 1: W_K and W_V are d x e (e > d), the cache holds the e-wide
+    keys K = X W_K, and W_KV (e x e) comes from the right inverse of W_K.  The decode step is the
+    ordinary slim_decode with its width set to e."""
+
+    def __init__(self, cfg: synth.Config, q_scale: float = 1.0):
+        assert cfg.kind == "xcache" and cfg.e > cfg.d
+        self.cfg = cfg
+        p = synth.make_problem(cfg)
+        B, T, e = cfg.B, cfg.T, cfg.e
+        q64 = p.q * q_scale
+        Kh = np.zeros((B, T, e), dtype=np.uint16 if cfg.dtype == "bf16" else np.float32)
+        Vh = np.zeros_like(Kh)
+        self.ref = np.empty((B, e))
+        for b, sq in enumerate(p.seqs):
+            K, V = orc_project(sq.X, p.w.W_K), orc_project(sq.X, p.w.W_V)
+            Kh[b], Vh[b] = synth.to_storage(K, cfg.dtype), synth.to_storage(V, cfg.dtype)
+            self.ref[b] = orc.vanilla_decode(q64[b], K, V, cfg.H)
+        wkv, self.rcond = binding.slim_prepare_wkv_nonsquare(p.w.W_K, p.w.W_V)
+        self.q = to_device(q64.astype(np.float32))
+        self.K, self.V = to_device(Kh), to_device(Vh)
+        self.Wkv = to_device(binding.slim_pack_weights(wkv, cfg.dtype))
+
+    def run_slim(self, **kw):
+        import torch
+        c = self.cfg
+        out = torch.full((c.B, c.e), float("nan"), device="cuda", dtype=torch.float32)
+        binding.slim_decode(self.q, self.K, self.Wkv, out, c.B, c.H, c.T, c.e, dtype=c.dtype, **kw)
+        torch.cuda.synchronize()
+        return out.cpu().numpy()
+
+    def run_vanilla(self):
+        import torch
+        c = self.cfg
+        out = torch.full((c.B, c.e), float("nan"), device="cuda", dtype=torch.float32)
+        binding.vanilla_kv_decode(self.q, self.K, self.V, out, c.B, c.H, c.T, c.e, dtype=c.dtype)
+        torch.cuda.synchronize()
+        return out.cpu().numpy()
+
+    def err(self, out):
+        assert np.isfinite(out).all(), "non-finite output"
+        return head_rel_err(out, self.ref, self.cfg.H)

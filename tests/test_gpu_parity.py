@@ -5,7 +5,7 @@ import numpy as np
 import pytest
 
 from paper_2503_05840_amd import binding, synth
-from gpu_harness import KCase, XCase, TOL, say
+from gpu_harness import KCase, NonSquareCase, XCase, TOL, say
 
 pytestmark = pytest.mark.gpu
 C = synth.CONFIGS
@@ -212,3 +212,21 @@ def test_xcache_mfma_path_agrees_with_plain_kernels_on_very_peaky_scores():
     e = head_rel_err(a, g.astype(np.float64), cfg.H)
     say(f"  rel diff {e:.3e}")
     assert e <= 1e-2          # bf16 weights and bf16 q~ operands vs fp32 arithmetic on the same inputs
+
+
+@pytest.mark.parametrize("name,cfg,q_scale", [
+    ("t5-like-r4", synth.scaled(C[4], B=2, H=8, d=256, d_k=128, T=700), 2.0),
+    ("r2-many-heads", synth.scaled(C[4], B=3, H=32, d=1024, d_k=64, T=300), 1.0),
+    ("r4-f32", synth.scaled(C[4], B=1, H=8, d=64, d_k=32, T=130, dtype="f32", x_pre_rounded=False), 4.0),
+])
+def test_nonsquare_option1_right_inverse_decode_matches_oracle(name, cfg, q_scale):
+    """Non-square section, option 1: e-wide K-cache, W_KV (e x e) from the right inverse of the d x e W_K."""
+    say(f"[case] non-square option 1 {name} (d={cfg.d}, e={cfg.e}, q x{q_scale})")
+    k = NonSquareCase(cfg, q_scale=q_scale)
+    for vname, variant in VARIANTS.items():
+        e = k.err(k.run_slim(variant=variant))
+        say(f"  slim {vname}: rel err {e:.3e} (rcond of W_K W_K^T {k.rcond:.2e})")
+        assert e <= TOL[cfg.dtype]
+    ev = k.err(k.run_vanilla())
+    say(f"  vanilla e-wide K+V: {ev:.3e}")
+    assert ev <= TOL[cfg.dtype]

@@ -455,3 +455,27 @@ def test_block_is_the_decode_step_between_its_projections():
     qr = orc.rope_encode((x @ W_Q)[None, :], h, [n], 100.0)[0]
     np.testing.assert_allclose(yr, orc.vanilla_decode_rope(qr, Xe @ W_K, Xe @ W_V, h, 100.0) @ W_O, rtol=1e-12)
     assert np.abs(yr - y).max() > 1e-3 * np.abs(y).max()
+
+
+# ------------------------------------------------------------------------------------------
+# non-square section, option 1: right inverse
+# ------------------------------------------------------------------------------------------
+def test_right_inverse_properties_and_decode_identity():
+    rng = np.random.default_rng(31)
+    d, e, h, n = 6, 16, 4, 11
+    W_K = rng.standard_normal((d, e)); W_V = rng.standard_normal((d, e))
+    X = rng.standard_normal((n, d)); q = rng.standard_normal(e)
+    W_KV = orc.wkv_right_inverse(W_K, W_V)
+    assert W_KV.shape == (e, e)
+    # the defining property, and the library's Moore-Penrose routine (full row rank: they coincide)
+    np.testing.assert_allclose(W_K @ W_KV, W_V, atol=1e-12)
+    np.testing.assert_allclose(W_KV, np.linalg.pinv(W_K) @ W_V, atol=1e-12)
+    # V from K, and the decode result over the e-wide K-cache
+    K, V = X @ W_K, X @ W_V
+    np.testing.assert_allclose(K @ W_KV, V, atol=1e-12)
+    ref = orc.vanilla_decode(q, K, V, h)
+    np.testing.assert_allclose(orc.slim_option2(q, K, W_KV, h), ref, rtol=1e-10)
+    np.testing.assert_allclose(orc.slim_option1(q, K, W_KV, h), ref, rtol=1e-10)
+    # a square W_K brings back eq. 6
+    W_sq = rng.standard_normal((d, d)); W_v2 = rng.standard_normal((d, d))
+    np.testing.assert_allclose(orc.wkv_right_inverse(W_sq, W_v2), orc.wkv_by_inverse(W_sq, W_v2), atol=1e-10)

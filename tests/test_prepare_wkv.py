@@ -5,6 +5,7 @@ import math
 import numpy as np
 import pytest
 
+from oracle import mha_oracle as orc
 from paper_2503_05840_amd import binding, synth
 
 
@@ -88,3 +89,33 @@ def test_pack_weights_rounding():
     assert f.dtype == np.float32 and np.array_equal(f, W.astype(np.float32))
     b = binding.slim_pack_weights(W, "bf16")
     assert b.dtype == np.uint16 and np.array_equal(b, synth.f64_to_bf16_bits(W))
+
+
+# ---- non-square projections, option 1 ----------------------------------------------------------
+@pytest.mark.parametrize("d,e", [(5, 12), (64, 256), (130, 200), (96, 96)])
+def test_nonsquare_right_inverse_matches_the_printed_formula(d, e):
+    rng = np.random.default_rng(100 + d)
+    W_K = rng.standard_normal((d, e)) / np.sqrt(d)
+    W_V = rng.standard_normal((d, e)) / np.sqrt(d)
+    got, rcond = binding.slim_prepare_wkv_nonsquare(W_K, W_V)
+    want = orc.wkv_right_inverse(W_K, W_V)
+    assert got.shape == (e, e)
+    assert np.abs(got - want).max() <= 1e-9 * np.abs(want).max()
+    assert np.abs(W_K @ got - W_V).max() <= 1e-10 * np.abs(W_V).max()      # W_K W_KV = W_V
+    assert 0 < rcond <= 1
+
+
+def test_nonsquare_from_the_config4_weights_recovers_v_from_k():
+    cfg = synth.scaled(synth.CONFIGS[4], B=1, H=8, d=64, d_k=32, T=50)
+    p = synth.make_problem(cfg)
+    W_KV, _ = binding.slim_prepare_wkv_nonsquare(p.w.W_K, p.w.W_V)
+    X = p.seqs[0].X
+    assert np.abs((X @ p.w.W_K) @ W_KV - X @ p.w.W_V).max() <= 1e-10
+
+
+def test_nonsquare_argument_checks():
+    lib = binding.load()
+    a = np.zeros((4, 8)); out = np.zeros((8, 8))
+    assert lib.slim_prepare_wkv_nonsquare(None, a.ctypes.data, out.ctypes.data, 4, 8, None) == -1
+    assert lib.slim_prepare_wkv_nonsquare(a.ctypes.data, a.ctypes.data, out.ctypes.data, 8, 4, None) == -2      # e < d
+    assert lib.slim_prepare_wkv_nonsquare(a.ctypes.data, a.ctypes.data, out.ctypes.data, 4, 8, None) == -6      # rank 0
