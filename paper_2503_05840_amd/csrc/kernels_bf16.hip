@@ -1131,17 +1131,24 @@ void launch_fused_stream(const FusedGeom& g, const FusedArgs& a, hipStream_t st)
 // Sequences per workgroup of the projection, in MFMA N tiles of 16 (1, 2 or 4).  One tile keeps the
 // kernel out of register spills and gives more workgroups; it costs one more pass over W_KV per 16
 // sequences, which is only worth it while those passes stay small.
-int proj_batch_tiles(int B, int rows, int e) {
+int proj_batch_tiles(int B, int rows, int e, int H) {
   if (B <= 16) return 1;
-  const long w_bytes = (long)rows * e * 2, chunks = (B + 15) / 16;
-  if (w_bytes * chunks <= (64L << 20)) return 1;
+  const long w_bytes = (long)rows * e * 2;
+  // The smallest batch tile whose grid is one round of workgroups (one per CU) with one 32-row tile of W
+  // per wave; W is read once per batch chunk (mostly from L2), which bounds the number of chunks.
+  const int csw = (rows + 8 * TILE_ROWS - 1) / (8 * TILE_ROWS);
+  for (int nbt = 1; nbt <= 2; nbt *= 2) {            // (four batch tiles per workgroup measured slower than two rounds)
+    const long chunks = (B + 16 * nbt - 1) / (16 * nbt);
+    if ((long)H * chunks * csw <= 256 && w_bytes * chunks <= (64L << 20)) return nbt;
+  }
+  if (w_bytes * ((B + 15) / 16) <= (64L << 20)) return 1;
   return B <= 32 ? 2 : 4;
 }
 
 int proj_row_splits(int H, int rows, int e, int B) {
   // one 32-row tile of W per wave (8 waves = 256 rows per workgroup) unless that makes more
   // workgroups than CUs
-  const int per = 16 * proj_batch_tiles(B, rows, e);
+  const int per = 16 * proj_batch_tiles(B, rows, e, H);
   const int zb = (B + per - 1) / per;
   int csw = (rows + 8 * TILE_ROWS - 1) / (8 * TILE_ROWS);
   const int cap = (256 + H * zb - 1) / (H * zb);      // one workgroup per CU: a single round
@@ -1155,7 +1162,7 @@ int proj_rows_per_split(int rows, int csw) {
 }
 
 void launch_project_mfma(ProjArgs a, hipStream_t st) {
-  const int nbt = proj_batch_tiles(a.B, a.rows, a.e);
+  const int nbt = proj_batch_tiles(a.B, a.rows, a.e, a.H);
   a.crows = proj_rows_per_split(a.rows, a.csw);
   dim3 grid(a.H, a.csw, (a.B + 16 * nbt - 1) / (16 * nbt)), block(512);
   if (nbt == 1) hipLaunchKernelGGL((project_mfma_kernel<1, false>), grid, block, 0, st, a);
@@ -1165,7 +1172,7 @@ void launch_project_mfma(ProjArgs a, hipStream_t st) {
 
 // out_m = x W_m for a.nmat matrices in one launch (a.Cpart = x, a.csw from dense_row_splits).
 void launch_dense_mfma(ProjArgs a, hipStream_t st) {
-  const int nbt = proj_batch_tiles(a.B, a.rows, a.e);
+  const int nbt = proj_batch_tiles(a.B, a.rows, a.e, a.H * a.nmat);
   a.crows = proj_rows_per_split(a.rows, a.csw);
   a.mode = 2;
   dim3 grid(a.H * a.nmat, a.csw, (a.B + 16 * nbt - 1) / (16 * nbt)), block(512);

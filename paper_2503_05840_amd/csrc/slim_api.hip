@@ -223,7 +223,7 @@ extern "C" int slim_decode(const void* q, const void* Kcache, const void* W_KV, 
   if (variant == SLIM_VARIANT_FUSED || variant == SLIM_VARIANT_FUSED_SPLIT) {
     const FusedGeom& g = p.geom;
     int* ctrl = (int*)(ws + p.off_ctrl);
-    const int per = 16 * proj_batch_tiles(B, d, d);
+    const int per = 16 * proj_batch_tiles(B, d, d, H);
     const int zb = (B + per - 1) / per;
     FusedArgs fa{};
     fa.q = (const float*)q; fa.K = (const uint16_t*)Kcache; fa.k_bstride = kb; fa.seq_lens = lens;
@@ -337,7 +337,7 @@ extern "C" int slim_decode_xcache(const void* q, const void* X, const void* W_K,
   if (req != SLIM_VARIANT_GENERIC && xcache_fast_ok(dtype, H, d_model, d_k) && H < CTRL_INTS / 2) {
     // MFMA path: q~, scores (log2 domain), weighted sum per context split, merge + projection
     int* ctrl = (int*)(ws + p.off_ctrl);
-    const int per = 16 * proj_batch_tiles(B, d_model, e);
+    const int per = 16 * proj_batch_tiles(B, d_model, e, H);
     const int zb = (B + per - 1) / per;
     launch_xq_tilde((const float*)q, W_K, qt, B, H, d_k, d_model, e, ctrl, H * zb, st);
     tm.mark();
@@ -386,8 +386,13 @@ BlockBufs block_layout(const Plan& p, int B, int H, int d) {
   b.off_k = o; o += row;
   b.off_v = o; o += row;
   b.off_attn = o; o += row;
-  // partial sums of the dense products: up to three matrices, each with at most the row splits of one
-  b.off_dpart = o; o += up(sizeof(float) * 3 * (size_t)proj_row_splits(H, d, d, B) * B * d);
+  // partial sums of the dense products: [matrix][row split][B][d] for one, two or three matrices
+  size_t parts = 1;
+  for (int nmat = 1; nmat <= 3; ++nmat) {
+    const size_t n = (size_t)nmat * dense_row_splits(H, nmat, d, d, B);
+    if (n > parts) parts = n;
+  }
+  b.off_dpart = o; o += up(sizeof(float) * parts * B * d);
   b.total = o;
   return b;
 }

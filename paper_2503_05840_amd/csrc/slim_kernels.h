@@ -121,7 +121,7 @@ int fused_by_sequence(const FusedGeom& g, int B, bool ragged);
 size_t fused_exch_bytes(const FusedGeom& g);
 bool xcd_round_robin(int device);
 void launch_fused_stream(const FusedGeom& g, const FusedArgs& a, hipStream_t st);
-int proj_batch_tiles(int B, int rows, int e);
+int proj_batch_tiles(int B, int rows, int e, int H);
 int proj_row_splits(int H, int rows, int e, int B);
 int proj_rows_per_split(int rows, int csw);
 void launch_project_mfma(ProjArgs a, hipStream_t st);
