@@ -13,6 +13,7 @@
 #include "slim_kernels.h"
 
 #include <math.h>
+#include <type_traits>
 
 namespace slim {
 namespace {
@@ -39,6 +40,32 @@ __device__ __forceinline__ void split_hi_lo(const float (&x)[8], bf16x8& hi, bf1
   }
 }
 
+// f(k + I, integral_constant<I>) for I = 0 .. N-1 while k + I < end: loop bodies whose register
+// buffers are chosen by a compile-time index.
+template <int I, int N, class F>
+__device__ __forceinline__ void unrolled_steps(int k, int end, F& f) {
+  if constexpr (I < N) {
+    if (k + I < end) f(k + I, std::integral_constant<int, I>{});
+    unrolled_steps<I + 1, N>(k, end, f);
+  }
+}
+
+// Workgroup barrier for data exchanged through LDS only: waits for this wave's LDS operations, not for its
+// global loads (__syncthreads() would also drain the tiles that are being prefetched from HBM).
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// The same without the bound checks, for whole groups of N steps (straight-line code: the compiler can
+// then count the loads in flight across steps).
+template <int I, int N, class F>
+__device__ __forceinline__ void full_steps(int k, F& f) {
+  if constexpr (I < N) {
+    f(k + I, std::integral_constant<int, I>{});
+    full_steps<I + 1, N>(k, f);
+  }
+}
+
 // 8 rows x 8 bf16 columns per lane  ->  8 operands (one per column), each 8 rows of that column.
 __device__ __forceinline__ void transpose8x8(const u32x4 (&kt)[8], u32x4 (&a)[8]) {
 #pragma unroll
@@ -53,14 +80,18 @@ __device__ __forceinline__ void transpose8x8(const u32x4 (&kt)[8], u32x4 (&a)[8]
 }
 
 // ------------------------------------------------------------------------------------------------
-// q~[b][h][c] = sum_j q[b][h d_k + j] W_K[c][h d_k + j]
+// q~[b][h][c] = scale * sum_j q[b][h d_k + j] W_K[c][h d_k + j]   (scale = log2(e) / sqrt(d_k)), written
+// as two bf16 arrays, hi = bf16(q~) and lo = bf16(q~ - hi), in the order the scores kernel's MFMA B operands
+// take them: [b][tile of 16 heads][k-step of 32 columns][lane = (column / 8 % 4) * 16 + head % 16][8 columns],
+// so that a wave reads one operand as 1 KB of consecutive bytes.
 // grid (H / XQ_HEADS, d_model / 128, batch chunks of 16); a wave owns 16 rows c of W_K for XQ_HEADS heads.
 // MFMA: A = W_K block (M = 16 rows c, K = the head's columns j), B = q^T (N = sequences) as hi + lo.
 // ------------------------------------------------------------------------------------------------
 constexpr int XQ_HEADS = 4;
 
-__global__ __launch_bounds__(512) void xq_tilde_kernel(const float* q, const uint16_t* Wk, float* qt, int B,
-                                                       int H, int d_k, int dm, int e, int* counters, int ncounters) {
+__global__ __launch_bounds__(512) void xq_tilde_kernel(const float* q, const uint16_t* Wk, uint16_t* qt, int B,
+                                                       int H, int d_k, int dm, int e, float scale, int* counters,
+                                                       int ncounters) {
   // (the arrival counters of the projection that ends this call start at 0)
   if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0)
     for (int i = threadIdx.x; i < ncounters; i += 512) counters[i] = 0;
@@ -99,150 +130,184 @@ __global__ __launch_bounds__(512) void xq_tilde_kernel(const float* q, const uin
       acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a8, hi, acc, 0, 0, 0);
       acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a8, lo, acc, 0, 0, 0);
     }
-    // D: column n = sequence, rows kq*4 + r = c0 + ...
-    if (b < B) *reinterpret_cast<f32x4*>(qt + ((size_t)b * H + h) * dm + c0 + kq * 4) = acc;
+    // D: column n = sequence, rows kq*4 + r = c0 + ...; stored scaled, as bf16 hi and lo halves
+    if (b < B) {
+      unsigned hw[2], lw[2];
+#pragma unroll
+      for (int r = 0; r < 4; r += 2) {
+        const float x0 = acc[r] * scale, x1 = acc[r + 1] * scale;
+        const __bf16 h0 = (__bf16)x0, h1 = (__bf16)x1;
+        const __bf16 l0 = (__bf16)(x0 - (float)h0), l1 = (__bf16)(x1 - (float)h1);
+        hw[r / 2] = (unsigned)__builtin_bit_cast(uint16_t, h0) | ((unsigned)__builtin_bit_cast(uint16_t, h1) << 16);
+        lw[r / 2] = (unsigned)__builtin_bit_cast(uint16_t, l0) | ((unsigned)__builtin_bit_cast(uint16_t, l1) << 16);
+      }
+      // B-operand order of the scores kernel: [b][head tile][k-step of 32 columns][lane (kq, n)][8]
+      const int c = c0 + kq * 4, nht = (H + 15) / 16;
+      const size_t at = ((((size_t)b * nht + h / 16) * (dm / 32) + c / 32) * 64 + ((c % 32) / 8) * 16 + h % 16) * 8 + c % 8;
+      *reinterpret_cast<uint2*>(qt + at) = make_uint2(hw[0], hw[1]);
+      *reinterpret_cast<uint2*>(qt + (size_t)B * nht * 16 * dm + at) = make_uint2(lw[0], lw[1]);
+    }
   }
 }
 
 // ------------------------------------------------------------------------------------------------
-// s[b][h][t] = scale * sum_c X[b][t][c] q~[b][h][c]       (scale = log2(e) / sqrt(d_k))
-// grid (row chunks of nblk x 256, ceil(H / HG), B), HG = 16 HT heads per workgroup (HT = 2 unless q~ of 32
-// heads does not fit LDS).  The workgroup keeps q~ of its heads in LDS as bf16 hi + lo (B operands); a wave
-// owns 32 rows of X per block (A operands straight from global memory).
+// Both passes over X share one layout: a workgroup stages tiles of X in LDS with coalesced loads
+// (every element of X leaves HBM once per pass) and its 8 waves split the HEADS: wave w owns head
+// tile (16 heads) w % P of the P tiles in flight, P = 1, 2, 4 or 8, and shares the rest of the work
+// with the 8 / P waves of the same head tile.  More than 16 P heads: several passes.
+//
+// xscores: s[b][h][t] = sum_c X[b][t][c] q~[b][h][c]   (log2 domain; q~ arrives scaled)
+// grid (blocks of 128 rows, B).  X is staged in chunks of 256 columns (double-buffered: the next chunk
+// travels HBM -> registers while this one is used, then registers -> LDS).  Per chunk a wave holds the
+// B operands of its head tile (hi + lo, 8 k-steps) in registers and runs over its M tiles of 16 rows:
+// A operands come from LDS (16 bytes per lane: row m, columns ks*32 + kq*8).
 // ------------------------------------------------------------------------------------------------
-constexpr int XS_PAD = 8;   // bf16 elements of padding per q~ row in LDS (spreads the rows over the banks)
-constexpr size_t XS_LDS_MAX = 150 * 1024;
+constexpr int XL_RB = 128;               // rows per workgroup
+constexpr int XL_KC = 128;               // columns per chunk
+constexpr int XL_KS = XL_KC / 32;        // k-steps per chunk
+constexpr int XL_PITCH = XL_KC + 8;      // bf16 elements per staged row (16 bytes of padding)
+constexpr int XL_AHEAD = 4;              // chunks of X in flight from HBM (register sets)
 
-template <int HT>
-__global__ __launch_bounds__(512) void xscores_kernel(const float* qt, const uint16_t* X, long x_bstride,
-                                                      const int32_t* seq_lens, int T, int H, int dm, float scale,
-                                                      float* S, int nblk) {
-  extern __shared__ __align__(16) uint16_t qs[];                    // [2][HG][dm + XS_PAD]
-  constexpr int HG = 16 * HT;
-  const int b = blockIdx.z, hg = blockIdx.y;
+template <int P>
+__global__ __launch_bounds__(512) void xscores_kernel(const uint16_t* qt, const uint16_t* X, long x_bstride,
+                                                      const int32_t* seq_lens, int T, int B, int H, int dm, float* S) {
+  __shared__ __align__(16) uint16_t xs[2][XL_RB * XL_PITCH];
+  constexpr int RS = 8 / P;                            // waves per head tile = row subsets
+  constexpr int D = XL_AHEAD;
+  const int b = blockIdx.y, row_base = blockIdx.x * XL_RB;
+  const int len = seq_len_of(seq_lens, b, T);
+  if (row_base >= len) return;                         // (workgroup-uniform)
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int n = lane & 15, kq = lane >> 4;
-  const int pitch = dm + XS_PAD;
-  const int len = seq_len_of(seq_lens, b, T);
-  const int row_base = blockIdx.x * nblk * 256;       // this workgroup: nblk blocks of 256 rows
-  if (row_base >= len) return;                        // (workgroup-uniform) nothing to score here
-  {
-    const int dm8 = dm >> 3;
-    for (int v = tid; v < HG * dm8; v += 512) {       // 8 columns per item
-      const int hd = v / dm8, c = (v - hd * dm8) * 8;
-      const int h = hg * HG + hd;
-      float x[8];
-      if (h < H) {
-        const float* src = qt + ((size_t)b * H + h) * dm + c;
-        const f32x4 lo4 = *reinterpret_cast<const f32x4*>(src), hi4 = *reinterpret_cast<const f32x4*>(src + 4);
+  const int htl = w % P, rs = w / P;
+  const int NHT = (H + 15) / 16;
+  const int nkc = dm / XL_KC, npass = (NHT + P - 1) / P;   // (dm is a multiple of 128)
+  const int total = npass * nkc;
+  const uint16_t* Xb = X + (size_t)b * x_bstride;
+  const size_t lo_off = (size_t)B * NHT * 16 * dm;     // the lo halves follow the hi halves
+  const int Tp = (T + 31) / 32 * 32;                   // rows of S are padded to whole tiles
+
+  // staging: thread t moves 16-byte column chunk t % 16 of rows t / 16 + 32 i
+  const int srow = tid >> 4, scol = (tid & 15) * 8;
+  u32x4 stg[D][4];
+  auto issue_x = [&](u32x4 (&g)[4], int it) {
+    const int col = (it % nkc) * XL_KC + scol;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) { x[j] = lo4[j] * scale; x[4 + j] = hi4[j] * scale; }
-      } else {
-#pragma unroll
-        for (int j = 0; j < 8; ++j) x[j] = 0.f;
-      }
-      bf16x8 hi, lo;
-      split_hi_lo(x, hi, lo);
-      *reinterpret_cast<bf16x8*>(&qs[hd * pitch + c]) = hi;
-      *reinterpret_cast<bf16x8*>(&qs[(HG + hd) * pitch + c]) = lo;
-    }
-  }
-  __syncthreads();
-  const int nks = dm / 32;                             // a multiple of 4
-  const uint16_t* Xb = X + (size_t)b * x_bstride + kq * 8;
-  // A wave owns 32 rows of a 256-row block (two A operands share every B operand read from LDS);
-  // 8 k-steps (256 columns) of A operands per buffer, the other buffer is in flight meanwhile.
-  constexpr int KH = 8;
-  u32x4 a0[2][KH], a1[2][KH];
-  auto load_part = [&](u32x4 (&a)[2][KH], int blk, int kbase) {
-    const int t0 = row_base + blk * 256 + w * 32;
-#pragma unroll
-    for (int rb = 0; rb < 2; ++rb) {
-      const uint16_t* xrow = Xb + (size_t)min(t0 + rb * 16 + n, len - 1) * dm;
-#pragma unroll
-      for (int u = 0; u < KH; ++u) a[rb][u] = *reinterpret_cast<const u32x4*>(xrow + min(kbase + u, nks - 1) * 32);
+    for (int i = 0; i < 4; ++i) {
+      const int r = min(row_base + srow + 32 * i, len - 1);   // rows past the end: any finite values, never stored
+      g[i] = *reinterpret_cast<const u32x4*>(Xb + (size_t)r * dm + col);
     }
   };
-  auto mma_part = [&](const u32x4 (&a)[2][KH], int kbase, f32x4 (&acc)[2][HT]) {
+  auto commit_x = [&](const u32x4 (&g)[4], int it) {
 #pragma unroll
-    for (int u = 0; u < KH; ++u) {
-      if (kbase + u >= nks) break;
-      const int coff = (kbase + u) * 32 + kq * 8;
+    for (int i = 0; i < 4; ++i)
+      *reinterpret_cast<u32x4*>(&xs[it & 1][(srow + 32 * i) * XL_PITCH + scol]) = g[i];
+  };
+  // B operands of iteration it (head tile and chunk): 1 KB of consecutive bytes per operand
+  auto load_b = [&](u32x4 (&bh)[XL_KS], u32x4 (&bl)[XL_KS], int it) {
+    const int ht = min((it / nkc) * P + htl, NHT - 1), kc = it % nkc;
+    const uint16_t* src = qt + ((((size_t)b * NHT + ht) * (dm / 32) + (size_t)kc * XL_KS) * 64 + lane) * 8;
 #pragma unroll
-      for (int ht = 0; ht < HT; ++ht) {
-        const bf16x8 bh = *reinterpret_cast<const bf16x8*>(&qs[(ht * 16 + n) * pitch + coff]);
-        const bf16x8 bl = *reinterpret_cast<const bf16x8*>(&qs[(HG + ht * 16 + n) * pitch + coff]);
+    for (int ks = 0; ks < XL_KS; ++ks) {
+      bh[ks] = *reinterpret_cast<const u32x4*>(src + ks * 512);
+      bl[ks] = *reinterpret_cast<const u32x4*>(src + lo_off + ks * 512);
+    }
+  };
+
+  f32x4 acc[P];
+  u32x4 bh[XL_KS], bl[XL_KS], nh[XL_KS], nl[XL_KS];
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb) {
-          const bf16x8 a8 = __builtin_bit_cast(bf16x8, a[rb][u]);
-          acc[rb][ht] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a8, bh, acc[rb][ht], 0, 0, 0);
-          acc[rb][ht] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a8, bl, acc[rb][ht], 0, 0, 0);
+  for (int j = 0; j < D; ++j) issue_x(stg[j], min(j, total - 1));
+  load_b(bh, bl, 0);
+  commit_x(stg[0], 0);
+  lds_barrier();
+  // One chunk; SI is it % D as a type: the register set whose chunk (it) has already gone to LDS.
+  auto step = [&](int it, auto SI) {
+    constexpr int si = decltype(SI)::value;
+    const int hp = it / nkc, kc = it % nkc;
+    const bool more = it + 1 < total;
+    // (a wave's loads complete in issue order: what the next chunk needs goes first, so that waiting for it
+    //  does not wait for the X chunk that is D chunks away)
+    // Issued unconditionally (past the end: the last chunk again, unused) so that the compiler can count
+    // the loads in flight and wait for exactly the ones a step needs.
+    load_b(nh, nl, min(it + 1, total - 1));
+    issue_x(stg[si], min(it + D, total - 1));
+    const int ht = hp * P + htl;
+    if (kc == 0) {
+#pragma unroll
+      for (int mi = 0; mi < P; ++mi) acc[mi] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    if (ht < NHT) {
+      const uint16_t* xa = &xs[it & 1][n * XL_PITCH + kq * 8];
+#pragma unroll
+      for (int mi = 0; mi < P; ++mi) {
+        const int mt = rs + mi * RS;                   // this wave's M tiles: rs, rs + RS, ...
+#pragma unroll
+        for (int ks = 0; ks < XL_KS; ++ks) {
+          const bf16x8 a8 = *reinterpret_cast<const bf16x8*>(xa + mt * 16 * XL_PITCH + ks * 32);
+          acc[mi] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a8, __builtin_bit_cast(bf16x8, bh[ks]), acc[mi], 0, 0, 0);
+          acc[mi] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a8, __builtin_bit_cast(bf16x8, bl[ks]), acc[mi], 0, 0, 0);
         }
       }
-    }
-  };
-  const int nparts = (nks + KH - 1) / KH;              // parts per block
-  const int nb_here = min(nblk, (len - row_base + 255) / 256);
-  const int total = nb_here * nparts;                  // parts this wave goes through
-  f32x4 acc[2][HT];
-#pragma unroll
-  for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-    for (int ht = 0; ht < HT; ++ht) acc[rb][ht] = f32x4{0.f, 0.f, 0.f, 0.f};
-  auto flush = [&](int part) {                         // last part of a block: write its scores
-    if ((part + 1) % nparts != 0) return;
-    const int t0 = row_base + (part / nparts) * 256 + w * 32;
-#pragma unroll
-    for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-      for (int ht = 0; ht < HT; ++ht) {
-        const int h = hg * HG + ht * 16 + n;           // D: column n = head, rows kq*4 + r
+      if (kc == nkc - 1) {                             // D: column n = head, rows kq*4 + r
+        const int h = ht * 16 + n;
         if (h < H) {
-          float* dst = S + ((size_t)b * H + h) * T + t0 + rb * 16 + kq * 4;
 #pragma unroll
-          for (int r = 0; r < 4; ++r)
-            if (t0 + rb * 16 + kq * 4 + r < len) dst[r] = acc[rb][ht][r];
+          for (int mi = 0; mi < P; ++mi) {
+            const int t0 = row_base + (rs + mi * RS) * 16 + kq * 4;
+            float* dst = S + ((size_t)b * H + h) * Tp + t0;
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+              if (t0 + r < len) dst[r] = acc[mi][r];
+          }
         }
-        acc[rb][ht] = f32x4{0.f, 0.f, 0.f, 0.f};
       }
-  };
-  load_part(a0, 0, 0);
-  for (int i = 0; i < total; i += 2) {                 // even parts in a0, odd parts in a1
-    if (i + 1 < total) load_part(a1, (i + 1) / nparts, ((i + 1) % nparts) * KH);
-    mma_part(a0, (i % nparts) * KH, acc);
-    flush(i);
-    if (i + 2 < total) load_part(a0, (i + 2) / nparts, ((i + 2) % nparts) * KH);
-    if (i + 1 < total) {
-      mma_part(a1, ((i + 1) % nparts) * KH, acc);
-      flush(i + 1);
     }
-  }
+    if (more) {
+      commit_x(stg[(si + 1) % D], it + 1);
+#pragma unroll
+      for (int ks = 0; ks < XL_KS; ++ks) { bh[ks] = nh[ks]; bl[ks] = nl[ks]; }
+    }
+    lds_barrier();
+  };
+  int it = 0;
+  for (; it + D <= total; it += D) full_steps<0, D>(it, step);
+  unrolled_steps<0, D>(it, total, step);
 }
 
 // ------------------------------------------------------------------------------------------------
-// Weighted sum of the rows of X for one (sequence, context split, group of 32 heads, block of
-// 1024 columns): wave w owns columns [128 w, 128 w + 128) of the block and all rows of the split.
+// Weighted sum of the rows of X for one (sequence, context split, group of 32 heads, block of 128
+// columns).  The 8 waves of the workgroup split the ROWS of the split (wave w takes 32-row tiles w,
+// w + 8, ...) and merge their (m, l, C) through LDS at the end, so one partial leaves per workgroup:
+// splitting the context across workgroups instead costs H x d_model x 4 bytes of partial per split and
+// sequence, which at 8 splits was four times the bytes of X itself.
 // Register tile and MFMA layout as in the K-cache stream kernel: lane (idx = l % 16, rg = l / 16)
 // loads 16 bytes of rows rg*8 .. rg*8+7, transposes its 8x8 block into 8 A operands; B = weights
 // P^T (lane (n = head, kg = row group) reads 8 consecutive scores of head n).
 // Writes Cpart[(b nsplit + s)][h][c] (unnormalised), mpart (log2 domain) and lpart.
 // ------------------------------------------------------------------------------------------------
+constexpr float XW_SLACK = 6.0f;
+
 __global__ __launch_bounds__(512) void xweighted_kernel(const float* S, const uint16_t* X, long x_bstride,
                                                         const int32_t* seq_lens, int T, int H, int dm, int nsplit,
                                                         float* Cpart, float* mpart, float* lpart) {
-  constexpr int NT = 2;
+  constexpr int NT = 2, NW = 8;
+  __shared__ float red[NW][NT][4][8][64];              // [wave][head tile][r][i][lane]: 128 KB
+  __shared__ float msh[NW][NT * 16], lsh[NW][NT * 16];
   const int b = blockIdx.z, s = blockIdx.x;
-  const int nhg = (H + 31) / 32;
-  const int hg = blockIdx.y % nhg, cb = blockIdx.y / nhg;
+  const int ncb = dm / 128;
+  const int cbk = blockIdx.y % ncb, hg = blockIdx.y / ncb;   // (the head groups of a column block: same XCD when ncb % 8 == 0)
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int idx = lane & 15, rg = lane >> 4;
   const int n = idx, kg = rg;
-  const int col0 = cb * 1024 + w * 128;
-  if (col0 >= dm) return;
+  const int col0 = cbk * 128;
   const int len = seq_len_of(seq_lens, b, T);
   const int rows_per = ((len + nsplit - 1) / nsplit + 31) / 32 * 32;
   const int r_lo = s * rows_per, r_hi = min(len, r_lo + rows_per);
   const int pid = b * nsplit + s;
+  const int ntile_all = r_lo < r_hi ? (r_hi - r_lo + 31) / 32 : 0;
+  const int ntile = ntile_all > w ? (ntile_all - w + NW - 1) / NW : 0;   // this wave's tiles: w, w + 8, ...
+  auto row_of = [&](int k) { return r_lo + 32 * (w + NW * k); };
 
   float m[NT];
   f32x4 acc[8][NT], accl[NT];
@@ -253,46 +318,63 @@ __global__ __launch_bounds__(512) void xweighted_kernel(const float* S, const ui
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc[i][t] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
-  const uint16_t* Xb = X + (size_t)b * x_bstride + col0 + idx * 8;
+  // Rows are addressed by 32-bit byte offsets from the sequence's base (a sequence of X is below 4 GB:
+  // checked on the host); rows past the end re-read the last row and weigh nothing (their scores are masked).
+  const char* Xb = reinterpret_cast<const char*>(X + (size_t)b * x_bstride + col0 + idx * 8);
+  const unsigned pitchB = (unsigned)dm * 2u;
   auto load_tile = [&](u32x4 (&t)[8], int r0) {
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      const int r = min(r0 + rg * 8 + j, len - 1);     // rows past the end weigh nothing (masked below)
-      t[j] = *reinterpret_cast<const u32x4*>(Xb + (size_t)r * dm);   // (re-read by the other head groups: keep it cached)
+      const unsigned off = __umul24((unsigned)min(r0 + rg * 8 + j, len - 1), pitchB);
+      t[j] = *reinterpret_cast<const u32x4*>(Xb + off);
     }
   };
-  // scores of a tile: lane (n, kg) takes rows r0 + kg*8 .. +7 of heads hg*32 + t*16 + n
-  const bool vec_ok = (T % 4) == 0;                  // 16-byte aligned rows of S
-  auto load_scores = [&](float (&x)[NT][8], int r0) {
+  // scores of a tile: lane (n, kg) takes rows r0 + kg*8 .. +7 of heads hg*32 + t*16 + n.  The rows of S
+  // are padded to a multiple of 32 floats, so the 32 bytes are always there; what lies past the end of
+  // the split (or belongs to a padded head) is replaced, not computed with.
+  const int Tp = (T + 31) / 32 * 32;
+  auto load_scores = [&](f32x4 (&x)[NT][2], int r0) {    // (raw: masked when used, so that nothing waits here)
     const int row = r0 + kg * 8;
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
-      const int h = hg * 32 + t * 16 + n;
-      const float* src = S + ((size_t)b * H + min(h, H - 1)) * T + row;
-      if (h < H && row + 8 <= r_hi && vec_ok) {
-        const f32x4 lo4 = *reinterpret_cast<const f32x4*>(src), hi4 = *reinterpret_cast<const f32x4*>(src + 4);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) { x[t][j] = lo4[j]; x[t][4 + j] = hi4[j]; }
-      } else {
-#pragma unroll
-        for (int j = 0; j < 8; ++j) x[t][j] = (h < H && row + j < r_hi) ? src[j] : NEG_INF;
-      }
+      const int h = min(hg * 32 + t * 16 + n, H - 1);
+      const float* src = S + ((size_t)b * H + h) * Tp + row;
+      x[t][0] = *reinterpret_cast<const f32x4*>(src);
+      x[t][1] = *reinterpret_cast<const f32x4*>(src + 4);
     }
   };
-  u32x4 cur[8], nxt[8];
-  float sx[NT][8], sn[NT][8];
-  if (r_lo < r_hi) { load_tile(cur, r_lo); load_scores(sx, r_lo); }
-  for (int r0 = r_lo; r0 < r_hi; r0 += 32) {
-    const bool more = r0 + 32 < r_hi;
-    if (more) { load_tile(nxt, r0 + 32); load_scores(sn, r0 + 32); }
+  // X tiles travel HBM/L2 -> registers D tiles ahead, scores DS tiles ahead (register sets chosen by a
+  // compile-time index).  A step's work is short next to the latency of a load, so what it needs must
+  // have been requested several steps earlier.  Loads past the end re-read the last tile (unused) so that
+  // every step issues the same loads and the compiler can wait for exactly the ones a step needs.
+  constexpr int D = 2, DS = 2, UN = 2;                 // X sets, score sets, steps per unrolled group (a common multiple)
+  u32x4 xt[D][8];
+  f32x4 sc[DS][NT][2];
+  if (ntile > 0) {
+#pragma unroll
+    for (int j = 0; j < DS; ++j) load_scores(sc[j], row_of(min(j, ntile - 1)));
+#pragma unroll
+    for (int j = 0; j < D; ++j) load_tile(xt[j], row_of(min(j, ntile - 1)));
+  }
+  auto step = [&](int k, auto SI) {
+    constexpr int si = decltype(SI)::value;
+    u32x4 (&cur)[8] = xt[si % D];
+    f32x4 (&sx)[NT][2] = sc[si % DS];
+    const int row = row_of(k) + kg * 8;
     bf16x8 pb[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
-      float (&x)[8] = sx[t];
+      const int live = (hg * 32 + t * 16 + n < H) ? r_hi - row : 0;   // rows of this lane that count
+      float x[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) x[j] = j < live ? sx[t][j >> 2][j & 3] : NEG_INF;
       float tmax = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
       tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
       tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-      const float mn = fmaxf(m[t], tmax);
+      // The reference the weights are taken against moves only when the maximum has grown by more than
+      // XW_SLACK (log2 domain): weights stay below 2^XW_SLACK, which costs bf16 and the fp32 sums nothing,
+      // and the accumulators are rescaled rarely instead of at nearly every tile.
+      const float mn = (tmax > m[t] + XW_SLACK) ? tmax : m[t];
       const float ref = (mn == NEG_INF) ? 0.f : mn;
       const float alpha = __builtin_amdgcn_exp2f(m[t] - ref);
 #pragma unroll
@@ -306,6 +388,9 @@ __global__ __launch_bounds__(512) void xweighted_kernel(const float* S, const ui
     }
     u32x4 am[8];
     transpose8x8(cur, am);
+    // both sets are free again: the scores of the wave's tile k + DS first, then X of its tile k + D
+    load_scores(sx, row_of(min(k + DS, ntile - 1)));
+    load_tile(cur, row_of(min(k + D, ntile - 1)));
     const u32x4 ones_bits = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
     const bf16x8 ones = __builtin_bit_cast(bf16x8, ones_bits);
 #pragma unroll
@@ -317,88 +402,107 @@ __global__ __launch_bounds__(512) void xweighted_kernel(const float* S, const ui
       for (int t = 0; t < NT; ++t)
         acc[i][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, pb[t], acc[i][t], 0, 0, 0);
     }
-    if (more) {
+  };
+  int k = 0;
+  for (; k + UN <= ntile; k += UN) full_steps<0, UN>(k, step);
+  unrolled_steps<0, UN>(k, ntile, step);
+
+  // ---- merge the 8 waves: common maximum per head, rescale, sum through LDS ---------------------
+  // (a lane's accumulators of head tile t all belong to head t*16 + n: the D operand's column)
+  if (kg == 0) {
 #pragma unroll
-      for (int j = 0; j < 8; ++j) cur[j] = nxt[j];
-#pragma unroll
-      for (int t = 0; t < NT; ++t)
-#pragma unroll
-        for (int j = 0; j < 8; ++j) sx[t][j] = sn[t][j];
-    }
+    for (int t = 0; t < NT; ++t) msh[w][t * 16 + n] = m[t];
   }
-  // acc[i][t][r]: column col0 + (rg*4 + r)*8 + i, head hg*32 + t*16 + n
+  __syncthreads();
+  float mall[NT];
 #pragma unroll
   for (int t = 0; t < NT; ++t) {
+    float mm = NEG_INF;
+#pragma unroll
+    for (int ww = 0; ww < NW; ++ww) mm = fmaxf(mm, msh[ww][t * 16 + n]);
+    mall[t] = mm;
+    const float sc = (m[t] == NEG_INF) ? 0.f : __builtin_amdgcn_exp2f(m[t] - mm);
+    if (kg == 0) lsh[w][t * 16 + n] = accl[t][0] * sc;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) red[w][t][r][i][lane] = acc[i][t][r] * sc;
+  }
+  __syncthreads();
+  // thread (t, r, lane): columns col0 + (rg*4 + r)*8 .. +7 of head hg*32 + t*16 + n
+  {
+    const int t = w >> 2, r = w & 3;
     const int h = hg * 32 + t * 16 + n;
-    if (h >= H) continue;
-    float* dst = Cpart + ((size_t)pid * H + h) * dm + col0;
+    float o[8];
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const int c = (rg * 4 + r) * 8;
-      f32x4 lo4, hi4;
+    for (int i = 0; i < 8; ++i) {
+      float sum = 0.f;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) { lo4[i] = acc[i][t][r]; hi4[i] = acc[4 + i][t][r]; }
-      *reinterpret_cast<f32x4*>(dst + c) = lo4;
-      *reinterpret_cast<f32x4*>(dst + c + 4) = hi4;
+      for (int ww = 0; ww < NW; ++ww) sum += red[ww][t][r][i][lane];
+      o[i] = sum;
     }
-    if (cb == 0 && w == 0 && kg == 0) {
-      mpart[(size_t)pid * H + h] = m[t];
-      lpart[(size_t)pid * H + h] = accl[t][0];
+    if (h < H) {
+      float* dst = Cpart + ((size_t)pid * H + h) * dm + col0 + (rg * 4 + r) * 8;
+      *reinterpret_cast<f32x4*>(dst) = f32x4{o[0], o[1], o[2], o[3]};
+      *reinterpret_cast<f32x4*>(dst + 4) = f32x4{o[4], o[5], o[6], o[7]};
+      if (cbk == 0 && r == 0 && kg == 0) {
+        float l = 0.f;
+#pragma unroll
+        for (int ww = 0; ww < NW; ++ww) l += lsh[ww][t * 16 + n];
+        mpart[(size_t)pid * H + h] = mall[t];
+        lpart[(size_t)pid * H + h] = l;
+      }
     }
   }
 }
 
 }  // namespace
 
+// Head tiles in flight for H heads: 1, 2, 4 or 8.
+static int head_tiles_in_flight(int H) {
+  const int nht = (H + 15) / 16;
+  int p = 1;
+  while (p < nht && p < 8) p *= 2;
+  return p;
+}
 bool xcache_fast_ok(int dtype, int H, int d_model, int d_k) {
-  return dtype == DT_BF16 && d_model % 128 == 0 && d_k % 32 == 0 && d_k >= 32 && H >= 1 &&
-         (size_t)2 * 16 * (d_model + XS_PAD) * 2 <= XS_LDS_MAX;
+  return dtype == DT_BF16 && d_model % 128 == 0 && d_k % 32 == 0 && d_k >= 32 && H >= 1 && d_model < (1 << 22);
 }
 
 int xcache_splits(int B, int H, int T, int d_model) {
-  const int per = B * ((H + 31) / 32) * ((d_model + 1023) / 1024);
+  // The weighted sum runs one workgroup per (split, 32 heads, 128 columns, sequence): split the context
+  // across workgroups only as far as it takes to fill the chip (every split costs a partial).
+  const int per = B * ((H + 31) / 32) * (d_model >= 128 ? d_model / 128 : 1);
   int s = (256 + per - 1) / per;
-  const int cap = (T + 127) / 128;
+  const int cap = (T + 255) / 256;
   if (s > cap) s = cap;
   if (s > PROJ_MAX_PARTS) s = PROJ_MAX_PARTS;
   return s < 1 ? 1 : s;
 }
 
 void launch_xq_tilde(const float* q, const void* Wk, float* qt, int B, int H, int d_k, int d_model, int e,
-                     int* counters, int ncounters, hipStream_t st) {
+                     float scale, int* counters, int ncounters, hipStream_t st) {
   dim3 grid((H + XQ_HEADS - 1) / XQ_HEADS, (d_model + 127) / 128, (B + 15) / 16);
-  hipLaunchKernelGGL(xq_tilde_kernel, grid, dim3(512), 0, st, q, (const uint16_t*)Wk, qt, B, H, d_k, d_model, e,
-                     counters, ncounters);
+  hipLaunchKernelGGL(xq_tilde_kernel, grid, dim3(512), 0, st, q, (const uint16_t*)Wk, (uint16_t*)qt, B, H, d_k, d_model,
+                     e, scale, counters, ncounters);
 }
 
 void launch_xscores(const float* qt, const void* X, long x_bstride, const int32_t* seq_lens, int T, int H,
-                    int d_model, float scale, float* S, int B, hipStream_t st) {
-  // 32 heads per workgroup when their q~ fits LDS (and there are more than 16), else 16
-  const bool wide = H > 16 && (size_t)2 * 32 * (d_model + XS_PAD) * sizeof(uint16_t) <= XS_LDS_MAX;
-  const int HG = wide ? 32 : 16;
-  // blocks of 256 rows per workgroup: about one workgroup per CU (the q~ operands are staged per workgroup)
-  const int blocks = (T + 255) / 256, per = ((H + HG - 1) / HG) * B;
-  int nblk = (blocks * per + 255) / 256;
-  if (nblk < 1) nblk = 1;
-  dim3 grid((blocks + nblk - 1) / nblk, (H + HG - 1) / HG, B);
-  const size_t lds = (size_t)2 * HG * (d_model + XS_PAD) * sizeof(uint16_t);
-  static bool raised = false;
-  if (!raised) {
-    (void)hipFuncSetAttribute((const void*)xscores_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)XS_LDS_MAX);
-    (void)hipFuncSetAttribute((const void*)xscores_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)XS_LDS_MAX);
-    raised = true;
+                    int d_model, float* S, int B, hipStream_t st) {
+  dim3 grid((T + XL_RB - 1) / XL_RB, B);
+  const uint16_t* q16 = (const uint16_t*)qt;
+  const uint16_t* X16 = (const uint16_t*)X;
+  switch (head_tiles_in_flight(H)) {
+    case 1: hipLaunchKernelGGL(xscores_kernel<1>, grid, dim3(512), 0, st, q16, X16, x_bstride, seq_lens, T, B, H, d_model, S); break;
+    case 2: hipLaunchKernelGGL(xscores_kernel<2>, grid, dim3(512), 0, st, q16, X16, x_bstride, seq_lens, T, B, H, d_model, S); break;
+    case 4: hipLaunchKernelGGL(xscores_kernel<4>, grid, dim3(512), 0, st, q16, X16, x_bstride, seq_lens, T, B, H, d_model, S); break;
+    default: hipLaunchKernelGGL(xscores_kernel<8>, grid, dim3(512), 0, st, q16, X16, x_bstride, seq_lens, T, B, H, d_model, S); break;
   }
-  if (wide)
-    hipLaunchKernelGGL(xscores_kernel<2>, grid, dim3(512), lds, st, qt, (const uint16_t*)X, x_bstride, seq_lens, T, H,
-                       d_model, scale, S, nblk);
-  else
-    hipLaunchKernelGGL(xscores_kernel<1>, grid, dim3(512), lds, st, qt, (const uint16_t*)X, x_bstride, seq_lens, T, H,
-                       d_model, scale, S, nblk);
 }
 
 void launch_xweighted(const float* S, const void* X, long x_bstride, const int32_t* seq_lens, int T, int H,
                       int d_model, int nsplit, float* Cpart, float* mpart, float* lpart, int B, hipStream_t st) {
-  dim3 grid(nsplit, ((H + 31) / 32) * ((d_model + 1023) / 1024), B);
+  dim3 grid(nsplit, ((H + 31) / 32) * (d_model / 128), B);
   hipLaunchKernelGGL(xweighted_kernel, grid, dim3(512), 0, st, S, (const uint16_t*)X, x_bstride, seq_lens, T, H,
                      d_model, nsplit, Cpart, mpart, lpart);
 }

@@ -53,12 +53,12 @@ Plan make_plan(int B, int H, int T, int width, int e) {
     const int tiles_w = (width + TILE_ROWS - 1) / TILE_ROWS;
     p.csw_f = p.geom.grid / H < tiles_w ? p.geom.grid / H : tiles_w;
   }
-  p.off_S = o;      o += up(sizeof(float) * (size_t)B * H * T);
+  p.off_S = o;      o += up(sizeof(float) * (size_t)B * H * ((T + 31) / 32 * 32));   // (rows padded to 32 scores)
   p.off_Cpart = o;  o += up(sizeof(float) * nparts * H * width);
   p.off_m = o;      o += up(sizeof(float) * nparts * H);
   p.off_l = o;      o += up(sizeof(float) * nparts * H);
   p.off_Cn = o;     o += up(sizeof(float) * (size_t)B * H * width);
-  p.off_qt = o;     o += up(sizeof(float) * (size_t)B * H * width);
+  p.off_qt = o;     o += up(sizeof(float) * (size_t)B * ((H + 15) / 16 * 16) * width);   // (whole tiles of 16 heads)
   p.off_vacc = o;   o += up(sizeof(float) * (size_t)B * p.nsplit_v * e);
   p.off_vm = o;     o += up(sizeof(float) * (size_t)B * p.nsplit_v * H);
   p.off_vl = o;     o += up(sizeof(float) * (size_t)B * p.nsplit_v * H);
@@ -334,14 +334,15 @@ extern "C" int slim_decode_xcache(const void* q, const void* X, const void* W_K,
 
   StageTimer tm(o, st);
   const int req = o ? o->variant : SLIM_VARIANT_AUTO;
-  if (req != SLIM_VARIANT_GENERIC && xcache_fast_ok(dtype, H, d_model, d_k) && H < CTRL_INTS / 2) {
+  if (req != SLIM_VARIANT_GENERIC && xcache_fast_ok(dtype, H, d_model, d_k) && H < CTRL_INTS / 2 &&
+      (size_t)T * d_model * 2 < ((size_t)1 << 32)) {      // (the kernels address a sequence's rows with 32-bit offsets)
     // MFMA path: q~, scores (log2 domain), weighted sum per context split, merge + projection
     int* ctrl = (int*)(ws + p.off_ctrl);
     const int per = 16 * proj_batch_tiles(B, d_model, e, H);
     const int zb = (B + per - 1) / per;
-    launch_xq_tilde((const float*)q, W_K, qt, B, H, d_k, d_model, e, ctrl, H * zb, st);
+    launch_xq_tilde((const float*)q, W_K, qt, B, H, d_k, d_model, e, scale * 1.4426950408889634f, ctrl, H * zb, st);
     tm.mark();
-    launch_xscores(qt, X, xb, lens, T, H, d_model, scale * 1.4426950408889634f, S, B, st);
+    launch_xscores(qt, X, xb, lens, T, H, d_model, S, B, st);
     tm.mark();
     launch_xweighted(S, X, xb, lens, T, H, d_model, p.nsplit_x, Cpart, mpart, lpart, B, st);
     tm.mark();

@@ -132,9 +132,9 @@ void launch_dense_mfma(ProjArgs a, hipStream_t st);
 bool xcache_fast_ok(int dtype, int H, int d_model, int d_k);
 int xcache_splits(int B, int H, int T, int d_model);
 void launch_xq_tilde(const float* q, const void* Wk, float* qt, int B, int H, int d_k, int d_model, int e,
-                     int* counters, int ncounters, hipStream_t st);
+                     float scale, int* counters, int ncounters, hipStream_t st);
 void launch_xscores(const float* qt, const void* X, long x_bstride, const int32_t* seq_lens, int T, int H,
-                    int d_model, float scale, float* S, int B, hipStream_t st);
+                    int d_model, float* S, int B, hipStream_t st);
 void launch_xweighted(const float* S, const void* X, long x_bstride, const int32_t* seq_lens, int T, int H,
                       int d_model, int nsplit, float* Cpart, float* mpart, float* lpart, int B, hipStream_t st);
 
