@@ -753,8 +753,8 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
         }
 #pragma unroll
         for (int j = 0; j < 8; ++j) {                 // sum over the head's lanes, all inside a 16-lane row
-          sc[j] = dpp_add<0xB1>(sc[j]);               // lane ^ 1
-          sc[j] = dpp_add<0x4E>(sc[j]);               // lane ^ 2
+          if (a.lphp > 1) sc[j] = dpp_add<0xB1>(sc[j]);    // lane ^ 1   (a head spans lphp = 1, 2, 4, 8 or 16 lanes)
+          if (a.lphp > 2) sc[j] = dpp_add<0x4E>(sc[j]);    // lane ^ 2
           if (a.lphp > 4) sc[j] = dpp_add<0x141>(sc[j]);   // other quad of the 8-lane half
           if (a.lphp > 8) sc[j] = dpp_add<0x140>(sc[j]);   // other half of the row
         }
