@@ -57,3 +57,64 @@ def test_shape_sweep_matches_oracle(i):
         e, ek = row_rel_err(y, b.ref), row_rel_err(krow, b.k_new)
         say(f"  block: y {e:.3e}, key row {ek:.3e}")
         assert e <= TOL["bf16"] and ek <= TOL["bf16"]
+
+
+def _xshapes():
+    rng = np.random.default_rng(20250306)
+    out = [  # (B, H, d_model, d_k, T, ragged)
+        (1, 1, 128, 32, 1, False), (2, 3, 128, 64, 31, False), (1, 16, 256, 32, 129, True), (3, 17, 128, 32, 200, True),
+        (1, 20, 1280, 64, 150, False), (17, 4, 256, 96, 77, True), (1, 33, 384, 32, 260, False), (2, 130, 128, 32, 140, True),
+        (1, 8, 2560, 32, 40, False),
+    ]
+    for _ in range(9):
+        H = int(rng.choice([2, 5, 12, 24, 40, 64]))
+        d_k = int(rng.choice([32, 64, 128]))
+        dm = int(rng.choice([128, 256, 512, 640]))
+        out.append((int(rng.choice([1, 2, 5])), H, dm, d_k, int(rng.integers(1, 500)), bool(rng.integers(0, 2))))
+    return out
+
+
+XSHAPES = _xshapes()
+
+
+@pytest.mark.parametrize("i", range(len(XSHAPES)))
+def test_xcache_shape_sweep_matches_oracle(i):
+    from gpu_harness import XCase
+    B, H, dm, d_k, T, ragged = XSHAPES[i]
+    cfg = synth.scaled(synth.CONFIGS[4], B=B, H=H, d=dm, d_k=d_k, T=T)
+    lens = None
+    if ragged:
+        lens = np.random.default_rng(i).integers(1, T + 1, size=B).astype(np.int32)
+        lens[0] = T
+    q_scale = [1.0, 2.0, 4.0][i % 3]
+    say(f"[case] xcache sweep {i}: B={B} H={H} d_model={dm} d_k={d_k} T={T} lens={None if lens is None else lens.tolist()} q x{q_scale}")
+    x = XCase(cfg, q_scale=q_scale, lens=lens)
+    for variant in (binding.VARIANT_AUTO, binding.VARIANT_GENERIC):
+        e = x.err(x.run(variant=variant))
+        say(f"  variant {variant}: {e:.3e}")
+        assert e <= TOL["bf16"]
+
+
+PARTITIONS = [  # (B, H, d_k, T, len_lo): batches and lengths that move the host's choice of partition and launch count
+    (20, 16, 128, 203, 0), (64, 20, 64, 300, 0), (100, 8, 64, 50, 0), (200, 4, 32, 33, 1), (1024, 2, 32, 5, 1),
+    (1025, 2, 32, 3, 0), (16, 32, 96, 1000, 1), (2, 32, 128, 5000, 100), (9, 12, 64, 777, 300), (1, 24, 128, 2049, 0),
+    (17, 32, 128, 64, 0), (48, 32, 64, 96, 10), (130, 20, 64, 31, 0),
+]
+
+
+@pytest.mark.parametrize("i", range(len(PARTITIONS)))
+def test_partition_sweep_matches_oracle(i):
+    B, H, d_k, T, lo = PARTITIONS[i]
+    cfg = synth.scaled(BASE, B=B, H=H, d=H * d_k, d_k=d_k, T=T, len_lo=lo)
+    rope = 10000.0 if i % 3 == 0 else None
+    say(f"[case] partition sweep {i}: B={B} H={H} d_k={d_k} T={T} len_lo={lo} rope={rope} "
+        f"-> {binding.auto_variant_name(B, H, T, H * d_k, 'bf16')}")
+    k = KCase(cfg, q_scale=8.0, rope_base=rope, need_v=False)
+    outs = []
+    for variant in (binding.VARIANT_AUTO, binding.VARIANT_FUSED_SPLIT, binding.VARIANT_GENERIC):
+        o = k.run_slim(variant=variant)
+        e = k.err(o)
+        say(f"  variant {variant}: {e:.3e}")
+        assert e <= TOL["bf16"]
+        outs.append(o)
+    assert np.array_equal(outs[0], k.run_slim())                  # repeatable
