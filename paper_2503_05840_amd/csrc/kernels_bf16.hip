@@ -255,7 +255,8 @@ __device__ __forceinline__ void project_work(const ProjArgs& a, int hx, int cs, 
     if (lane < np) sm.wpid[bl][lane] = wgt / L;
     if (lane == 0) { sm.pid0s[bl] = p0; sm.nps[bl] = np; }
   }
-  __syncthreads();
+  // (a barrier for the weights in LDS only: __syncthreads() would also wait for the tiles of W in flight)
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 
   f32x4 acc[8][NBT];
 #pragma unroll
