@@ -215,6 +215,18 @@ __device__ __forceinline__ void project_work(const ProjArgs& a, int hx, int cs, 
       wt[j] = col_active ? *reinterpret_cast<const u32x4*>(Wh + (size_t)r * a.e) : u32x4{0u, 0u, 0u, 0u};
     }
   };
+  // DENSE: the B operand is a slice of x, known from the start: requested first, one tile ahead.
+  f32x4 xc[NBT][2], xn[NBT][2];
+  auto load_x = [&](f32x4 (&x)[NBT][2], int ct) {
+    const int c = min(c_lo + ct * TILE_ROWS + kg * 8, a.rows - 8);
+#pragma unroll
+    for (int t = 0; t < NBT; ++t) {
+      const float* src = a.Cpart + (size_t)min(bbase + t * 16 + n, a.B - 1) * a.rows + c;
+      x[t][0] = *reinterpret_cast<const f32x4*>(src);
+      x[t][1] = *reinterpret_cast<const f32x4*>(src + 4);
+    }
+  };
+  if constexpr (DENSE) load_x(xc, min(w, max(ntile - 1, 0)));
   u32x4 wt[8], wn[8];
   if (w < ntile) load_w(wt, w);                      // in flight while the merge weights are built
   if (w + NW < ntile) load_w(wn, w + NW);
@@ -270,13 +282,19 @@ __device__ __forceinline__ void project_work(const ProjArgs& a, int hx, int cs, 
     // B operand: merged C for (b = bt*16 + n, rows c0 + kg*8 .. +8)
     bf16x8 bhi[NBT], blo[NBT];
     const int c = c0 + kg * 8;
+    if constexpr (DENSE) load_x(xn, min(ct + NW, ntile - 1));
 #pragma unroll
     for (int t = 0; t < NBT; ++t) {
       float cn[8];
 #pragma unroll
       for (int j = 0; j < 8; ++j) cn[j] = 0.f;
       const int bl = t * 16 + n;
-      if (bl < nb && c < c_hi) {
+      if constexpr (DENSE) {
+        if (bl < nb && c < c_hi) {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) { cn[j] = xc[t][0][j]; cn[4 + j] = xc[t][1][j]; }
+        }
+      } else if (bl < nb && c < c_hi) {
         const int p0 = sm.pid0s[bl], np = sm.nps[bl];
         if constexpr (COH) {
           // eight partials per round trip: agent-scope loads, one wait
@@ -338,6 +356,10 @@ __device__ __forceinline__ void project_work(const ProjArgs& a, int hx, int cs, 
 #pragma unroll
       for (int j = 0; j < 8; ++j) wt[j] = wn[j];
       if (ct + 2 * NW < ntile) load_w(wn, ct + 2 * NW);
+    }
+    if constexpr (DENSE) {
+#pragma unroll
+      for (int t = 0; t < NBT; ++t) { xc[t][0] = xn[t][0]; xc[t][1] = xn[t][1]; }
     }
   }
 
