@@ -12,12 +12,13 @@
 // workgroups; but head h's weights need columns [h d_k, (h+1) d_k) only, which one column owner
 // holds, while every column owner needs every head's weights.  A "group" of G workgroups (one per
 // column unit of <=128 columns) therefore walks the same rows together; a scoring wave computes
-// the scores of the heads inside its unit from the 32-row tile it has just moved into LDS and
-// publishes them to a small ring in global memory as (score, tag) words; a summing wave gathers all
-// heads' scores of the tile, takes the tile out of LDS and feeds it to the MFMA.  No fences are
-// needed: every 8-byte half of a word carries the tile's tag, so a reader either sees the value of
-// this tile or gathers again.  Every wait is bounded; a time-out raises an error word instead of
-// hanging.
+// the scores of the heads inside its unit from the 32-row tile it has just loaded, turns them into
+// softmax numerators against the head's running reference, parks the tile in LDS and publishes
+// 16-byte words {tag, reference, 4 bf16 numerators} to a small ring in global memory; a summing wave
+// gathers all heads' words of the tile, takes the tile out of LDS and feeds it to the MFMA.  No fences
+// are needed: every 16-byte word (written by one store) carries the tile's tag, so a reader either
+// sees the values of this tile or gathers again.  Every wait is bounded; a time-out raises an error
+// word instead of hanging.
 //
 // Register tile.  A wave owns 32 rows x 128 columns: lane l loads 16 bytes (8 columns) of 8 rows,
 // column group l%16, row group l/16.  The MFMA (v_mfma_f32_16x16x32_bf16) contracts over rows,
@@ -56,8 +57,7 @@ __device__ __forceinline__ float dpp_add(float v) {
 }
 
 // max over the four lanes l, l^16, l^32, l^48 (the same column group in the four row groups).
-// Register swaps (v_permlane32_swap / v_permlane16_swap), no LDS traffic: a wave's LDS operations
-// queue behind its direct-to-LDS loads.
+// Register swaps (v_permlane32_swap / v_permlane16_swap), no LDS traffic.
 __device__ __forceinline__ float max_over_row_groups(float v) {
   const unsigned u = __float_as_uint(v);
   const auto a = __builtin_amdgcn_permlane32_swap(u, u, false, false);

@@ -1,9 +1,9 @@
-// bf16 fast path of the X-cache scheme for projection width e > d_model (non-square section,
-// Fig. 4): the cache holds the layer input X [T][d_model]; K and V are never formed.
+// bf16 fast path of the X-cache scheme (non-square section, Fig. 4; also the encoder-cache option of
+// the encoder-decoder section): the cache holds the layer input X [T][d_model]; K and V are never formed.
 //
-//   xq_tilde_kernel   : q~_h = q_h W_K,h^T           [B][H][d_model]   (W_K read once)
-//   xscores_kernel    : s[h][t] = q~_h . X[t]        [B][H][T], log2 domain, on MFMA
-//   xweighted_kernel  : per context split, m = max s, l = sum 2^(s-m), C_h = sum_t 2^(s-m) X[t]
+//   xq_tilde_kernel   : q~_h = q_h W_K,h^T, scaled, as bf16 hi + lo in MFMA operand order (W_K read once)
+//   xscores_kernel    : s[h][t] = q~_h . X[t]        [B][H][T padded to 32], log2 domain, on MFMA
+//   xweighted_kernel  : per context split, m = reference, l = sum 2^(s-m), C_h = sum_t 2^(s-m) X[t]
 //                       on MFMA, one contraction for 32 heads at a time
 // followed by the merge + projection of the K-cache path with W_V in place of W_KV.
 //
