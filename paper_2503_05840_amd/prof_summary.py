@@ -1,7 +1,7 @@
 """Text summary of a rocprofv3 result database (per-kernel calls / total / average), the
 form kept under profiles/.
 
-    python -m paper_2503_05840_amd.prof_summary gpurun_out/prof/NAME_results.db ["command line"]
+    python -m paper_2503_05840_amd.prof_summary OUTDIR/NAME_results.db ["command line"]
 """
 import sqlite3
 import sys

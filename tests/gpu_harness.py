@@ -19,7 +19,8 @@ _LOG = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))),
 
 
 def say(*a):
-    """Progress line, flushed before the GPU step it names; mirrored to gpurun_out/parity.log."""
+    """Progress line, flushed before the GPU step it names; mirrored to parity.log in the scratch
+    output folder when that folder exists."""
     print(*a, flush=True)
     if os.path.isdir(_LOG):
         with open(os.path.join(_LOG, "parity.log"), "a") as f:
