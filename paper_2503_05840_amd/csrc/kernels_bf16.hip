@@ -676,27 +676,12 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
     while (next_segment(sg)) {
       const int ntl = sg.ntl, len = sg.len;
       const uint16_t* Kb = sg.Kb;
-      // query for this lane's 8 columns, pre-scaled (log2 domain), split into bf16 hi + lo pairs
-      // so that the dot products run on v_dot2c_f32_bf16 without losing the fp32 query
+      // query for this lane's 8 columns: requested here, used only after the first tiles have been
+      // requested (the wait for it then overlaps theirs)
+      const u32x4* qsrc = reinterpret_cast<const u32x4*>(a.q + (size_t)sg.b * a.d + (col_active ? mycol : 0));
+      const u32x4 qraw0 = qsrc[0], qraw1 = qsrc[1];
       unsigned qh[4], ql[4];
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const float f0 = col_active ? a.q[(size_t)sg.b * a.d + mycol + 2 * c] * a.qscale : 0.f;
-        const float f1 = col_active ? a.q[(size_t)sg.b * a.d + mycol + 2 * c + 1] * a.qscale : 0.f;
-        const __bf16 h0 = (__bf16)f0, h1 = (__bf16)f1;
-        const bf16x2 hi = {h0, h1};
-        const bf16x2 lo = {(__bf16)(f0 - (float)h0), (__bf16)(f1 - (float)h1)};
-        qh[c] = __builtin_bit_cast(unsigned, hi);
-        ql[c] = __builtin_bit_cast(unsigned, lo);
-      }
-      unsigned ph[4], pl[4];                          // (-q2, q1) of every pair, same split
-      if constexpr (ROPE) {
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          ph[c] = ((qh[c] >> 16) ^ 0x8000u) | (qh[c] << 16);
-          pl[c] = ((ql[c] >> 16) ^ 0x8000u) | (ql[c] << 16);
-        }
-      }
+      unsigned ph[4], pl[4];                          // (-q2, q1) of every pair, same split (rotary keys)
       // (lanes without live columns re-read the unit's first columns: finite values that meet a zero
       //  query here and accumulator rows nobody reads in the summing wave)
       const unsigned lane_off = (unsigned)(rg * 8) * pitchB + (unsigned)(col_active ? mycol : ucol0) * 2u;
@@ -832,6 +817,26 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
 #pragma unroll
       for (int k = 0; k < PD; ++k)
         if (k < ntl) load_tile(ts[k], tr[k], k);
+      // the query, pre-scaled (log2 domain), split into bf16 hi + lo pairs so that the dot products run
+      // on v_dot2c_f32_bf16 without losing the fp32 query
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const unsigned r0 = c < 2 ? qraw0[2 * c] : qraw1[2 * c - 4], r1 = c < 2 ? qraw0[2 * c + 1] : qraw1[2 * c - 3];
+        const float f0 = col_active ? __uint_as_float(r0) * a.qscale : 0.f;
+        const float f1 = col_active ? __uint_as_float(r1) * a.qscale : 0.f;
+        const __bf16 h0 = (__bf16)f0, h1 = (__bf16)f1;
+        const bf16x2 hi = {h0, h1};
+        const bf16x2 lo = {(__bf16)(f0 - (float)h0), (__bf16)(f1 - (float)h1)};
+        qh[c] = __builtin_bit_cast(unsigned, hi);
+        ql[c] = __builtin_bit_cast(unsigned, lo);
+      }
+      if constexpr (ROPE) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          ph[c] = ((qh[c] >> 16) ^ 0x8000u) | (qh[c] << 16);
+          pl[c] = ((ql[c] >> 16) ^ 0x8000u) | (ql[c] << 16);
+        }
+      }
       for (int k = 0; k < ntl; k += PD) unrolled_steps<0, PD>(k, ntl, step);
       if (!by_seq) {
         // ---- end of this share (the barriers of the merge; the slots are its buffer) --------------
