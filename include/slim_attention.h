@@ -18,6 +18,9 @@
  *   - Device pointers must be 16-byte aligned; row pitches are dense.
  *   - Every function returns SLIM_OK (0) or a negative SLIM_ERR_* code; nothing throws or
  *     aborts.  Argument errors are detected on the host before anything is launched.
+ *   - Waits between workgroups inside the kernels are bounded; if one ever runs out (a device
+ *     that cannot keep a launch's 256 workgroups resident at once), the affected outputs are
+ *     written as NaN instead of the kernel hanging.
  *   - q is the already projected, un-scaled query (the library applies 1/sqrt(d_k)); out is
  *     concat(head_1..head_H) before W_O (eq. 5).  Attention runs over exactly the cached
  *     rows handed in (the caller appends the new token's key first if it wants it attended).
@@ -94,7 +97,10 @@ typedef struct slim_opts {
                                     work across the chip for ragged batches and is validated      */
   int64_t        t_stride;       /* cache rows between consecutive sequences, 0 => T              */
   void*          workspace;      /* device scratch, nullable => library-owned, grown on demand
-                                    with hipMalloc and kept per device until process exit         */
+                                    with hipMalloc and kept per device until process exit.  Calls
+                                    that may overlap on one device (different streams or threads)
+                                    need a workspace each: the library-owned one is shared, and
+                                    growing it frees the old block after waiting for the device   */
   size_t         workspace_bytes;
   void*          stream;         /* hipStream_t, null => the null stream                          */
   int            variant;        /* 0 = library's choice; other values select an implementation
