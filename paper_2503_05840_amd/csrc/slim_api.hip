@@ -173,7 +173,9 @@ int pick_variant(int requested, int B, int H, int T, int d, int dtype) {
 // Tags of the score exchange are unique per launch within the process and start at a random
 // point, so words left in a workspace by earlier launches (or an earlier process) never match.
 std::atomic<unsigned> g_tag{(unsigned)std::chrono::steady_clock::now().time_since_epoch().count() * 2654435761u};
-std::atomic<unsigned> g_launch{1};
+// Launch ids (arrival flags, error word) start at a random point as well: a fresh workspace may hold
+// anything, small integers included.
+std::atomic<unsigned> g_launch{((unsigned)std::chrono::steady_clock::now().time_since_epoch().count() * 2246822519u) | 1u};
 
 extern "C" int slim_variant_for(int B, int H, int T, int d, int dtype) {
   if (B < 1 || H < 1 || T < 1 || d < 1 || d % H != 0) return 0;
