@@ -230,3 +230,34 @@ def test_nonsquare_option1_right_inverse_decode_matches_oracle(name, cfg, q_scal
     ev = k.err(k.run_vanilla())
     say(f"  vanilla e-wide K+V: {ev:.3e}")
     assert ev <= TOL[cfg.dtype]
+
+
+@pytest.mark.parametrize("fill", [0, 1, 2, 0x7FC00000, -1])
+def test_workspace_needs_no_initialisation(cases, fill):
+    """The caller's scratch may hold anything -- small integers (which could pass for counters, flags or
+    launch ids), NaN patterns, all ones: results are bitwise those of a zeroed scratch."""
+    import torch
+    from gpu_harness import BlockCase, XCase
+    say(f"[case] workspace pre-filled with int32 {fill}")
+
+    def scratch(nbytes, value):
+        return torch.full(((nbytes + 3) // 4,), value, dtype=torch.int32, device="cuda").view(torch.uint8)
+
+    for name in ("cfg1-like", "cfg2-like-ragged", "batch-by-sequence"):
+        k = cases(name)
+        c = k.cfg
+        need = binding.slim_workspace_bytes(c.B, c.H, c.T, c.d, c.dtype)
+        for variant in VARIANTS.values():
+            ref = k.run_slim(variant=variant, workspace=scratch(need, 0))
+            got = k.run_slim(variant=variant, workspace=scratch(need, fill))
+            assert np.array_equal(ref, got), (name, variant)
+        assert np.array_equal(k.run_vanilla(workspace=scratch(need, 0)), k.run_vanilla(workspace=scratch(need, fill)))
+    cfg = synth.scaled(C[4], B=2, H=32, d=256, d_k=64, T=300)
+    x = XCase(cfg, oracle_seqs=set())
+    need = binding.slim_workspace_bytes_xcache(cfg.B, cfg.H, cfg.T, cfg.d, cfg.d_k, cfg.dtype)
+    assert np.array_equal(x.run(workspace=scratch(need, 0)), x.run(workspace=scratch(need, fill)))
+    cfg = synth.scaled(C[1], B=3, H=8, d=1024, T=200, len_lo=20)
+    b = BlockCase(cfg)
+    need = binding.slim_workspace_bytes_block(cfg.B, cfg.H, cfg.T, cfg.d, cfg.dtype)
+    assert np.array_equal(b.run_slim(workspace=scratch(need, 0))[0], b.run_slim(workspace=scratch(need, fill))[0])
+    assert np.array_equal(b.run_vanilla(workspace=scratch(need, 0))[0], b.run_vanilla(workspace=scratch(need, fill))[0])
