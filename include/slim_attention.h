@@ -100,7 +100,9 @@ typedef struct slim_opts {
                                     with hipMalloc and kept per device until process exit.  Calls
                                     that may overlap on one device (different streams or threads)
                                     need a workspace each: the library-owned one is shared, and
-                                    growing it frees the old block after waiting for the device   */
+                                    growing it frees the old block after waiting for the device.
+                                    (The bf16 fast path uses the whole chip per launch; the library
+                                    orders such launches of different streams one after the other) */
   size_t         workspace_bytes;
   void*          stream;         /* hipStream_t, null => the null stream                          */
   int            variant;        /* 0 = library's choice; other values select an implementation

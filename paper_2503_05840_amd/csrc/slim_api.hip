@@ -96,6 +96,28 @@ int get_workspace(const slim_opts* o, size_t need, char** ws) {
 
 bool misaligned(const void* p) { return (((uintptr_t)p) & 15) != 0; }
 
+// The stream kernel's workgroups wait for each other, so all of a launch's workgroups must be resident
+// together: two such launches running side by side (different streams) could each hold half of the chip
+// and starve each other until their waits run out.  Launches that arrive on another stream than the
+// previous one are therefore ordered behind it with an event; on one stream this costs nothing.
+struct StreamOrder { hipStream_t last = nullptr; bool any = false; hipEvent_t ev = nullptr; };
+StreamOrder g_order[64];
+std::mutex g_order_mu;
+
+void order_after_previous_stream_kernel(hipStream_t st) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return;
+  std::lock_guard<std::mutex> lk(g_order_mu);
+  StreamOrder& o = g_order[dev];
+  if (o.any && o.last != st) {
+    if (!o.ev && hipEventCreateWithFlags(&o.ev, hipEventDisableTiming) != hipSuccess) { o.ev = nullptr; (void)hipGetLastError(); }
+    if (o.ev && hipEventRecord(o.ev, o.last) == hipSuccess) (void)hipStreamWaitEvent(st, o.ev, 0);
+    else (void)hipGetLastError();
+  }
+  o.last = st;
+  o.any = true;
+}
+
 int check_common(int B, int H, int T, int e, int d_k, int width, const slim_opts* o, int* dtype,
                  long* t_stride) {
   if (B < 1 || H < 1 || T < 1 || e < 1 || width < 1) return SLIM_ERR_SHAPE;
@@ -264,6 +286,7 @@ extern "C" int slim_decode(const void* q, const void* Kcache, const void* W_KV, 
       pa.crows = proj_rows_per_split(d, p.csw_f);
       fa.fuse = 1; fa.flags = (unsigned*)(ctrl + CTRL_INTS / 2); fa.proj = pa;
     }
+    order_after_previous_stream_kernel(st);
     launch_fused_stream(g, fa, st);
     tm.mark();
     if (!one_launch) {

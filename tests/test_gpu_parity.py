@@ -261,3 +261,30 @@ def test_workspace_needs_no_initialisation(cases, fill):
     need = binding.slim_workspace_bytes_block(cfg.B, cfg.H, cfg.T, cfg.d, cfg.dtype)
     assert np.array_equal(b.run_slim(workspace=scratch(need, 0))[0], b.run_slim(workspace=scratch(need, fill))[0])
     assert np.array_equal(b.run_vanilla(workspace=scratch(need, 0))[0], b.run_vanilla(workspace=scratch(need, fill))[0])
+
+
+def test_calls_on_two_streams_with_their_own_scratch(cases):
+    """Launches of the fast path need the whole chip; issued from two streams they are ordered by the
+    library and both give the single-stream result."""
+    import torch
+    say("[case] two streams, interleaved calls")
+    k1, k2 = cases("cfg1-like"), cases("cfg2-like-ragged")
+    ref1, ref2 = k1.run_slim(), k2.run_slim()
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    ws = [torch.empty(binding.slim_workspace_bytes(k.cfg.B, k.cfg.H, k.cfg.T, k.cfg.d, k.cfg.dtype), dtype=torch.uint8,
+                      device="cuda") for k in (k1, k2)]
+    outs1 = [torch.full((k1.cfg.B, k1.cfg.d), float("nan"), device="cuda") for _ in range(6)]
+    outs2 = [torch.full((k2.cfg.B, k2.cfg.d), float("nan"), device="cuda") for _ in range(6)]
+    torch.cuda.synchronize()
+    for i in range(6):
+        with torch.cuda.stream(s1):
+            binding.slim_decode(k1.q, k1.K, k1.Wkv, outs1[i], k1.cfg.B, k1.cfg.H, k1.cfg.T, k1.cfg.d,
+                                **k1._kw(workspace=ws[0]))
+        with torch.cuda.stream(s2):
+            binding.slim_decode(k2.q, k2.K, k2.Wkv, outs2[i], k2.cfg.B, k2.cfg.H, k2.cfg.T, k2.cfg.d,
+                                **k2._kw(workspace=ws[1]))
+    torch.cuda.synchronize()
+    for o in outs1:
+        assert np.array_equal(o.cpu().numpy(), ref1)
+    for o in outs2:
+        assert np.array_equal(o.cpu().numpy(), ref2)
