@@ -182,9 +182,27 @@ extern "C" const char* slim_strerror(int code) {
   }
 }
 
+// The stream kernel's workgroups wait for each other: all 256 must be resident at once, one per compute
+// unit.  A device (or partition) with fewer compute units takes the plain kernels.  Unknown (no device
+// visible, e.g. when only sizes are asked for on a build machine) counts as enough.
+bool chip_holds_stream_kernel() {
+  static std::atomic<int> cached[64];                  // 0 unknown, 1 yes, 2 no
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) { (void)hipGetLastError(); return true; }
+  int c = cached[dev].load();
+  if (c == 0) {
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) { (void)hipGetLastError(); return true; }
+    c = cus >= 256 ? 1 : 2;
+    cached[dev].store(c);
+  }
+  return c == 1;
+}
+
 // Which implementation runs for a K-cache decode of this shape.
 int pick_variant(int requested, int B, int H, int T, int d, int dtype) {
   if (requested == SLIM_VARIANT_GENERIC) return SLIM_VARIANT_GENERIC;
+  if (!chip_holds_stream_kernel()) return SLIM_VARIANT_GENERIC;
   FusedGeom g;
   const int zb = (B + 15) / 16;                      // upper bound of the projection's batch chunks
   if (dtype == SLIM_BF16 && fused_geometry(B, H, T, d, &g) && H * zb < CTRL_INTS / 2 && g.grid <= CTRL_INTS / 2 - 1)
