@@ -319,6 +319,25 @@ extern "C" int slim_decode(const void* q, const void* Kcache, const void* W_KV, 
   tm.mark();
   launch_weighted_sum(dtype, S, Kcache, kb, d, lens, T, H, p.nsplit, Cpart, mpart, lpart, B, st);
   tm.mark();
+  // Shapes the stream kernel does not take (more than 32 heads, very large batches) still get the MFMA
+  // merge + projection when the head width allows it; an explicit request for the plain kernels keeps
+  // every step on the vector ALU.
+  const int requested = o ? o->variant : SLIM_VARIANT_AUTO;
+  if (dtype == SLIM_BF16 && requested != SLIM_VARIANT_GENERIC && d_k % 8 == 0 && d_k <= 128 &&
+      (long)H * ((B + 15) / 16) < CTRL_INTS / 2) {
+    int* ctrl = (int*)(ws + p.off_ctrl);
+    launch_zero_ints(ctrl, CTRL_INTS / 2, st);
+    ProjArgs pa{};
+    pa.Cpart = Cpart; pa.mpart = mpart; pa.lpart = lpart; pa.W = (const uint16_t*)W_KV;
+    pa.out = (float*)out; pa.outpart = (float*)(ws + p.off_outpart); pa.counters = ctrl;
+    pa.seq_lens = lens; pa.B = B; pa.T = T; pa.H = H; pa.d_k = d_k; pa.rows = d; pa.e = d;
+    pa.nsplit = p.nsplit; pa.mode = 1; pa.mscale = 1.4426950408889634f;      // natural-log maxima
+    pa.csw = p.csw;
+    launch_project_mfma(pa, st);
+    tm.mark();
+    tm.finish();
+    return launch_status();
+  }
   launch_combine(Cpart, mpart, lpart, p.nsplit, H, d, Cn, B, st);
   tm.mark();
   launch_project(dtype, Cn, W_KV, d, d, H, d_k, (float*)out, B, st);

@@ -99,6 +99,8 @@ PARTITIONS = [  # (B, H, d_k, T, len_lo): batches and lengths that move the host
     (20, 16, 128, 203, 0), (64, 20, 64, 300, 0), (100, 8, 64, 50, 0), (200, 4, 32, 33, 1), (1024, 2, 32, 5, 1),
     (1025, 2, 32, 3, 0), (16, 32, 96, 1000, 1), (2, 32, 128, 5000, 100), (9, 12, 64, 777, 300), (1, 24, 128, 2049, 0),
     (17, 32, 128, 64, 0), (48, 32, 64, 96, 10), (130, 20, 64, 31, 0),
+    # more than 32 heads / more than 1024 sequences: plain score and sum kernels, MFMA merge + projection
+    (2, 40, 64, 300, 50), (1, 64, 128, 257, 0), (3, 96, 32, 90, 1), (1100, 2, 32, 4, 1), (20, 48, 96, 70, 0),
 ]
 
 
