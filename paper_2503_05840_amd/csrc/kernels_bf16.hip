@@ -496,7 +496,9 @@ __global__ __launch_bounds__(512) void project_mfma_kernel(const ProjArgs a) {
 // following seven rows advance by the one-position rotation (table row 1), kept in registers.
 constexpr float SOFTMAX_SLACK = 6.0f;
 
-template <int NT, bool ROPE>
+// LPHP: lanes reserved per head as a compile-time constant (16 or 8: heads of 128 or 64 columns), or 0
+// for the run-time value.
+template <int NT, bool ROPE, int LPHP>
 __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const FusedArgs a) {
   constexpr int NP = FUSED_PAIRS, NS = FUSED_SLOTS, PD = FUSED_AHEAD;
   constexpr int NTHR = NP * 128;
@@ -557,7 +559,8 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
   if (!has_work && !fuse) return;
 
   // ---- lane -> column mapping inside the unit --------------------------------------------------
-  const int hh = idx / a.lphp, li = idx % a.lphp;
+  const int lphp = LPHP ? LPHP : a.lphp;
+  const int hh = idx / lphp, li = idx % lphp;
   const int myhead = u * a.hpu + hh;
   const bool col_active = (li < a.lph) && (hh < a.hpu) && (myhead < a.H);
   const int mycol = myhead * a.d_k + li * 8;        // first of this lane's 8 columns
@@ -568,7 +571,7 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
     const int mi = rg * 4 + r;                      // column group (the A operand's M index)
-    const int h2 = mi / a.lphp, l2 = mi % a.lphp;
+    const int h2 = mi / lphp, l2 = mi % lphp;
     ocol[r] = (l2 < a.lph && h2 < a.hpu) ? h2 * a.d_k + l2 * 8 : -1;
   }
 
@@ -684,13 +687,18 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
       unsigned ph[4], pl[4];                          // (-q2, q1) of every pair, same split (rotary keys)
       // (lanes without live columns re-read the unit's first columns: finite values that meet a zero
       //  query here and accumulator rows nobody reads in the summing wave)
-      const unsigned lane_off = (unsigned)(rg * 8) * pitchB + (unsigned)(col_active ? mycol : ucol0) * 2u;
+      const unsigned lane_col_off = (unsigned)(col_active ? mycol : ucol0) * 2u;
+      const unsigned lane_off = (unsigned)(rg * 8) * pitchB + lane_col_off;
       float mrun = NEG_INF;                           // running maximum of this lane's head (log2 domain)
       // Tiles travel HBM -> registers (PD register sets: PD-1 tiles in flight while one is being
       // scored) -> LDS slot, where the summing wave picks them up.  Direct-to-LDS loads are slower
       // to issue here, and a wave's LDS operations queue behind those it has in flight.
       u32x4 ts[PD][8];
       f32x4 tr[PD][2];                                // ROPE: {cos, sin} x 4 pairs at the lane's first row of the tile
+      // Every call issues the same number of loads on every path (also for k past the end of the segment,
+      // where all rows collapse onto the last one and nobody uses the result): the compiler's s_waitcnt
+      // for the next tile's registers is then exact.  A load skipped on some path would make it wait for
+      // the youngest loads in flight instead, i.e. for the tile requested a moment ago.
       auto load_tile = [&](u32x4 (&t)[8], f32x4 (&r)[2], int k) {
         const int st = __builtin_amdgcn_readfirstlane(sg.t0 + k * sg.stride);
         if constexpr (ROPE) {
@@ -699,19 +707,20 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
           r[0] = rp[0];
           r[1] = rp[1];
         }
-        if ((st + 1) * TILE_ROWS <= len) {
+        if (k < ntl && (st + 1) * TILE_ROWS <= len) {
           // full tile: uniform row base + per-lane 32-bit offset
           const char* tb = reinterpret_cast<const char*>(Kb) + (size_t)st * TILE_ROWS * pitchB;
 #pragma unroll
           for (int j = 0; j < 8; ++j)
             t[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tb + (size_t)j * pitchB + lane_off));
         } else {
+          // last, partial tile (rows past the end re-read the last row; masked in the scores) or no tile
           const int r0 = st * TILE_ROWS + rg * 8;
+          const char* cb = reinterpret_cast<const char*>(Kb) + lane_col_off;
 #pragma unroll
           for (int j = 0; j < 8; ++j) {
-            const int r = min(r0 + j, len - 1);       // rows past the end re-read the last row; masked below
-            t[j] = col_active ? __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(Kb + (size_t)r * a.d + mycol))
-                              : u32x4{0u, 0u, 0u, 0u};
+            const int rr = max(min(r0 + j, len - 1), 0);
+            t[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(cb + (size_t)rr * pitchB));
           }
         }
       };
@@ -761,10 +770,10 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
         }
 #pragma unroll
         for (int j = 0; j < 8; ++j) {                 // sum over the head's lanes, all inside a 16-lane row
-          if (a.lphp > 1) sc[j] = dpp_add<0xB1>(sc[j]);    // lane ^ 1   (a head spans lphp = 1, 2, 4, 8 or 16 lanes)
-          if (a.lphp > 2) sc[j] = dpp_add<0x4E>(sc[j]);    // lane ^ 2
-          if (a.lphp > 4) sc[j] = dpp_add<0x141>(sc[j]);   // other quad of the 8-lane half
-          if (a.lphp > 8) sc[j] = dpp_add<0x140>(sc[j]);   // other half of the row
+          if (lphp > 1) sc[j] = dpp_add<0xB1>(sc[j]);      // lane ^ 1   (a head spans lphp = 1, 2, 4, 8 or 16 lanes)
+          if (lphp > 2) sc[j] = dpp_add<0x4E>(sc[j]);      // lane ^ 2
+          if (lphp > 4) sc[j] = dpp_add<0x141>(sc[j]);     // other quad of the 8-lane half
+          if (lphp > 8) sc[j] = dpp_add<0x140>(sc[j]);     // other half of the row
         }
         // ---- this tile's softmax numerators of the unit's heads, against the running maximum -----
         const int st = sg.t0 + k * sg.stride;
@@ -812,11 +821,10 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
         }
         // a hint for the summing wave (the words themselves carry the proof)
         if (lane == 0) __hip_atomic_store(&published[p], gk + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        if (k + PD < ntl) load_tile(cur, rot, k + PD);
+        load_tile(cur, rot, k + PD);
       };
 #pragma unroll
-      for (int k = 0; k < PD; ++k)
-        if (k < ntl) load_tile(ts[k], tr[k], k);
+      for (int k = 0; k < PD; ++k) load_tile(ts[k], tr[k], k);
       // the query, pre-scaled (log2 domain), split into bf16 hi + lo pairs so that the dot products run
       // on v_dot2c_f32_bf16 without losing the fp32 query
 #pragma unroll
@@ -837,7 +845,11 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
           pl[c] = ((ql[c] >> 16) ^ 0x8000u) | (ql[c] << 16);
         }
       }
-      for (int k = 0; k < ntl; k += PD) unrolled_steps<0, PD>(k, ntl, step);
+      // Whole rounds of PD tiles without a condition between the steps (a step that may be skipped
+      // inside the loop would again make the waits for the tile registers conservative), then the rest.
+      int k = 0;
+      for (; k + PD <= ntl; k += PD) unrolled_steps<0, PD>(k, k + PD, step);
+      unrolled_steps<0, PD - 1>(k, ntl, step);
       if (!by_seq) {
         // ---- end of this share (the barriers of the merge; the slots are its buffer) --------------
         __syncthreads();
@@ -1152,13 +1164,20 @@ size_t fused_exch_bytes(const FusedGeom& g) {
 
 void launch_fused_stream(const FusedGeom& g, const FusedArgs& a, hipStream_t st) {
   dim3 grid(g.grid), block(g.NP * 128);
-  if (a.rope) {
-    if (g.NT == 1) hipLaunchKernelGGL((fused_stream_kernel<1, true>), grid, block, 0, st, a);
-    else hipLaunchKernelGGL((fused_stream_kernel<2, true>), grid, block, 0, st, a);
-  } else {
-    if (g.NT == 1) hipLaunchKernelGGL((fused_stream_kernel<1, false>), grid, block, 0, st, a);
-    else hipLaunchKernelGGL((fused_stream_kernel<2, false>), grid, block, 0, st, a);
-  }
+  auto go = [&](auto nt, auto rope, auto lphp) {
+    hipLaunchKernelGGL((fused_stream_kernel<decltype(nt)::value, decltype(rope)::value, decltype(lphp)::value>), grid, block, 0, st, a);
+  };
+  auto with_lphp = [&](auto nt, auto rope) {
+    if (g.lphp == 16) go(nt, rope, std::integral_constant<int, 16>{});
+    else if (g.lphp == 8) go(nt, rope, std::integral_constant<int, 8>{});
+    else go(nt, rope, std::integral_constant<int, 0>{});
+  };
+  auto with_rope = [&](auto nt) {
+    if (a.rope) with_lphp(nt, std::true_type{});
+    else with_lphp(nt, std::false_type{});
+  };
+  if (g.NT == 1) with_rope(std::integral_constant<int, 1>{});
+  else with_rope(std::integral_constant<int, 2>{});
 }
 
 // Sequences per workgroup of the projection, in MFMA N tiles of 16 (1, 2 or 4).  One tile keeps the
