@@ -473,24 +473,24 @@ __global__ __launch_bounds__(512) void project_mfma_kernel(const ProjArgs a) {
 // ------------------------------------------------------------------------------------------------
 // fused stream kernel
 //
-// A workgroup is FUSED_PAIRS pairs of waves.  The first wave of a pair (the "scoring" wave) streams
-// its K tiles from HBM into registers (FUSED_AHEAD register sets, so the next tile is in flight
-// while one is being scored), computes the scores of its unit's heads, turns them into softmax
-// numerators against the head's running maximum (bf16, the precision the MFMA consumes anyway),
-// parks the tile in an LDS slot and publishes {tag, running max, 4 numerators} words; it never
-// waits for another workgroup, so the stream from HBM runs at its own pace.  The second wave (the
-// "summing" wave) gathers all heads' words of a tile (up to FUSED_GATHERS tiles ahead), takes the
-// tile out of the LDS slot, rescales its accumulators when a maximum moved and does the MFMA
-// contraction; it may run FUSED_SLOTS-1 tiles behind its partner, which hides the latency of the
-// exchange.  The two roles sit in different waves because vector-memory operations of one wave
-// complete in issue order: a wave that mixed the long-latency tile loads with the gathers could
-// not wait for a gather without also waiting for every tile load issued before it.  A slot goes
-// back to the scoring wave through a counter in LDS.
+// A workgroup is FUSED_WAVES waves that all do the same work on tiles of their own.  In step k a wave
+//   1. requests all heads' words of its tile k-1 (published by the same wave of every workgroup of the
+//      group one step earlier),
+//   2. scores tile k (in registers since two steps ago): scores of its unit's heads, softmax numerators
+//      against the head's running maximum (bf16, the precision the MFMA consumes anyway), parks the
+//      tile in one of its two LDS slots, publishes {tag, running max, 4 numerators} words, and requests
+//      tile k+2 into the registers that have just become free,
+//   3. takes tile k-1 out of its LDS slot, rescales its accumulators when a maximum moved and does the
+//      MFMA contraction with the words gathered in 1.
+// Scoring is the long part of a step and every wave does it, so all eight waves of a compute unit share
+// it; the gather travels while the wave scores, and because it is requested before the next tile (a
+// wave's vector-memory operations complete in issue order) it only ever waits for tiles that were
+// requested a whole step earlier.  A wave never waits for another wave of its workgroup.
 // ------------------------------------------------------------------------------------------------
 //
 // ROPE (RoPE appendix, option 1): the cache holds raw keys and row t sits at position t.  The
-// scoring wave rotates each key pair by its position for the score only; the tile that goes to
-// the summing wave stays raw.  With (y1, y2) = (x1 c + x2 s, -x1 s + x2 c) the pair's share of the
+// scoring rotates each key pair by its position for the score only; the tile that goes to the
+// weighted sum stays raw.  With (y1, y2) = (x1 c + x2 s, -x1 s + x2 c) the pair's share of the
 // score is c (q1 x1 + q2 x2) + s (q1 x2 - q2 x1): two dot products of the raw pair, with (q1, q2)
 // and with (-q2, q1).  cos / sin of a lane's first row come from the table with the tile; the
 // following seven rows advance by the one-position rotation (table row 1), kept in registers.
@@ -499,28 +499,28 @@ constexpr float SOFTMAX_SLACK = 6.0f;
 // LPHP: lanes reserved per head as a compile-time constant (16 or 8: heads of 128 or 64 columns), or 0
 // for the run-time value.
 template <int NT, bool ROPE, int LPHP>
-__global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const FusedArgs a) {
-  constexpr int NP = FUSED_PAIRS, NS = FUSED_SLOTS, PD = FUSED_AHEAD;
-  constexpr int NTHR = NP * 128;
+__global__ __launch_bounds__(FUSED_WAVES * 64) void fused_stream_kernel(const FusedArgs a) {
+  constexpr int NP = FUSED_WAVES, NS = FUSED_SLOTS, PD = FUSED_AHEAD;
+  constexpr int NTHR = NP * 64;
   constexpr int HP = NT * 16;                       // heads padded to the MFMA N tile
+  static_assert(NP == 8 && NS == 2 && PD == 2, "the step structure and the thread mappings below assume these");
   __shared__ int prefix[FUSED_MAX_B + 1];
   __shared__ float marr[NP][NT][16];
   __shared__ float larr[NP][NT][16];
-  __shared__ int consumed[NP];                      // tiles (of all segments so far) the summing wave has taken
-  __shared__ int published[NP];                     // tiles (of all segments so far) the scoring wave has published
-  __shared__ u32x4 tiles[NP][NS][512];              // per pair: 8 KB landing slots for K tiles
-  // By-context partition: the end-of-share merge of the four summing waves goes through the (then
-  // idle) slots.  By-sequence partition: the scoring waves keep streaming, so a summing wave
-  // transposes its result through a part of its own, TRANSPOSE_HEADS heads per pass.  The
-  // projection of the single-launch mode runs after everything else and reuses both.
-  constexpr int TRANSPOSE_HEADS = 8;
+  // Per wave: NS landing slots of 8 KB for K tiles.  By-context partition: the end-of-share merge of
+  // the waves goes through the (then idle) slots, which is why the array is a little larger than
+  // the slots.  By-sequence partition: the other waves keep streaming, so a wave transposes its
+  // result through a part of its own in sbuf, TRANSPOSE_HEADS heads per pass.  The projection of the
+  // single-launch mode runs after everything else and reuses both.
+  constexpr int TRANSPOSE_HEADS = 4;
+  constexpr size_t SLOT_BYTES = sizeof(u32x4) * NP * NS * 512, MERGE_BYTES = sizeof(float) * NP * HP * 129;
+  __shared__ __align__(16) unsigned char lds_main[SLOT_BYTES > MERGE_BYTES ? SLOT_BYTES : MERGE_BYTES];
   __shared__ __align__(16) float sbuf[(sizeof(ProjShared<1>) > sizeof(float) * NP * TRANSPOSE_HEADS * 129
                                            ? sizeof(ProjShared<1>) : sizeof(float) * NP * TRANSPOSE_HEADS * 129) / sizeof(float)];
-  float* const mbuf = reinterpret_cast<float*>(&tiles[0][0][0]);   // [NP][HP][129] floats
-  static_assert(sizeof(float) * NP * HP * 129 <= sizeof(u32x4) * NP * NS * 512, "merge buffer must fit the slots");
-  float* const red = reinterpret_cast<float*>(&tiles[0][0][0]);    // 64 KB for the projection's cross-wave sum
-  static_assert(sizeof(float) * 8 * 8 * 4 * 64 <= sizeof(u32x4) * NP * NS * 512, "cross-wave sum must fit the slots");
-  static_assert(NP == 4 && NS >= 3 && NS <= 5, "the thread mappings below assume 4 pairs");
+  u32x4* const tiles = reinterpret_cast<u32x4*>(lds_main);          // [NP][NS][512]
+  float* const mbuf = reinterpret_cast<float*>(lds_main);           // [NP][HP][129] floats
+  float* const red = reinterpret_cast<float*>(lds_main);            // 64 KB for the projection's cross-wave sum
+  static_assert(sizeof(float) * 8 * 8 * 4 * 64 <= sizeof(lds_main), "cross-wave sum must fit");
 
   // ---- which group / column unit is this workgroup -------------------------------------------
   int g = 0, u = 0;
@@ -543,14 +543,12 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
   const int idx = lane & 15, rg = lane >> 4;        // column group / row group of the register tile
   const int n = idx, kg = rg;                       // head-in-tile / row group of the B operand
   const int wu = __builtin_amdgcn_readfirstlane(w);
-  const bool scoring = wu < NP;                     // wave role
-  const int p = wu & (NP - 1);                      // pair
+  const int p = wu;                                 // this wave's team: wave p of every workgroup of the group
 
   const bool fuse = a.fuse != 0;
   if (blockIdx.x == 0 && a.counters)                // the projection's arrival counters start at 0
     for (int i = tid; i < a.ncounters; i += NTHR) st_result(a.counters + i, 0, fuse);
 
-  if (tid < NP) { consumed[tid] = 0; published[tid] = 0; }
   build_tile_prefix(prefix, a.seq_lens, a.B, a.T);     // (ends with a workgroup barrier)
   const int VT = prefix[a.B];
   const int Qt = (VT + a.NG - 1) / a.NG;            // tiles per group
@@ -579,24 +577,25 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
   const bool heads_full = (a.H == HP);               // no padded heads in the MFMA N tiles
   const unsigned pitchB = (unsigned)a.d * 2u;        // bytes per cache row
   u32x4* const team_ring = reinterpret_cast<u32x4*>(a.exch) + (size_t)(g * NP + p) * EXCH_SLOTS * (HP * 8);
+  u32x4* const myslots = tiles + (size_t)p * NS * 512;
   bool dead = false;                                // a wait timed out: stop waiting, just drain
   auto give_up = [&]() {
     if (!dead && lane == 0) atomicExch(a.err, (int)a.launch_id);
     dead = true;
   };
 
-  // The work of this wave pair, the same walk for both roles, as a list of segments (a sequence or
-  // a share of one); tile k of a segment is row tile t0 + k * stride of sequence b.  Two partitions:
+  // The work of this wave as a list of segments (a sequence or a share of one); tile k of a segment is
+  // row tile t0 + k * stride of sequence b.  Two partitions:
   //  * by context (default): the group's range of tiles [v0, v1) is cut at sequence boundaries and
-  //    the four pairs take the tiles of a share round-robin; the pairs' results are merged at the
+  //    the waves take the tiles of a share round-robin; the waves' results are merged at the
   //    end of each share and the groups' partials by the projection.  Balanced for any lengths.
-  //  * by sequence: every sequence is cut into a.by_sequence equal shares and pair slot g * NP + p
+  //  * by sequence: every sequence is cut into a.by_sequence equal shares and wave slot g * NP + p
   //    takes shares round-robin; no merge inside the workgroup, one partial per share.  For batches
   //    whose shares fill the slots evenly (many short sequences).
   struct Seg { int b, t0, stride, ntl, len, pid; unsigned it0; const uint16_t* Kb; };   // it0: tiles of earlier segments
   const bool by_seq = a.by_sequence != 0;
   int seg_b = by_seq ? g * NP + p : 0;
-  unsigned seg_it = 0;                              // tiles this pair has been through so far
+  unsigned seg_it = 0;                              // tiles this wave has been through so far
   if (has_work && !by_seq)
     while (prefix[seg_b + 1] <= v0) ++seg_b;
   auto next_segment = [&](Seg& sg) -> bool {
@@ -620,7 +619,7 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
       const int s1 = min(v1, prefix[b + 1]) - prefix[b];
       if (s0 >= s1) continue;
       sg.b = b; sg.pid = b + g;
-      sg.t0 = s0 + p; sg.stride = NP;                 // this pair's tiles are s0+p, s0+p+NP, ...
+      sg.t0 = s0 + p; sg.stride = NP;                 // this wave's tiles are s0+p, s0+p+NP, ...
       sg.len = seq_len_of(a.seq_lens, b, a.T);
       sg.Kb = a.K + (size_t)b * a.k_bstride;
       sg.ntl = max(0, (s1 - s0 - p + NP - 1) / NP);
@@ -631,8 +630,8 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
     }
     return false;
   };
-  // End of a share in the by-context partition, all threads: sum the summing waves' accumulators
-  // out of mbuf[pair][head][col] (one thread per column and head quarter) and write the group's
+  // End of a share in the by-context partition, all threads: sum the waves' accumulators
+  // out of mbuf[wave][head][col] (one thread per column and head quarter) and write the group's
   // partial for this sequence.
   auto write_partial = [&](int pid) {
     const int ocl = tid & 127, ohq = tid >> 7;
@@ -659,12 +658,8 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
     }
   };
 
-  if (!has_work) {
-    // no share of the cache (fewer tiles than groups): straight to the projection
-  } else if (scoring) {
-    // ========================= scoring waves: HBM -> registers -> LDS, scores, publish ===========
+  if (has_work) {
     Seg sg;
-    int seen_consumed = 0;                          // last value read from consumed[p]
     // rotary table: this lane's 4 column pairs start at pair li * 4 of the head
     const float* rope_lane = nullptr;
     const unsigned rope_pitch = (unsigned)(a.d_k / 2) * 8u;   // bytes per table row
@@ -686,19 +681,27 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
       unsigned qh[4], ql[4];
       unsigned ph[4], pl[4];                          // (-q2, q1) of every pair, same split (rotary keys)
       // (lanes without live columns re-read the unit's first columns: finite values that meet a zero
-      //  query here and accumulator rows nobody reads in the summing wave)
+      //  query in the scores and accumulator rows nobody reads in the weighted sum)
       const unsigned lane_col_off = (unsigned)(col_active ? mycol : ucol0) * 2u;
       const unsigned lane_off = (unsigned)(rg * 8) * pitchB + lane_col_off;
       float mrun = NEG_INF;                           // running maximum of this lane's head (log2 domain)
-      // Tiles travel HBM -> registers (PD register sets: PD-1 tiles in flight while one is being
-      // scored) -> LDS slot, where the summing wave picks them up.  Direct-to-LDS loads are slower
-      // to issue here, and a wave's LDS operations queue behind those it has in flight.
+      // softmax state of the weighted sum and its accumulators; accl: sum of the weights (an all-ones A operand)
+      float m[NT];
+      f32x4 acc[8][NT], accl[NT];
+#pragma unroll
+      for (int t = 0; t < NT; ++t) {
+        m[t] = NEG_INF;
+        accl[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+      }
+      // Tiles travel HBM -> registers (PD register sets: one tile being scored, the other in flight)
+      // -> LDS slot, where the same wave picks them up one step later.
       u32x4 ts[PD][8];
       f32x4 tr[PD][2];                                // ROPE: {cos, sin} x 4 pairs at the lane's first row of the tile
       // Every call issues the same number of loads on every path (also for k past the end of the segment,
       // where all rows collapse onto the last one and nobody uses the result): the compiler's s_waitcnt
-      // for the next tile's registers is then exact.  A load skipped on some path would make it wait for
-      // the youngest loads in flight instead, i.e. for the tile requested a moment ago.
+      // for the next tile's registers is then exact.
       auto load_tile = [&](u32x4 (&t)[8], f32x4 (&r)[2], int k) {
         const int st = __builtin_amdgcn_readfirstlane(sg.t0 + k * sg.stride);
         if constexpr (ROPE) {
@@ -724,11 +727,25 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
           }
         }
       };
-      // One tile; SI is k % PD as a type, so that the register set is a compile-time choice.
-      auto step = [&](int k, auto SI) {
+      // ---- all heads' words of tile k: requested here, waited for in sum_step
+      constexpr int GW = 2 * NT;                      // 16-byte words per lane and tile
+      u32x4 gq[GW];
+      auto gather = [&](int k) {
+        const u32x4* base = team_ring + (size_t)((sg.it0 + (unsigned)k + 1u) & (EXCH_SLOTS - 1)) * (HP * 8) + (n * 4 + kg);
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+#pragma unroll
+          for (int t = 0; t < NT; ++t) gq[c * NT + t] = ld_exch(base + (c * HP + t * 16) * 4);
+      };
+      auto pin_gq = [&]() {                           // (the asm loads' results, as far as the compiler is concerned)
+        if constexpr (NT == 1) asm volatile("" : "+v"(gq[0]), "+v"(gq[1]) : : "memory");
+        else asm volatile("" : "+v"(gq[0]), "+v"(gq[1]), "+v"(gq[2]), "+v"(gq[3]) : : "memory");
+      };
+      // ---- scoring of tile k; SI is k % PD as a type, so that the register set is a compile-time choice
+      auto score_compute = [&](int k, auto SI, unsigned (&pw)[4]) {
         u32x4 (&cur)[8] = ts[decltype(SI)::value];
         f32x4 (&rot)[2] = tr[decltype(SI)::value];
-        // ---- scores of this unit's heads for the lane's 8 rows (log2 domain) --------------------
+        // scores of this unit's heads for the lane's 8 rows (log2 domain)
         float sc[8];
         if constexpr (ROPE) {
           float cc[4] = {rot[0][0], rot[0][2], rot[1][0], rot[1][2]};
@@ -775,7 +792,7 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
           if (lphp > 4) sc[j] = dpp_add<0x141>(sc[j]);     // other quad of the 8-lane half
           if (lphp > 8) sc[j] = dpp_add<0x140>(sc[j]);     // other half of the row
         }
-        // ---- this tile's softmax numerators of the unit's heads, against the running maximum -----
+        // this tile's softmax numerators of the unit's heads, against the running maximum
         const int st = sg.t0 + k * sg.stride;
         if ((st + 1) * TILE_ROWS > len) {             // last, partial tile: rows past the end weigh nothing
           const int row0 = st * TILE_ROWS + rg * 8;
@@ -786,32 +803,24 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
         tmax = max_over_row_groups(tmax);
         // The reference moves only when the maximum has grown by more than SOFTMAX_SLACK (log2 domain):
         // numerators stay below 2^SOFTMAX_SLACK, which costs bf16 and the fp32 sums nothing, and the
-        // summing waves rescale their accumulators rarely instead of at most early tiles.
+        // accumulators are rescaled rarely instead of at most early tiles.
         mrun = (tmax > mrun + SOFTMAX_SLACK) ? tmax : mrun;
         const float ref = (mrun == NEG_INF) ? 0.f : mrun;
-        unsigned pw[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const bf16x2 v = {(__bf16)__builtin_amdgcn_exp2f(sc[2 * i] - ref), (__bf16)__builtin_amdgcn_exp2f(sc[2 * i + 1] - ref)};
           pw[i] = __builtin_bit_cast(unsigned, v);
         }
-        // ---- hand the tile over: slot gk % NS (gk counts this pair's tiles over all segments), once
-        //      the summing wave has taken tile gk-NS out of it; the tile is in LDS before the words
-        //      that announce it leave
-        const int gk = (int)sg.it0 + k;
-        if (seen_consumed < gk - NS + 1) {            // (the counter only grows: re-read it only when needed)
-          int spins = 0;
-          while (!dead && (seen_consumed = __builtin_amdgcn_readfirstlane(__hip_atomic_load(
-                               &consumed[p], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP))) < gk - NS + 1) {
-            if (++spins > a.spin_limit) { give_up(); break; }
-            __builtin_amdgcn_s_sleep(2);
-          }
-        }
-        asm volatile("" ::: "memory");
+      };
+      // ---- rest of tile k's step: park, publish, request tile k+2 into the registers that become free
+      auto finish_tile = [&](int k, auto SI, const unsigned (&pw)[4]) {
+        u32x4 (&cur)[8] = ts[decltype(SI)::value];
+        f32x4 (&rot)[2] = tr[decltype(SI)::value];
+        // park the tile for this wave's own weighted sum two steps later (slot k % NS: the tile that was
+        // there has just been taken out)
 #pragma unroll
-        for (int j = 0; j < 8; ++j) tiles[p][gk % NS][j * 64 + lane] = cur[j];
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        // ---- publish: {tag, running max, p0 p1, p2 p3} and {tag, 0, p4 p5, p6 p7} per row group ----
+        for (int j = 0; j < 8; ++j) myslots[(k & (NS - 1)) * 512 + j * 64 + lane] = cur[j];
+        // publish: {tag, running max, p0 p1, p2 p3} and {tag, 0, p4 p5, p6 p7} per row group
         const unsigned itk = sg.it0 + (unsigned)k + 1u;
         const unsigned tag = a.tag_base + itk;
         u32x4* ring = team_ring + (size_t)(itk & (EXCH_SLOTS - 1)) * (HP * 8);
@@ -819,10 +828,80 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
           st_exch(ring + (myhead * 4 + rg), u32x4{tag, __float_as_uint(mrun), pw[0], pw[1]}, xl);
           st_exch(ring + ((HP + myhead) * 4 + rg), u32x4{tag, 0u, pw[2], pw[3]}, xl);
         }
-        // a hint for the summing wave (the words themselves carry the proof)
-        if (lane == 0) __hip_atomic_store(&published[p], gk + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         load_tile(cur, rot, k + PD);
       };
+      // ---- weighted sum of tile k, first part (needs no words): the tile out of its slot, as A operands
+      auto sum_prep = [&](int k, u32x4 (&am)[8]) {
+        u32x4 kt[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) kt[j] = myslots[(k & (NS - 1)) * 512 + j * 64 + lane];
+        transpose8x8(kt, am);
+      };
+      // ---- second part, with the words gathered for it (the gather's loads are done)
+      auto sum_finish = [&](int k, const u32x4 (&am)[8]) {
+        const unsigned tag = a.tag_base + sg.it0 + (unsigned)k + 1u;
+        pin_gq();
+        // every word of tile k must carry its tag; gather again while any is missing
+        int spins = 0;
+        for (;;) {
+          unsigned bad = 0;
+#pragma unroll
+          for (int t = 0; t < NT; ++t) {
+            const unsigned bt = (gq[t][0] ^ tag) | (gq[NT + t][0] ^ tag);
+            bad |= (heads_full || (t * 16 + n) < a.H) ? bt : 0u;
+          }
+          if (__all(bad == 0)) break;
+          if (dead || ++spins > a.spin_limit) { give_up(); break; }
+          __builtin_amdgcn_s_sleep(8);
+          gather(k);
+          asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+          pin_gq();
+        }
+        bf16x8 pb[NT];
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+          const bool live = heads_full || (t * 16 + n) < a.H;      // padded head: no weights at all
+          const float mn = live ? __uint_as_float(gq[t][1]) : NEG_INF;
+          const float ref = (mn == NEG_INF) ? 0.f : mn;            // all -inf so far: exp2(-inf - 0) = 0
+          const float alpha = __builtin_amdgcn_exp2f(m[t] - ref);
+          m[t] = mn;
+          const u32x4 pw = live ? u32x4{gq[t][2], gq[t][3], gq[NT + t][2], gq[NT + t][3]} : u32x4{0u, 0u, 0u, 0u};
+          pb[t] = __builtin_bit_cast(bf16x8, pw);
+          if (__any(alpha != 1.f)) {
+            accl[t] *= alpha;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[i][t] *= alpha;
+          }
+        }
+        const u32x4 ones_bits = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
+        const bf16x8 ones = __builtin_bit_cast(bf16x8, ones_bits);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) accl[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pb[t], accl[t], 0, 0, 0);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const bf16x8 av = __builtin_bit_cast(bf16x8, am[i]);
+#pragma unroll
+          for (int t = 0; t < NT; ++t)
+            acc[i][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, pb[t], acc[i][t], 0, 0, 0);
+        }
+      };
+      // One step (k >= 2): the words of tile k-2, published by every workgroup of the group more than a
+      // step ago, travel while tile k is scored; nothing younger than that gather is in flight when it
+      // is waited for, so the wait (and a repeat, should a word be missing) costs one trip to the L2.
+      auto sum_tile = [&](int k) {
+        u32x4 am[8];
+        sum_prep(k, am);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        sum_finish(k, am);
+      };
+      auto step = [&](int k, auto SI) {
+        unsigned pw[4];
+        gather(k - 2);
+        score_compute(k, SI, pw);
+        sum_tile(k - 2);
+        finish_tile(k, SI, pw);
+      };
+
 #pragma unroll
       for (int k = 0; k < PD; ++k) load_tile(ts[k], tr[k], k);
       // the query, pre-scaled (log2 domain), split into bf16 hi + lo pairs so that the dot products run
@@ -845,141 +924,31 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
           pl[c] = ((ql[c] >> 16) ^ 0x8000u) | (ql[c] << 16);
         }
       }
-      // Whole rounds of PD tiles without a condition between the steps (a step that may be skipped
-      // inside the loop would again make the waits for the tile registers conservative), then the rest.
-      int k = 0;
-      for (; k + PD <= ntl; k += PD) unrolled_steps<0, PD>(k, k + PD, step);
-      unrolled_steps<0, PD - 1>(k, ntl, step);
-      if (!by_seq) {
-        // ---- end of this share (the barriers of the merge; the slots are its buffer) --------------
-        __syncthreads();
-        __syncthreads();
-        __syncthreads();
-        write_partial(sg.pid);
-        __syncthreads();
+      {
+        using S0 = std::integral_constant<int, 0>;
+        using S1 = std::integral_constant<int, 1>;
+        unsigned pw[4];
+        if (ntl > 0) { score_compute(0, S0{}, pw); finish_tile(0, S0{}, pw); }
+        if (ntl > 1) { score_compute(1, S1{}, pw); finish_tile(1, S1{}, pw); }
+        // Whole rounds of PD steps without a condition between them (a step that may be skipped
+        // inside the loop would make the compiler's waits for the tile registers conservative).
+        int k = 2;
+        for (; k + PD <= ntl; k += PD) {
+          step(k, S0{});
+          step(k + 1, S1{});
+        }
+        if (k < ntl) step(k, S0{});
+        // the last two tiles: nothing left to score while their words travel
+        for (int kk = max(ntl - 2, 0); kk < ntl; ++kk) {
+          gather(kk);
+          sum_tile(kk);
+        }
       }
-      // (by sequence: on to the next sequence at once; its tiles wait in the slots meanwhile)
-    }
-  } else {
-    // ========================= summing waves: gather, rescale, MFMA ==============================
-    Seg sg;
-    while (next_segment(sg)) {
-      const int ntl = sg.ntl;
-      const int gk0 = (int)sg.it0;                    // this pair's tiles before this segment
-      // softmax state and accumulators; accl: sum of the weights (an all-ones A operand)
-      float m[NT];
-      f32x4 acc[8][NT], accl[NT];
-#pragma unroll
-      for (int t = 0; t < NT; ++t) {
-        m[t] = NEG_INF;
-        accl[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int i = 0; i < 8; ++i) acc[i][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-      }
-      constexpr int GW = 2 * NT;                      // 16-byte words per lane and tile
-      constexpr int DEPTH = FUSED_GATHERS;            // gathers in flight; buffer of tile k is k % DEPTH
-      auto gather = [&](u32x4 (&q)[GW], int k) {
-        const u32x4* base = team_ring + (size_t)((sg.it0 + (unsigned)k + 1u) & (EXCH_SLOTS - 1)) * (HP * 8) + (n * 4 + kg);
-#pragma unroll
-        for (int c = 0; c < 2; ++c)
-#pragma unroll
-          for (int t = 0; t < NT; ++t) q[c * NT + t] = ld_exch(base + (c * HP + t * 16) * 4);
-      };
-      // A gather is only worth issuing once the words are probably there: the partner's own
-      // progress is the hint (the workgroups of a group move at about the same pace).
-      auto partner_at = [&]() {
-        return __builtin_amdgcn_readfirstlane(
-            __hip_atomic_load(&published[p], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
-      };
-      u32x4 gq[DEPTH][GW];
-      int issued = 0;                                 // gathers of tiles 0 .. issued-1 have been issued
-      // One tile; BI is k % DEPTH as a type, so that every buffer index is a compile-time constant
-      // (the buffers must stay in the registers their loads were issued to).
-      auto step = [&](int k, auto BI) {
-        constexpr int B0 = decltype(BI)::value;
-        const unsigned tag = a.tag_base + sg.it0 + (unsigned)k + 1u;
-        if (issued == k) {                            // nothing in flight for this tile yet
-          int hs = 0;
-          while (!dead && partner_at() < gk0 + k + 1) {
-            if (++hs > a.spin_limit) { give_up(); break; }
-            __builtin_amdgcn_s_sleep(1);
-          }
-          gather(gq[B0], k);
-          issued = k + 1;
-        }
-        {                                             // look ahead as far as the partner has published
-          const int pa = partner_at();
-#pragma unroll
-          for (int i = 1; i < DEPTH; ++i)
-            if (issued == k + i && issued < ntl && pa > gk0 + issued) {
-              gather(gq[(B0 + i) % DEPTH], issued);
-              ++issued;
-            }
-        }
-        wait_vm_outstanding((issued - k - 1) * GW);
-        u32x4 (&q)[GW] = gq[B0];
-        if constexpr (NT == 1) asm volatile("" : "+v"(q[0]), "+v"(q[1]) : : "memory");
-        else asm volatile("" : "+v"(q[0]), "+v"(q[1]), "+v"(q[2]), "+v"(q[3]) : : "memory");
-        // every word of tile k must carry its tag; gather again while any is missing
-        int spins = 0;
-        for (;;) {
-          unsigned bad = 0;
-#pragma unroll
-          for (int t = 0; t < NT; ++t) {
-            const unsigned bt = (q[t][0] ^ tag) | (q[NT + t][0] ^ tag);
-            bad |= (heads_full || (t * 16 + n) < a.H) ? bt : 0u;
-          }
-          if (__all(bad == 0)) break;
-          if (dead || ++spins > a.spin_limit) { give_up(); break; }
-          __builtin_amdgcn_s_sleep(8);
-          gather(q, k);
-          asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-          if constexpr (NT == 1) asm volatile("" : "+v"(q[0]), "+v"(q[1]) : : "memory");
-          else asm volatile("" : "+v"(q[0]), "+v"(q[1]), "+v"(q[2]), "+v"(q[3]) : : "memory");
-        }
-        // the scoring wave published after it had written the tile, so the tile is in its slot
-        u32x4 kt[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) kt[j] = tiles[p][(gk0 + k) % NS][j * 64 + lane];
-        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(kt[0]), "+v"(kt[1]), "+v"(kt[2]), "+v"(kt[3]),
-                     "+v"(kt[4]), "+v"(kt[5]), "+v"(kt[6]), "+v"(kt[7]) : : "memory");
-        if (lane == 0) __hip_atomic_store(&consumed[p], gk0 + k + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        bf16x8 pb[NT];
-#pragma unroll
-        for (int t = 0; t < NT; ++t) {
-          const bool live = heads_full || (t * 16 + n) < a.H;      // padded head: no weights at all
-          const float mn = live ? __uint_as_float(q[t][1]) : NEG_INF;
-          const float ref = (mn == NEG_INF) ? 0.f : mn;            // all -inf so far: exp2(-inf - 0) = 0
-          const float alpha = __builtin_amdgcn_exp2f(m[t] - ref);
-          m[t] = mn;
-          const u32x4 pw = live ? u32x4{q[t][2], q[t][3], q[NT + t][2], q[NT + t][3]} : u32x4{0u, 0u, 0u, 0u};
-          pb[t] = __builtin_bit_cast(bf16x8, pw);
-          if (__any(alpha != 1.f)) {
-            accl[t] *= alpha;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) acc[i][t] *= alpha;
-          }
-        }
-        u32x4 am[8];
-        transpose8x8(kt, am);
-        const u32x4 ones_bits = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
-        const bf16x8 ones = __builtin_bit_cast(bf16x8, ones_bits);
-#pragma unroll
-        for (int t = 0; t < NT; ++t) accl[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pb[t], accl[t], 0, 0, 0);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          const bf16x8 av = __builtin_bit_cast(bf16x8, am[i]);
-#pragma unroll
-          for (int t = 0; t < NT; ++t)
-            acc[i][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, pb[t], acc[i][t], 0, 0, 0);
-        }
-      };
-      for (int k = 0; k < ntl; k += DEPTH) unrolled_steps<0, DEPTH>(k, ntl, step);
 
-      // ---- end of this sequence's share: merge the four summing waves and write one partial -------
+      // ---- end of this sequence's share ---------------------------------------------------------------
       if (by_seq) {
-        // the whole sequence was this wave's: transpose through the pair's part of sbuf
-        // (TRANSPOSE_HEADS heads per pass, no other wave involved) and write the sequence's partial
+        // the whole share was this wave's: transpose through the wave's part of sbuf
+        // (TRANSPOSE_HEADS heads per pass, no other wave involved) and write the share's partial
         float* mine = sbuf + (size_t)p * TRANSPOSE_HEADS * 129;
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
@@ -1015,7 +984,8 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
         }
         continue;
       }
-      // ---- by context: merge the four summing waves and write one partial -------------------------
+      // ---- by context: merge the waves and write one partial (every wave of the workgroup walks the
+      //      same shares, so all of them meet at these barriers) -------------------------------------
       __syncthreads();                                // every slot is idle from here on
       if (kg == 0) {
 #pragma unroll
@@ -1023,8 +993,8 @@ __global__ __launch_bounds__(FUSED_PAIRS * 128) void fused_stream_kernel(const F
       }
       __syncthreads();
       {
-        // accumulators -> mbuf[pair][head][col] (row pitch 129 floats), in MFMA layout, scaled to
-        // the maximum over the four summing waves
+        // accumulators -> mbuf[wave][head][col] (row pitch 129 floats), in MFMA layout, scaled to
+        // the maximum over the waves
         float wsc[NT];
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
@@ -1100,7 +1070,7 @@ bool fused_geometry(int B, int H, int T, int d, FusedGeom* g) {
   g->hpu = 16 / lphp;
   g->G = (H + g->hpu - 1) / g->hpu;
   g->NT = H <= 16 ? 1 : 2;
-  g->NP = FUSED_PAIRS;
+  g->NP = FUSED_WAVES;
   const int cus = 256;
   if (g->G > cus) return false;
   if (g->G <= 32) {
@@ -1145,7 +1115,7 @@ bool xcd_round_robin(int device) {
 // the wave-pair slots evenly (1..4), or 0 to keep the balanced by-context partition.  Ragged
 // batches qualify only with many shares per slot.
 int fused_by_sequence(const FusedGeom& g, int B, bool ragged) {
-  const long slots = (long)g.NG * FUSED_PAIRS;
+  const long slots = (long)g.NG * FUSED_WAVES;
   int best = 0;
   double best_waste = 1.13;                           // at most 13 % idle slot-time
   for (int s = 1; s <= 4; ++s) {
@@ -1163,7 +1133,7 @@ size_t fused_exch_bytes(const FusedGeom& g) {
 }
 
 void launch_fused_stream(const FusedGeom& g, const FusedArgs& a, hipStream_t st) {
-  dim3 grid(g.grid), block(g.NP * 128);
+  dim3 grid(g.grid), block(g.NP * 64);
   auto go = [&](auto nt, auto rope, auto lphp) {
     hipLaunchKernelGGL((fused_stream_kernel<decltype(nt)::value, decltype(rope)::value, decltype(lphp)::value>), grid, block, 0, st, a);
   };

@@ -56,16 +56,15 @@ void launch_vanilla(int dtype, const float* q, const void* K, const void* V, lon
 constexpr int TILE_ROWS = 32;        // cache rows per wave tile
 constexpr int EXCH_SLOTS = 16;       // ring depth of the score exchange (a power of two >= 2 * FUSED_SLOTS)
 constexpr int FUSED_MAX_B = 1024;    // sequences per call the fast path handles
-constexpr int FUSED_PAIRS = 4;       // (scoring wave, summing wave) pairs per workgroup of the stream kernel
-constexpr int FUSED_SLOTS = 4;       // LDS landing slots (8 KB tiles) per pair
-constexpr int FUSED_AHEAD = 2;       // register sets of a scoring wave: one tile being scored, the others in flight
-constexpr int FUSED_GATHERS = 4;     // score gathers a summing wave keeps in flight
+constexpr int FUSED_WAVES = 8;       // waves per workgroup of the stream kernel, each with tiles of its own
+constexpr int FUSED_SLOTS = 2;       // LDS landing slots (8 KB tiles) per wave
+constexpr int FUSED_AHEAD = 2;       // register sets of a wave: one tile being scored, the other in flight
 constexpr int PROJ_MAX_PARTS = 64;   // partials per sequence the projection merges
 
 struct FusedGeom {
   int lph, lphp, hpu;   // active lanes per head (d_k/8), lanes reserved per head, heads per unit
   int G, NG, gpx;       // column units per group, groups, groups per XCD (0 = not packed)
-  int NT, NP, grid, nparts;   // MFMA head tiles, wave pairs per workgroup
+  int NT, NP, grid, nparts;   // MFMA head tiles, waves per workgroup
 };
 
 struct ProjArgs {
