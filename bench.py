@@ -1,13 +1,15 @@
 #!/usr/bin/env python3
 """Benchmark of the slim-attention decode step on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1] [--variant auto]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config N] [--variant auto]
 
 A step is one pass of the whole hot path (`slim_decode`: scores, softmax, weighted sum of K,
 split merge, per-head W_KV projection) over one batch of the seeded synthetic workload, with
-every input resident in HBM before the timed region.  The default workload is config 1
-(CodeLlama-7B-shaped layer, B=1, H=32, d=4096, T=16384, bf16 K-cache).  The K-cache is rotated
-over several identical copies so the 256 MB memory-side cache cannot serve the stream.
+every input resident in HBM before the timed region.  The default workload is config 2, the
+largest one that fits one GPU (Phi-3-mini-shaped batch, B=16, H=32, d=3072, ragged contexts of
+8192..32768 rows, bf16 K-cache); config 1 (CodeLlama-7B-shaped, B=1, T=16384) is timed in the same
+run and nested in the same line.  The K-cache and W_KV are rotated over several identical copies so
+the 256 MB memory-side cache cannot serve them.
 
 Prints one JSON line: whole-job tokens/s (a token = one sequence's decode step through this
 one attention layer), the same-GPU `vanilla_kv_decode` time, the roofline entry of the
@@ -258,45 +260,9 @@ def bench_block(args, cfg, torch, binding, synth):
     print(json.dumps(result), flush=True)
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", type=int, default=1, choices=[0, 1, 2, 3, 4])
-    ap.add_argument("--variant", default="auto", choices=["auto", "generic", "fused", "fused_split"])
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--copies", type=int, default=0, help="K-cache copies to rotate over (0 = enough to exceed 512 MB)")
-    ap.add_argument("--rope", action="store_true",
-                    help="keys carry rotary positions: slim_decode rotates the raw cached keys for the scores (K-cache configs)")
-    ap.add_argument("--ecache", action="store_true",
-                    help="config 3 only: the cross-attention layer reads the encoder output E through slim_decode_xcache "
-                         "(option 2 of the encoder-decoder section) instead of a cross K-cache")
-    ap.add_argument("--block", action="store_true",
-                    help="time the whole attention block (slim_attention_block vs vanilla_attention_block) instead of the decode step")
-    ap.add_argument("--calibration-copy", action="store_true",
-                    help="also run a few plain 128 MiB device copies (a kernel of known traffic, for scaling rocprofv3 byte counters)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        sys.exit("bench.py: this build runs on one GPU only (no sharding or collectives); use --gpus 1")
-
-    import torch
-    from paper_2503_05840_amd import binding, synth
-
-    if not torch.cuda.is_available():
-        sys.exit("bench.py: no GPU visible")
-    binding.load()
-    cfg = synth.CONFIGS[args.config]
-    if args.ecache:
-        if args.config != 3:
-            sys.exit("bench.py: --ecache applies to config 3 (the encoder-decoder cross-attention shape)")
-        cfg = synth.scaled(cfg, kind="xcache", name=cfg.name + " as E-cache (option 2)")
-    if cfg.kind == "xcache":
-        if args.rope or args.block:
-            sys.exit("bench.py: --rope and --block apply to the K-cache configs (0-3)")
-        return bench_xcache(args, cfg, torch, binding, synth)
-    if args.block:
-        return bench_block(args, cfg, torch, binding, synth)
+def bench_kcache(args, cfg, torch, binding, synth, with_cpu):
+    """One K-cache config: slim_decode against vanilla_kv_decode, per-kernel times, the read probe and
+    (with_cpu) the oracle on the host cores.  Returns the result as a dict."""
     B, H, T, d, d_k = cfg.B, cfg.H, cfg.T, cfg.d, cfg.d_k
     es = 2 if cfg.dtype == "bf16" else 4
     log(f"[bench] building inputs for config {cfg.index} ({cfg.name}) ...")
@@ -324,8 +290,14 @@ def main():
     ncopies = args.copies or max(2, int(np.ceil(512e6 / k_bytes_alloc)) + 1)
     Ks = [to_device(Kh) for _ in range(ncopies)]
     Vs = [to_device(Vh) for _ in range(ncopies)]
+    del Kh, Vh
     q = to_device(p.q.astype(np.float32))
-    Wkv = to_device(binding.slim_pack_weights(wkv, cfg.dtype))
+    # W_KV rotates with the cache copies: at small batch it is a quarter of the step's bytes and one
+    # buffer would be served by the memory-side cache
+    w_host = binding.slim_pack_weights(wkv, cfg.dtype)
+    wcopies = max(2, int(np.ceil(512e6 / w_host.nbytes)) + 1) if w_host.nbytes < 512e6 else 2
+    wcopies = min(wcopies, 24)
+    Wkvs = [to_device(w_host) for _ in range(wcopies)]
     lens_dev = torch.from_numpy(lens).cuda()
     out = torch.zeros((B, d), device="cuda", dtype=torch.float32)
     out_v = torch.zeros_like(out)
@@ -343,22 +315,13 @@ def main():
         kw_rope = {}
     variant = {"auto": binding.VARIANT_AUTO, "generic": binding.VARIANT_GENERIC,
                "fused": binding.VARIANT_FUSED, "fused_split": binding.VARIANT_FUSED_SPLIT}[args.variant]
+    binding.slim_init()
 
-    def slim(i, **extra):
-        binding.slim_decode(q, Ks[i % ncopies], Wkv, out, B, H, T, d, variant=variant, **kw, **kw_rope, **extra)
+    def slim(i, variant=variant, **extra):
+        binding.slim_decode(q, Ks[i % ncopies], Wkvs[i % wcopies], out, B, H, T, d, variant=variant, **kw, **kw_rope, **extra)
 
     def vanilla(i, **extra):
         binding.vanilla_kv_decode(q, Ks[i % ncopies], Vs[i % ncopies], out_v, B, H, T, d, **kw, **extra)
-
-    def timed(fn, steps, warmup):
-        for i in range(warmup):
-            fn(i)
-        torch.cuda.synchronize()
-        t = time.perf_counter()
-        for i in range(steps):
-            fn(i)
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t) * 1e3 / steps
 
     if args.calibration_copy:
         src = torch.empty(128 << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
@@ -368,11 +331,14 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     log("[bench] timing slim_decode ...")
-    ms_slim = timed(slim, args.steps, args.warmup)
+    ms_slim = timed(torch, slim, args.steps, args.warmup)
     log("[bench] timing vanilla_kv_decode ...")
-    ms_van = timed(vanilla, args.steps, args.warmup)
+    ms_van = timed(torch, vanilla, args.steps, args.warmup)
     # hot numbers (one buffer, may be served by the memory-side cache)
-    ms_slim_hot = timed(lambda i: slim(0), args.steps, 3)
+    ms_slim_hot = timed(torch, lambda i: slim(0), args.steps, 3)
+    # the read rate this GPU sustains on the same buffers, same process: the practical ceiling of the K stream
+    ms_probe = timed(torch, lambda i: binding.slim_read_probe(Ks[i % ncopies]), max(10, args.steps // 4), 3)
+    probe_gbps = k_bytes_alloc / (ms_probe * 1e-3) / 1e9
 
     # per-kernel durations, HIP events on the launch stream (second pass over the same steps)
     log("[bench] per-kernel event timing ...")
@@ -394,6 +360,15 @@ def main():
     k_bytes = float(lens.astype(np.int64).sum()) * d * es            # K-cache rows read once
     w_bytes = float(d) * d * es                                       # W_KV once per step
     one_launch = which == "fused" and acc[1] == 0.0                   # B <= 16: merge + projection inside
+    split_ms = None
+    if which == "fused":
+        # the K stream alone (scores, softmax, weighted sum) and the merge + projection as launches of their own
+        sacc = np.zeros(binding.MAX_STAGES)
+        for i in range(args.steps):
+            slim(i, variant=binding.VARIANT_FUSED_SPLIT, stage_ms=stage)
+            sacc += np.array(list(stage))
+        sacc /= args.steps
+        split_ms = (float(sacc[0]), float(sacc[1]))
     if one_launch:
         names = ["fused_stream"]
     dom = int(np.argmax(acc[:len(names)]))
@@ -408,7 +383,7 @@ def main():
                 "stage_ms": {n: round(float(acc[i]), 5) for i, n in enumerate(names)}}
 
     cpu = None
-    if not args.no_cpu_baseline:
+    if with_cpu and not args.no_cpu_baseline:
         # the only place bench.py touches the oracle: it is timed as it stands, and its result
         # for sequence 0 is compared with what the timed GPU path produced
         from oracle import mha_oracle as orc
@@ -434,6 +409,7 @@ def main():
                "gpu_max_rel_err_vs_oracle_seq0": float(f"{err:.3e}")}
 
     ms = ms_slim
+    k_gbps = k_bytes / (ms * 1e-3) / 1e9
     result = {
         "metric": "decode tokens/s (one attention layer step, K-cache only) + effective K-cache GB/s vs vanilla K+V, 1 GPU",
         "value": round(B / (ms * 1e-3), 2), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
@@ -441,16 +417,81 @@ def main():
         "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"configs[{cfg.index}] {cfg.name}" + (" + rotary keys (RoPE option 1, raw keys cached)" if args.rope else ""),
                    "B": B, "H": H, "d": d, "d_k": d_k, "T": T,
-                   "sum_len": int(lens.sum()), "variant": which, "k_cache_copies_rotated": ncopies},
-        "k_cache_gbps": round(k_bytes / (ms * 1e-3) / 1e9, 1),
-        "k_cache_frac_of_hbm_peak": round(k_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                   "sum_len": int(lens.sum()), "variant": which, "k_cache_copies_rotated": ncopies, "w_kv_copies_rotated": wcopies},
+        "k_cache_gbps": round(k_gbps, 1),
+        "k_cache_frac_of_hbm_peak": round(k_gbps / HBM_PEAK_GBPS, 4),
+        "measured_read_stream_gbps": round(probe_gbps, 1),
+        "k_cache_frac_of_measured_stream_peak": round(k_gbps / probe_gbps, 4),
         "ms_per_step_hot_single_buffer": round(ms_slim_hot, 5),
         "vanilla_kv_ms_per_step": round(ms_van, 5), "vanilla_kv_kernel_ms": round(vacc, 5),
         "vanilla_kv_gbps": round(2 * k_bytes / (ms_van * 1e-3) / 1e9, 1),
         "speedup_vs_vanilla_kv": round(ms_van / ms, 3),
+        "bytes_ratio_vanilla_over_slim": round(2 * k_bytes / (k_bytes + w_bytes), 3),
         "roofline": roofline, "cpu_baseline": cpu,
-        "paper_context": "paper reports no measurement; analytical: up to 2x for long context (memory-bound), Whisper B=64 1.8x (K-only) / 5.3x (E-cache)",
     }
+    if split_ms is not None:
+        # K1 + K2 (the K stream) apart from K3 (merge + W_KV projection), as two launches
+        result["k_stream_only_ms"] = round(split_ms[0], 5)
+        result["k_stream_only_gbps"] = round(k_bytes / (split_ms[0] * 1e-3) / 1e9, 1)
+        result["k_stream_only_frac_of_hbm_peak"] = round(k_bytes / (split_ms[0] * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)
+        result["merge_projection_ms"] = round(split_ms[1], 5)
+    del Ks, Vs, Wkvs, ws
+    torch.cuda.empty_cache()
+    return result
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=None, choices=[0, 1, 2, 3, 4],
+                    help="time this config only (default: configs[2], the largest single-GPU one, as the headline, "
+                         "with configs[1] nested in the same line)")
+    ap.add_argument("--variant", default="auto", choices=["auto", "generic", "fused", "fused_split"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copies", type=int, default=0, help="K-cache copies to rotate over (0 = enough to exceed 512 MB)")
+    ap.add_argument("--rope", action="store_true",
+                    help="keys carry rotary positions: slim_decode rotates the raw cached keys for the scores (K-cache configs)")
+    ap.add_argument("--ecache", action="store_true",
+                    help="config 3 only: the cross-attention layer reads the encoder output E through slim_decode_xcache "
+                         "(option 2 of the encoder-decoder section) instead of a cross K-cache")
+    ap.add_argument("--block", action="store_true",
+                    help="time the whole attention block (slim_attention_block vs vanilla_attention_block) instead of the decode step")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run a few plain 128 MiB device copies (a kernel of known traffic, for scaling rocprofv3 byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no sharding or collectives); use --gpus 1")
+
+    import torch
+    from paper_2503_05840_amd import binding, synth
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    binding.load()
+    headline = 2 if args.config is None else args.config
+    cfg = synth.CONFIGS[headline]
+    if args.ecache:
+        if headline != 3:
+            sys.exit("bench.py: --ecache applies to config 3 (the encoder-decoder cross-attention shape)")
+        cfg = synth.scaled(cfg, kind="xcache", name=cfg.name + " as E-cache (option 2)")
+    if cfg.kind == "xcache":
+        if args.rope or args.block:
+            sys.exit("bench.py: --rope and --block apply to the K-cache configs (0-3)")
+        return bench_xcache(args, cfg, torch, binding, synth)
+    if args.block:
+        return bench_block(args, cfg, torch, binding, synth)
+    result = bench_kcache(args, cfg, torch, binding, synth, with_cpu=True)
+    if args.config is None:
+        # the 16k-context single-sequence config rides along in the same line (no second oracle timing)
+        extra = bench_kcache(args, synth.CONFIGS[1], torch, binding, synth, with_cpu=False)
+        keep = ("ms_per_step", "value", "k_cache_gbps", "k_cache_frac_of_hbm_peak", "k_cache_frac_of_measured_stream_peak",
+                "measured_read_stream_gbps", "vanilla_kv_ms_per_step", "speedup_vs_vanilla_kv", "bytes_ratio_vanilla_over_slim",
+                "k_stream_only_ms", "k_stream_only_frac_of_hbm_peak", "merge_projection_ms", "roofline", "config")
+        result["other_configs"] = {"configs[1]": {k: extra[k] for k in keep if k in extra}}
+    result["paper_context"] = ("paper reports no measurement; analytical: up to 2x for long context (memory-bound), "
+                               "Whisper B=64 1.8x (K-only) / 5.3x (E-cache)")
     print(json.dumps(result), flush=True)
 
 

@@ -18,9 +18,9 @@
  *   - Device pointers must be 16-byte aligned; row pitches are dense.
  *   - Every function returns SLIM_OK (0) or a negative SLIM_ERR_* code; nothing throws or
  *     aborts.  Argument errors are detected on the host before anything is launched.
- *   - Waits between workgroups inside the kernels are bounded; if one ever runs out (a device
- *     that cannot keep a launch's 256 workgroups resident at once), the affected outputs are
- *     written as NaN instead of the kernel hanging.
+ *   - Waits between workgroups inside the kernels are bounded in real time; if one ever runs out
+ *     (the launch's workgroups were not all resident together), the outputs of that call are
+ *     written as NaN instead of the kernel hanging, and slim_status reports SLIM_ERR_TIMEOUT.
  *   - q is the already projected, un-scaled query (the library applies 1/sqrt(d_k)); out is
  *     concat(head_1..head_H) before W_O (eq. 5).  Attention runs over exactly the cached
  *     rows handed in (the caller appends the new token's key first if it wants it attended).
@@ -46,6 +46,7 @@ extern "C" {
 #define SLIM_ERR_ILLCOND    -7   /* result written, but rcond(W_K) < 1e-12: do not trust it   */
 #define SLIM_ERR_LAUNCH     -8   /* HIP reported an error at allocation or launch             */
 #define SLIM_ERR_SEQLEN     -9   /* a host-side sequence length is < 1 or > T                 */
+#define SLIM_ERR_TIMEOUT   -10   /* slim_status: a wait between workgroups ran out (outputs NaN) */
 
 /* ---- element types of the cache and of packed weights -------------------------------- */
 #define SLIM_F32   0
@@ -113,6 +114,10 @@ typedef struct slim_opts {
                                     milliseconds in launch order (unused entries = 0)             */
   const float*   rope_table;     /* device fp32 [T][d_k/2][2] from slim_rope_table, nullable => keys
                                     carry no rotary position.  slim_decode only (see there)       */
+  int64_t        wait_budget_us; /* bound of every wait between workgroups of the bf16 fast path, in
+                                    microseconds of real time: 0 => 20000; negative => no waiting at
+                                    all (every wait that is not satisfied at once gives up: for tests
+                                    of the failure path, see slim_status)                          */
 } slim_opts;
 
 #define SLIM_MAX_STAGES 8
@@ -124,6 +129,25 @@ typedef struct slim_opts {
 #define SLIM_VARIANT_FUSED     3   /* bf16, H <= 32, d_k <= 128: single pass over K with the weighted
                                       sum and the projection on MFMA (one launch when B <= 16, else
                                       two); falls back to GENERIC when the shape does not qualify */
+
+/* Per-device set-up for the current device, idempotent and thread-safe: looks up the address of the
+ * library's static device array, counts the compute units, checks with one probe launch on the null stream (plus a
+ * blocking read-back; no allocation) that consecutive workgroups of a launch are spread round-robin
+ * over the XCDs, and creates the event that orders launches of different streams.  The decode calls
+ * do this themselves on first use; calling it up front keeps that work (and its synchronisation) out
+ * of the first decode call, e.g. before a stream capture starts.  SLIM_ERR_LAUNCH when HIP fails. */
+int slim_init(void);
+
+/* Whether the waits between workgroups of the latest bf16 fast-path launch that used this workspace
+ * ended normally.  The decode calls are asynchronous and return before their kernels have run, so a
+ * wait that runs out inside a kernel (the chip could not keep the launch's workgroups resident
+ * together within opts->wait_budget_us, e.g. because other work held compute units) cannot be reported
+ * by the call itself: the kernel raises an error word in the workspace and writes NaN outputs.  This
+ * query waits for `stream` (hipStream_t, null => the null stream), reads the word back and returns
+ * SLIM_ERR_TIMEOUT or SLIM_OK.  The fast path needs the chip free of other kernels while it runs.
+ *   workspace: the device scratch the call was given; NULL => the library-owned scratch of the
+ *              current device. */
+int slim_status(const void* workspace, void* stream);
 
 /* The implementation SLIM_VARIANT_AUTO resolves to for a K-cache decode of this shape
  * (one of the SLIM_VARIANT_* values above, never AUTO); 0 on invalid arguments. */
@@ -168,6 +192,12 @@ int vanilla_kv_decode(const void* q, const void* Kcache, const void* Vcache, voi
 int slim_decode_xcache(const void* q, const void* X, const void* W_K, const void* W_V,
                        void* out, int B, int H, int T, int d_model, int d_k,
                        const slim_opts* opts);
+
+/* Measurement only: one plain streaming read of `bytes` bytes of device memory at `buf` (16-byte loads,
+ * nothing else), asynchronous on `stream`.  Timed by the benchmark beside the decode step: the read
+ * rate this GPU sustains in the same process is the practical ceiling of the K stream (eq. 7 option 2
+ * reads the cache once; Table 2 counts those reads). */
+int slim_read_probe(const void* buf, size_t bytes, void* stream);
 
 /* ---- the steps either side of the decode step ------------------------------------------- */
 

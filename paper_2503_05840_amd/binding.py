@@ -21,7 +21,8 @@ DTYPES = {"f32": SLIM_F32, "bf16": SLIM_BF16}
 
 EXPORTS = ("slim_strerror", "slim_prepare_wkv", "slim_prepare_wkv_nonsquare", "slim_pack_weights", "slim_rope_table", "slim_workspace_bytes",
            "slim_workspace_bytes_xcache", "slim_workspace_bytes_block", "slim_attention_block", "vanilla_attention_block",
-           "slim_variant_for", "slim_decode", "vanilla_kv_decode", "slim_decode_xcache")
+           "slim_variant_for", "slim_decode", "vanilla_kv_decode", "slim_decode_xcache", "slim_init", "slim_status",
+           "slim_read_probe")
 VARIANT_NAMES = {1: "generic", 2: "fused_split", 3: "fused"}
 
 
@@ -37,6 +38,7 @@ class SlimOpts(ctypes.Structure):
         ("variant", ctypes.c_int),
         ("stage_ms", ctypes.POINTER(ctypes.c_float)),
         ("rope_table", ctypes.c_void_p),
+        ("wait_budget_us", ctypes.c_int64),
     ]
 
 
@@ -93,6 +95,12 @@ def load():
     lib.slim_attention_block.argtypes = [vp, vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, op]
     lib.vanilla_attention_block.restype = ci
     lib.vanilla_attention_block.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, op]
+    lib.slim_init.restype = ci
+    lib.slim_init.argtypes = []
+    lib.slim_status.restype = ci
+    lib.slim_status.argtypes = [vp, vp]
+    lib.slim_read_probe.restype = ci
+    lib.slim_read_probe.argtypes = [vp, ctypes.c_size_t, vp]
     _lib = lib
     return lib
 
@@ -179,7 +187,32 @@ def to_device(a: np.ndarray):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
-def _opts(dtype, seq_lens, seq_lens_host, t_stride, workspace, variant, stage_ms=None, rope_table=None):
+SLIM_ERR_TIMEOUT = -10
+
+
+def slim_init():
+    rc = load().slim_init()
+    if rc != SLIM_OK:
+        raise SlimError(rc, "slim_init")
+
+
+def slim_status(workspace=None) -> int:
+    """SLIM_OK or SLIM_ERR_TIMEOUT for the latest fast-path launch on `workspace` (a device tensor, None for
+    the library-owned scratch); waits for the current stream."""
+    import torch
+    ws = workspace if isinstance(workspace, int) or workspace is None else workspace.data_ptr()
+    return int(load().slim_status(ws, torch.cuda.current_stream().cuda_stream))
+
+
+def slim_read_probe(buf) -> None:
+    """Plain streaming read of a device tensor (measurement only: the read rate this GPU sustains)."""
+    import torch
+    rc = load().slim_read_probe(_dev_ptr(buf), buf.numel() * buf.element_size(), torch.cuda.current_stream().cuda_stream)
+    if rc != SLIM_OK:
+        raise SlimError(rc, "slim_read_probe")
+
+
+def _opts(dtype, seq_lens, seq_lens_host, t_stride, workspace, variant, stage_ms=None, rope_table=None, wait_budget_us=0):
     import torch
     o = SlimOpts()
     o.dtype = DTYPES[dtype]
@@ -198,6 +231,7 @@ def _opts(dtype, seq_lens, seq_lens_host, t_stride, workspace, variant, stage_ms
         o.stage_ms = ctypes.cast(stage_ms, ctypes.POINTER(ctypes.c_float))
     if rope_table is not None:
         o.rope_table = _dev_ptr(rope_table)
+    o.wait_budget_us = int(wait_budget_us)
     return o, keep
 
 
@@ -213,8 +247,8 @@ def _dev_ptr(t):
 
 
 def slim_decode(q, Kcache, W_KV, out, B, H, T, d, dtype="bf16", seq_lens=None, seq_lens_host=None,
-                t_stride=0, workspace=None, variant=VARIANT_AUTO, stage_ms=None, rope_table=None):
-    o, keep = _opts(dtype, seq_lens, seq_lens_host, t_stride, workspace, variant, stage_ms, rope_table)
+                t_stride=0, workspace=None, variant=VARIANT_AUTO, stage_ms=None, rope_table=None, wait_budget_us=0):
+    o, keep = _opts(dtype, seq_lens, seq_lens_host, t_stride, workspace, variant, stage_ms, rope_table, wait_budget_us)
     rc = load().slim_decode(_dev_ptr(q), _dev_ptr(Kcache), _dev_ptr(W_KV), _dev_ptr(out), B, H, T, d,
                             ctypes.byref(o))
     if rc != SLIM_OK:

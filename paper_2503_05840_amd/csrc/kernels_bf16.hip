@@ -509,16 +509,14 @@ __global__ __launch_bounds__(FUSED_WAVES * 64) void fused_stream_kernel(const Fu
   __shared__ float larr[NP][NT][16];
   // Per wave: NS landing slots of 8 KB for K tiles.  By-context partition: the end-of-share merge of
   // the waves goes through the (then idle) slots, which is why the array is a little larger than
-  // the slots.  By-sequence partition: the other waves keep streaming, so a wave transposes its
-  // result through a part of its own in sbuf, TRANSPOSE_HEADS heads per pass.  The projection of the
-  // single-launch mode runs after everything else and reuses both.
-  constexpr int TRANSPOSE_HEADS = 4;
-  constexpr size_t SLOT_BYTES = sizeof(u32x4) * NP * NS * 512, MERGE_BYTES = sizeof(float) * NP * HP * 129;
+  // the slots.  By-sequence partition: the other waves keep streaming; a wave writes its result
+  // straight from its registers.  The projection of the single-launch mode runs after everything
+  // else and reuses the slots and sbuf.
+  constexpr int MERGE_PITCH = 132;                  // floats per head row of the merge buffer: 16-byte accesses without bank conflicts
+  constexpr size_t SLOT_BYTES = (size_t)NP * NS * TILE_ROWS * 272, MERGE_BYTES = sizeof(float) * NP * HP * MERGE_PITCH;   // (272: a tile row and its padding)
   __shared__ __align__(16) unsigned char lds_main[SLOT_BYTES > MERGE_BYTES ? SLOT_BYTES : MERGE_BYTES];
-  __shared__ __align__(16) float sbuf[(sizeof(ProjShared<1>) > sizeof(float) * NP * TRANSPOSE_HEADS * 129
-                                           ? sizeof(ProjShared<1>) : sizeof(float) * NP * TRANSPOSE_HEADS * 129) / sizeof(float)];
-  u32x4* const tiles = reinterpret_cast<u32x4*>(lds_main);          // [NP][NS][512]
-  float* const mbuf = reinterpret_cast<float*>(lds_main);           // [NP][HP][129] floats
+  __shared__ __align__(16) float sbuf[sizeof(ProjShared<1>) / sizeof(float)];
+  float* const mbuf = reinterpret_cast<float*>(lds_main);           // [NP][HP][MERGE_PITCH] floats
   float* const red = reinterpret_cast<float*>(lds_main);            // 64 KB for the projection's cross-wave sum
   static_assert(sizeof(float) * 8 * 8 * 4 * 64 <= sizeof(lds_main), "cross-wave sum must fit");
 
@@ -570,19 +568,43 @@ __global__ __launch_bounds__(FUSED_WAVES * 64) void fused_stream_kernel(const Fu
   for (int r = 0; r < 4; ++r) {
     const int mi = rg * 4 + r;                      // column group (the A operand's M index)
     const int h2 = mi / lphp, l2 = mi % lphp;
-    ocol[r] = (l2 < a.lph && h2 < a.hpu) ? h2 * a.d_k + l2 * 8 : -1;
+    ocol[r] = (l2 < a.lph && h2 < a.hpu && h2 * a.d_k + l2 * 8 < uwc) ? h2 * a.d_k + l2 * 8 : -1;
   }
+
+  // A tile in its LDS slot: row r, 16-byte chunk c (8 columns) at byte r * ROW_PITCH + c * 16, with one
+  // chunk of padding per row (17 chunks), so that all three access patterns are free of bank conflicts
+  // and each is one per-lane base plus compile-time offsets: the store and the read for the weighted sum
+  // (the 16 chunks of a row) and the A operands of the score MFMA (one chunk of 16 consecutive rows).
+  //   store of row rg*8 + j, chunk idx ........................ wpos + j * ROW_PITCH
+  //   score A operand, rows mt*16 + idx, chunk ks*4 + rg ...... spos + mt * 16 * ROW_PITCH + ks * 64
+  //   sum, rows jh*16 + kg*4 + jl, chunk idx (no rotary keys) . ppos + (jh * 16 + jl) * ROW_PITCH
+  constexpr unsigned ROW_PITCH = 272, SLOT_PITCH = TILE_ROWS * ROW_PITCH;
+  const unsigned wpos = (unsigned)(rg * 8) * ROW_PITCH + (unsigned)idx * 16u;
+  const unsigned spos = (unsigned)idx * ROW_PITCH + (unsigned)rg * 16u;
+  const unsigned ppos = (unsigned)(kg * 4) * ROW_PITCH + (unsigned)idx * 16u;
+  // Scores on MFMA (no rotary keys): column n = 2 * (head in unit) + {0: query hi, 1: query lo}; the lane
+  // with the even n publishes its head's words for its four-row groups.
+  const int mhead = u * a.hpu + (idx >> 1);          // head of this lane's score column
+  const bool mpub_lane = !(idx & 1) && (idx >> 1) < a.hpu && mhead < a.H;
 
   const bool xl = a.xcd_local != 0;
   const bool heads_full = (a.H == HP);               // no padded heads in the MFMA N tiles
   const unsigned pitchB = (unsigned)a.d * 2u;        // bytes per cache row
   u32x4* const team_ring = reinterpret_cast<u32x4*>(a.exch) + (size_t)(g * NP + p) * EXCH_SLOTS * (HP * 8);
-  u32x4* const myslots = tiles + (size_t)p * NS * 512;
+  char* const myslots = reinterpret_cast<char*>(lds_main) + (size_t)p * NS * SLOT_PITCH;
   bool dead = false;                                // a wait timed out: stop waiting, just drain
   auto give_up = [&]() {
     if (!dead && lane == 0) atomicExch(a.err, (int)a.launch_id);
     dead = true;
   };
+  // Every wait for another workgroup is bounded by the same budget of real time (the constant
+  // 100 MHz counter), measured from the first failed check of that wait.
+  auto out_of_time = [&](unsigned long long& since) {
+    const unsigned long long now = __builtin_amdgcn_s_memrealtime();
+    if (since == ~0ull) since = now;
+    return now - since >= a.wait_ticks;
+  };
+  if (blockIdx.x == 0 && tid == 0) st_result(a.err - 1, (int)a.launch_id, true);   // the launch the error word speaks of
 
   // The work of this wave as a list of segments (a sequence or a share of one); tile k of a segment is
   // row tile t0 + k * stride of sequence b.  Two partitions:
@@ -631,18 +653,18 @@ __global__ __launch_bounds__(FUSED_WAVES * 64) void fused_stream_kernel(const Fu
     return false;
   };
   // End of a share in the by-context partition, all threads: sum the waves' accumulators
-  // out of mbuf[wave][head][col] (one thread per column and head quarter) and write the group's
+  // out of mbuf[wave][head][col] (one thread per four columns of a head) and write the group's
   // partial for this sequence.
   auto write_partial = [&](int pid) {
-    const int ocl = tid & 127, ohq = tid >> 7;
-    if (ocl < uwc) {
+    const int oc4 = (tid & 31) * 4, oh0 = tid >> 5;  // four columns of heads oh0, oh0 + 16
+    if (oc4 < uwc) {
 #pragma unroll
-      for (int jj = 0; jj < HP / 4; ++jj) {
-        const int h = ohq + 4 * jj;
-        float osum = 0.f;
+      for (int jj = 0; jj < HP / 16; ++jj) {
+        const int h = oh0 + 16 * jj;
+        f32x4 osum = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int ww = 0; ww < NP; ++ww) osum += mbuf[((size_t)ww * HP + h) * 129 + ocl];
-        if (h < a.H) st_result(a.Cpart + ((size_t)pid * a.H + h) * a.d + ucol0 + ocl, osum, fuse);
+        for (int ww = 0; ww < NP; ++ww) osum += *reinterpret_cast<const f32x4*>(mbuf + ((size_t)ww * HP + h) * MERGE_PITCH + oc4);
+        if (h < a.H) st_result4(a.Cpart + ((size_t)pid * a.H + h) * a.d + ucol0 + oc4, osum, fuse);
       }
     }
     if (u == 0 && tid < a.H) {
@@ -685,6 +707,7 @@ __global__ __launch_bounds__(FUSED_WAVES * 64) void fused_stream_kernel(const Fu
       const unsigned lane_col_off = (unsigned)(col_active ? mycol : ucol0) * 2u;
       const unsigned lane_off = (unsigned)(rg * 8) * pitchB + lane_col_off;
       float mrun = NEG_INF;                           // running maximum of this lane's head (log2 domain)
+      bf16x8 bq[4];                                   // B operands of the score MFMA (filled below, behind the first tile requests)
       // softmax state of the weighted sum and its accumulators; accl: sum of the weights (an all-ones A operand)
       float m[NT];
       f32x4 acc[8][NT], accl[NT];
@@ -741,63 +764,22 @@ __global__ __launch_bounds__(FUSED_WAVES * 64) void fused_stream_kernel(const Fu
         if constexpr (NT == 1) asm volatile("" : "+v"(gq[0]), "+v"(gq[1]) : : "memory");
         else asm volatile("" : "+v"(gq[0]), "+v"(gq[1]), "+v"(gq[2]), "+v"(gq[3]) : : "memory");
       };
-      // ---- scoring of tile k; SI is k % PD as a type, so that the register set is a compile-time choice
-      auto score_compute = [&](int k, auto SI, unsigned (&pw)[4]) {
+      // ---- tile k out of its registers into its LDS slot (the tile that was there has been summed in the
+      //      step before); tile k+2 requested into the registers
+      auto park = [&](int k, auto SI) {
         u32x4 (&cur)[8] = ts[decltype(SI)::value];
-        f32x4 (&rot)[2] = tr[decltype(SI)::value];
-        // scores of this unit's heads for the lane's 8 rows (log2 domain)
-        float sc[8];
-        if constexpr (ROPE) {
-          float cc[4] = {rot[0][0], rot[0][2], rot[1][0], rot[1][2]};
-          float ss[4] = {rot[0][1], rot[0][3], rot[1][1], rot[1][3]};
+        char* sl = myslots + (k & (NS - 1)) * SLOT_PITCH + wpos;
 #pragma unroll
-          for (int j = 0; j < 8; ++j) {
-            float sj = 0.f;
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-              const unsigned kw = cur[j][c];
-              const bf16x2 kv = __builtin_bit_cast(bf16x2, kw);
-              float da = __builtin_amdgcn_fdot2_f32_bf16(kv, __builtin_bit_cast(bf16x2, qh[c]), 0.f, false);
-              da = __builtin_amdgcn_fdot2_f32_bf16(kv, __builtin_bit_cast(bf16x2, ql[c]), da, false);
-              float db = __builtin_amdgcn_fdot2_f32_bf16(kv, __builtin_bit_cast(bf16x2, ph[c]), 0.f, false);
-              db = __builtin_amdgcn_fdot2_f32_bf16(kv, __builtin_bit_cast(bf16x2, pl[c]), db, false);
-              sj = fmaf(cc[c], da, sj);
-              sj = fmaf(ss[c], db, sj);
-              if (j < 7) {                              // on to the next row's position
-                const float nc = fmaf(cc[c], w1c[c], -ss[c] * w1s[c]);
-                ss[c] = fmaf(ss[c], w1c[c], cc[c] * w1s[c]);
-                cc[c] = nc;
-              }
-            }
-            sc[j] = sj;
-          }
-        } else {
-#pragma unroll
-          for (int j = 0; j < 8; ++j) {
-            float d0 = 0.f, d1 = 0.f;
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-              const unsigned kw = cur[j][c];           // (a scalar copy: bit_cast of a vector element picks lane 0)
-              const bf16x2 kv = __builtin_bit_cast(bf16x2, kw);
-              d0 = __builtin_amdgcn_fdot2_f32_bf16(kv, __builtin_bit_cast(bf16x2, qh[c]), d0, false);
-              d1 = __builtin_amdgcn_fdot2_f32_bf16(kv, __builtin_bit_cast(bf16x2, ql[c]), d1, false);
-            }
-            sc[j] = d0 + d1;
-          }
-        }
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {                 // sum over the head's lanes, all inside a 16-lane row
-          if (lphp > 1) sc[j] = dpp_add<0xB1>(sc[j]);      // lane ^ 1   (a head spans lphp = 1, 2, 4, 8 or 16 lanes)
-          if (lphp > 2) sc[j] = dpp_add<0x4E>(sc[j]);      // lane ^ 2
-          if (lphp > 4) sc[j] = dpp_add<0x141>(sc[j]);     // other quad of the 8-lane half
-          if (lphp > 8) sc[j] = dpp_add<0x140>(sc[j]);     // other half of the row
-        }
-        // this tile's softmax numerators of the unit's heads, against the running maximum
+        for (int j = 0; j < 8; ++j) *reinterpret_cast<u32x4*>(sl + j * ROW_PITCH) = cur[j];
+      };
+      auto request = [&](int k, auto SI) { load_tile(ts[decltype(SI)::value], tr[decltype(SI)::value], k); };
+      // ---- softmax numerators of the unit's heads from the 8 scores of a lane (row of score jj given by
+      //      row_of), against the head's running maximum
+      auto numerators = [&](int k, float (&sc)[8], unsigned (&pw)[4], auto&& row_of) {
         const int st = sg.t0 + k * sg.stride;
         if ((st + 1) * TILE_ROWS > len) {             // last, partial tile: rows past the end weigh nothing
-          const int row0 = st * TILE_ROWS + rg * 8;
 #pragma unroll
-          for (int j = 0; j < 8; ++j) sc[j] = (row0 + j < len) ? sc[j] : NEG_INF;
+          for (int j = 0; j < 8; ++j) sc[j] = (st * TILE_ROWS + row_of(j) < len) ? sc[j] : NEG_INF;
         }
         float tmax = fmaxf(fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3])), fmaxf(fmaxf(sc[4], sc[5]), fmaxf(sc[6], sc[7])));
         tmax = max_over_row_groups(tmax);
@@ -812,37 +794,116 @@ __global__ __launch_bounds__(FUSED_WAVES * 64) void fused_stream_kernel(const Fu
           pw[i] = __builtin_bit_cast(unsigned, v);
         }
       };
-      // ---- rest of tile k's step: park, publish, request tile k+2 into the registers that become free
-      auto finish_tile = [&](int k, auto SI, const unsigned (&pw)[4]) {
+      // ---- scores of tile k on MFMA, from its LDS slot: S[row][n] = sum_c K[row][c] q_n[c], two M tiles of
+      //      16 rows, four k-steps of 32 columns.  A lane ends up with rows mt*16 + rg*4 + r of column idx.
+      auto score_mfma = [&](int k, unsigned (&pw)[4]) {
+        const char* sl = myslots + (k & (NS - 1)) * SLOT_PITCH + spos;
+        f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+          const bf16x8 a0 = *reinterpret_cast<const bf16x8*>(sl + ks * 64);
+          const bf16x8 a1 = *reinterpret_cast<const bf16x8*>(sl + ks * 64 + 16 * ROW_PITCH);
+          s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, bq[ks], s0, 0, 0, 0);
+          s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, bq[ks], s1, 0, 0, 0);
+        }
+        float sc[8];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {                 // query hi + lo: neighbour columns
+          sc[r] = dpp_add<0xB1>(s0[r]);
+          sc[4 + r] = dpp_add<0xB1>(s1[r]);
+        }
+        numerators(k, sc, pw, [&](int jj) { return (jj >> 2) * 16 + rg * 4 + (jj & 3); });
+      };
+      // ---- scores of tile k with rotary keys, on the vector ALU from the tile's registers; a lane ends up
+      //      with rows rg*8 + j of its head
+      auto score_rotary = [&](int k, auto SI, unsigned (&pw)[4]) {
         u32x4 (&cur)[8] = ts[decltype(SI)::value];
         f32x4 (&rot)[2] = tr[decltype(SI)::value];
-        // park the tile for this wave's own weighted sum two steps later (slot k % NS: the tile that was
-        // there has just been taken out)
+        float sc[8];
+        float cc[4] = {rot[0][0], rot[0][2], rot[1][0], rot[1][2]};
+        float ss[4] = {rot[0][1], rot[0][3], rot[1][1], rot[1][3]};
 #pragma unroll
-        for (int j = 0; j < 8; ++j) myslots[(k & (NS - 1)) * 512 + j * 64 + lane] = cur[j];
-        // publish: {tag, running max, p0 p1, p2 p3} and {tag, 0, p4 p5, p6 p7} per row group
+        for (int j = 0; j < 8; ++j) {
+          float sj = 0.f;
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            const unsigned kw = cur[j][c];             // (a scalar copy: bit_cast of a vector element picks lane 0)
+            const bf16x2 kv = __builtin_bit_cast(bf16x2, kw);
+            float da = __builtin_amdgcn_fdot2_f32_bf16(kv, __builtin_bit_cast(bf16x2, qh[c]), 0.f, false);
+            da = __builtin_amdgcn_fdot2_f32_bf16(kv, __builtin_bit_cast(bf16x2, ql[c]), da, false);
+            float db = __builtin_amdgcn_fdot2_f32_bf16(kv, __builtin_bit_cast(bf16x2, ph[c]), 0.f, false);
+            db = __builtin_amdgcn_fdot2_f32_bf16(kv, __builtin_bit_cast(bf16x2, pl[c]), db, false);
+            sj = fmaf(cc[c], da, sj);
+            sj = fmaf(ss[c], db, sj);
+            if (j < 7) {                              // on to the next row's position
+              const float nc = fmaf(cc[c], w1c[c], -ss[c] * w1s[c]);
+              ss[c] = fmaf(ss[c], w1c[c], cc[c] * w1s[c]);
+              cc[c] = nc;
+            }
+          }
+          sc[j] = sj;
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {                 // sum over the head's lanes, all inside a 16-lane row
+          if (lphp > 1) sc[j] = dpp_add<0xB1>(sc[j]);      // lane ^ 1   (a head spans lphp = 1, 2, 4, 8 or 16 lanes)
+          if (lphp > 2) sc[j] = dpp_add<0x4E>(sc[j]);      // lane ^ 2
+          if (lphp > 4) sc[j] = dpp_add<0x141>(sc[j]);     // other quad of the 8-lane half
+          if (lphp > 8) sc[j] = dpp_add<0x140>(sc[j]);     // other half of the row
+        }
+        numerators(k, sc, pw, [&](int jj) { return rg * 8 + jj; });
+      };
+      // ---- publish tile k's words: {tag, running max, p0 p1, p2 p3} and {tag, 0, p4 p5, p6 p7} per row group
+      auto publish = [&](int k, const unsigned (&pw)[4]) {
         const unsigned itk = sg.it0 + (unsigned)k + 1u;
         const unsigned tag = a.tag_base + itk;
         u32x4* ring = team_ring + (size_t)(itk & (EXCH_SLOTS - 1)) * (HP * 8);
-        if (pub_lane) {
-          st_exch(ring + (myhead * 4 + rg), u32x4{tag, __float_as_uint(mrun), pw[0], pw[1]}, xl);
-          st_exch(ring + ((HP + myhead) * 4 + rg), u32x4{tag, 0u, pw[2], pw[3]}, xl);
+        const int head = ROPE ? myhead : mhead;
+        if (ROPE ? pub_lane : mpub_lane) {
+          st_exch(ring + (head * 4 + rg), u32x4{tag, __float_as_uint(mrun), pw[0], pw[1]}, xl);
+          st_exch(ring + ((HP + head) * 4 + rg), u32x4{tag, 0u, pw[2], pw[3]}, xl);
         }
-        load_tile(cur, rot, k + PD);
       };
-      // ---- weighted sum of tile k, first part (needs no words): the tile out of its slot, as A operands
-      auto sum_prep = [&](int k, u32x4 (&am)[8]) {
-        u32x4 kt[8];
+      // ---- the scoring half of a step: tile k parked, its numerators published
+      constexpr int LOADS_PER_TILE = ROPE ? 10 : 8;
+      auto score_tile = [&](int k, auto SI) {
+        unsigned pw[4];
+        if constexpr (ROPE) {
+          score_rotary(k, SI, pw);
+          park(k, SI);
+        } else {
+          park(k, SI);
+          score_mfma(k, pw);
+        }
+        publish(k, pw);
+      };
+      // ---- weighted sum of tile k with the words gathered for it.  (k-slot jj of the operands is the row
+      //      the numerators' jj stands for: rg*8 + jj with rotary keys, (jj / 4) * 16 + kg * 4 + jj % 4 otherwise.)
+      //      HALF: the tile comes out of its slot in two halves of 64 columns (the first four and the last
+      //      four columns of every lane), which keeps fewer registers live.
+      auto tile_half = [&](int k, auto HALF, u32x4 (&am)[4]) {
+        constexpr int hf = decltype(HALF)::value;
+        const char* sl = myslots + (k & (NS - 1)) * SLOT_PITCH + (ROPE ? wpos : ppos) + hf * 8;
+        unsigned lo[8], hi[8];                        // columns 4 hf + {0, 1} and 4 hf + {2, 3} of the lane's 8 rows
 #pragma unroll
-        for (int j = 0; j < 8; ++j) kt[j] = myslots[(k & (NS - 1)) * 512 + j * 64 + lane];
-        transpose8x8(kt, am);
+        for (int jj = 0; jj < 8; ++jj) {
+          const unsigned off = ROPE ? jj * ROW_PITCH : ((jj >> 2) * 16 + (jj & 3)) * ROW_PITCH;
+          const auto v = *reinterpret_cast<const __attribute__((ext_vector_type(2))) unsigned*>(sl + off);
+          lo[jj] = v[0];
+          hi[jj] = v[1];
+        }
+#pragma unroll
+        for (int jp = 0; jp < 4; ++jp) {                // (the 8 x 4 half of transpose8x8)
+          am[0][jp] = __builtin_amdgcn_perm(lo[2 * jp + 1], lo[2 * jp], 0x05040100u);
+          am[1][jp] = __builtin_amdgcn_perm(lo[2 * jp + 1], lo[2 * jp], 0x07060302u);
+          am[2][jp] = __builtin_amdgcn_perm(hi[2 * jp + 1], hi[2 * jp], 0x05040100u);
+          am[3][jp] = __builtin_amdgcn_perm(hi[2 * jp + 1], hi[2 * jp], 0x07060302u);
+        }
       };
-      // ---- second part, with the words gathered for it (the gather's loads are done)
-      auto sum_finish = [&](int k, const u32x4 (&am)[8]) {
+      auto sum_finish = [&](int k, u32x4 (&am)[4]) {    // am: the first half, already out of the slot
         const unsigned tag = a.tag_base + sg.it0 + (unsigned)k + 1u;
         pin_gq();
         // every word of tile k must carry its tag; gather again while any is missing
-        int spins = 0;
+        unsigned long long since = ~0ull;
         for (;;) {
           unsigned bad = 0;
 #pragma unroll
@@ -851,7 +912,7 @@ __global__ __launch_bounds__(FUSED_WAVES * 64) void fused_stream_kernel(const Fu
             bad |= (heads_full || (t * 16 + n) < a.H) ? bt : 0u;
           }
           if (__all(bad == 0)) break;
-          if (dead || ++spins > a.spin_limit) { give_up(); break; }
+          if (dead || out_of_time(since)) { give_up(); break; }
           __builtin_amdgcn_s_sleep(8);
           gather(k);
           asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -878,32 +939,69 @@ __global__ __launch_bounds__(FUSED_WAVES * 64) void fused_stream_kernel(const Fu
 #pragma unroll
         for (int t = 0; t < NT; ++t) accl[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pb[t], accl[t], 0, 0, 0);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
+        for (int i = 0; i < 4; ++i) {
           const bf16x8 av = __builtin_bit_cast(bf16x8, am[i]);
 #pragma unroll
           for (int t = 0; t < NT; ++t)
             acc[i][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, pb[t], acc[i][t], 0, 0, 0);
         }
+        __builtin_amdgcn_sched_barrier(0);            // (the second half's registers only after the first half's are dead)
+        tile_half(k, std::integral_constant<int, 1>{}, am);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const bf16x8 av = __builtin_bit_cast(bf16x8, am[i]);
+#pragma unroll
+          for (int t = 0; t < NT; ++t)
+            acc[4 + i][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, pb[t], acc[4 + i][t], 0, 0, 0);
+        }
       };
-      // One step (k >= 2): the words of tile k-2, published by every workgroup of the group more than a
-      // step ago, travel while tile k is scored; nothing younger than that gather is in flight when it
-      // is waited for, so the wait (and a repeat, should a word be missing) costs one trip to the L2.
-      auto sum_tile = [&](int k) {
-        u32x4 am[8];
-        sum_prep(k, am);
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        sum_finish(k, am);
-      };
+      // One step (k >= 1).  Tile k is scored and published first; only then are the words of tile k-1
+      // requested (every workgroup of the group published them a scoring time ago), and behind them
+      // tile k+2 (LOADS_PER_TILE loads, the only vector-memory operations younger than the gather when it
+      // is waited for).  The tile comes out of its slot while the words travel.
       auto step = [&](int k, auto SI) {
-        unsigned pw[4];
-        gather(k - 2);
-        score_compute(k, SI, pw);
-        sum_tile(k - 2);
-        finish_tile(k, SI, pw);
+        u32x4 am[4];
+        score_tile(k, SI);
+        gather(k - 1);
+        request(k + PD, SI);
+        tile_half(k - 1, std::integral_constant<int, 0>{}, am);
+        if constexpr (ROPE) asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        static_assert(LOADS_PER_TILE == (ROPE ? 10 : 8), "the wait above counts the loads of one tile");
+        sum_finish(k - 1, am);
       };
 
+      f32x4 qx[4][2];                                 // the query columns behind bq, as loaded
+      bool qlive[4];
+      if constexpr (!ROPE) {
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+          const int C = ks * 4 + rg, hq = C / lphp, lq = C % lphp;
+          qlive[ks] = lq < a.lph && hq < a.hpu && u * a.hpu + hq < a.H && (idx >> 1) == hq;
+          const f32x4* src = reinterpret_cast<const f32x4*>(a.q + (size_t)sg.b * a.d + (qlive[ks] ? (u * a.hpu + hq) * a.d_k + lq * 8 : 0));
+          qx[ks][0] = src[0];
+          qx[ks][1] = src[1];
+        }
+      }
 #pragma unroll
       for (int k = 0; k < PD; ++k) load_tile(ts[k], tr[k], k);
+      // B operands of the score MFMA: k-step ks covers chunks ks*4 .. ks*4+3 of the unit; this lane holds
+      // chunk ks*4 + rg of column n = idx: the head's query (pre-scaled, bf16 hi or lo) where the chunk
+      // belongs to that head, zero elsewhere.  (Requested ahead of the first tiles, converted behind
+      // their requests: the wait for it then overlaps theirs.)
+      if constexpr (!ROPE) {
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+          const f32x4 x0 = qx[ks][0], x1 = qx[ks][1];
+          const bool live = qlive[ks];
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            const float f = live ? (i < 4 ? x0[i] : x1[i - 4]) * a.qscale : 0.f;
+            const __bf16 h = (__bf16)f;
+            bq[ks][i] = (idx & 1) ? (__bf16)(f - (float)h) : h;
+          }
+        }
+      }
       // the query, pre-scaled (log2 domain), split into bf16 hi + lo pairs so that the dot products run
       // on v_dot2c_f32_bf16 without losing the fp32 query
 #pragma unroll
@@ -927,56 +1025,41 @@ __global__ __launch_bounds__(FUSED_WAVES * 64) void fused_stream_kernel(const Fu
       {
         using S0 = std::integral_constant<int, 0>;
         using S1 = std::integral_constant<int, 1>;
-        unsigned pw[4];
-        if (ntl > 0) { score_compute(0, S0{}, pw); finish_tile(0, S0{}, pw); }
-        if (ntl > 1) { score_compute(1, S1{}, pw); finish_tile(1, S1{}, pw); }
+        if (ntl > 0) { score_tile(0, S0{}); request(PD, S0{}); }
         // Whole rounds of PD steps without a condition between them (a step that may be skipped
         // inside the loop would make the compiler's waits for the tile registers conservative).
-        int k = 2;
+        int k = 1;
         for (; k + PD <= ntl; k += PD) {
-          step(k, S0{});
-          step(k + 1, S1{});
+          step(k, S1{});
+          step(k + 1, S0{});
         }
-        if (k < ntl) step(k, S0{});
-        // the last two tiles: nothing left to score while their words travel
-        for (int kk = max(ntl - 2, 0); kk < ntl; ++kk) {
-          gather(kk);
-          sum_tile(kk);
+        if (k < ntl) step(k, S1{});
+        // the last tile: nothing left to score while its words travel
+        if (ntl > 0) {
+          u32x4 am[4];
+          gather(ntl - 1);
+          tile_half(ntl - 1, std::integral_constant<int, 0>{}, am);
+          asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+          sum_finish(ntl - 1, am);
         }
       }
 
       // ---- end of this sequence's share ---------------------------------------------------------------
       if (by_seq) {
-        // the whole share was this wave's: transpose through the wave's part of sbuf
-        // (TRANSPOSE_HEADS heads per pass, no other wave involved) and write the share's partial
-        float* mine = sbuf + (size_t)p * TRANSPOSE_HEADS * 129;
+        // the whole share was this wave's: its partial goes out straight from the accumulators (a lane
+        // holds 8 consecutive columns of a head per accumulator row: two 16-byte stores)
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
-#pragma unroll 1
-          for (int hq = 0; hq < 16 / TRANSPOSE_HEADS; ++hq) {
-            const int n0 = hq * TRANSPOSE_HEADS;
-            if (n >= n0 && n < n0 + TRANSPOSE_HEADS) {
-#pragma unroll
-              for (int r = 0; r < 4; ++r) {
-                if (ocol[r] < 0) continue;
-#pragma unroll
-                for (int i = 0; i < 8; ++i) mine[(n - n0) * 129 + ocol[r] + i] = acc[i][t][r];
-              }
-            }
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-#pragma unroll
-            for (int hl = 0; hl < TRANSPOSE_HEADS; ++hl) {
-              const int h = t * 16 + n0 + hl;
-              if (h >= a.H) break;
-#pragma unroll
-              for (int cc = 0; cc < 2; ++cc) {
-                const int col = lane + 64 * cc;
-                if (col < uwc) st_result(a.Cpart + ((size_t)sg.pid * a.H + h) * a.d + ucol0 + col, mine[hl * 129 + col], fuse);
-              }
-            }
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-          }
           const int h = t * 16 + n;
+          if (h < a.H) {
+            float* dst = a.Cpart + ((size_t)sg.pid * a.H + h) * a.d + ucol0;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              if (ocol[r] < 0) continue;
+              st_result4(dst + ocol[r], f32x4{acc[0][t][r], acc[1][t][r], acc[2][t][r], acc[3][t][r]}, fuse);
+              st_result4(dst + ocol[r] + 4, f32x4{acc[4][t][r], acc[5][t][r], acc[6][t][r], acc[7][t][r]}, fuse);
+            }
+          }
           if (u == 0 && kg == 0 && h < a.H) {
             st_result(a.mpart + (size_t)sg.pid * a.H + h, m[t], fuse);
             st_result(a.lpart + (size_t)sg.pid * a.H + h, accl[t][0], fuse);
@@ -993,8 +1076,7 @@ __global__ __launch_bounds__(FUSED_WAVES * 64) void fused_stream_kernel(const Fu
       }
       __syncthreads();
       {
-        // accumulators -> mbuf[wave][head][col] (row pitch 129 floats), in MFMA layout, scaled to
-        // the maximum over the waves
+        // accumulators -> mbuf[wave][head][col], in MFMA layout, scaled to the maximum over the waves
         float wsc[NT];
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
@@ -1004,14 +1086,16 @@ __global__ __launch_bounds__(FUSED_WAVES * 64) void fused_stream_kernel(const Fu
           wsc[t] = (m[t] == NEG_INF) ? 0.f : exp2f(m[t] - mall);
           if (kg == 0) larr[p][t][n] = accl[t][0] * wsc[t];   // every accumulator row holds the same sum
         }
-        float* mine = mbuf + (size_t)p * HP * 129 + n * 129;
+        float* mine = mbuf + (size_t)p * HP * MERGE_PITCH + n * MERGE_PITCH;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           if (ocol[r] < 0) continue;
 #pragma unroll
-          for (int t = 0; t < NT; ++t)
-#pragma unroll
-            for (int i = 0; i < 8; ++i) mine[t * 16 * 129 + ocol[r] + i] = acc[i][t][r] * wsc[t];
+          for (int t = 0; t < NT; ++t) {
+            f32x4* dst = reinterpret_cast<f32x4*>(mine + t * 16 * MERGE_PITCH + ocol[r]);
+            dst[0] = f32x4{acc[0][t][r], acc[1][t][r], acc[2][t][r], acc[3][t][r]} * wsc[t];
+            dst[1] = f32x4{acc[4][t][r], acc[5][t][r], acc[6][t][r], acc[7][t][r]} * wsc[t];
+          }
         }
       }
       __syncthreads();
@@ -1033,13 +1117,13 @@ __global__ __launch_bounds__(FUSED_WAVES * 64) void fused_stream_kernel(const Fu
   project_work<1, true, false>(a.proj, wg / a.proj.csw, wg % a.proj.csw, 0, prefix, psm, red, [&]() {
     // every workgroup's partials must be out: all arrival flags carry this launch's id
     if (wu == 0) {
-      int spins = 0;
+      unsigned long long since = ~0ull;
       for (;;) {
         bool ok = true;
         for (int i = lane; i < (int)gridDim.x; i += 64)
           ok = ok && (__hip_atomic_load(a.flags + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == a.launch_id);
         if (__all(ok)) break;
-        if (dead || ++spins > a.spin_limit) { give_up(); break; }
+        if (dead || out_of_time(since)) { give_up(); break; }
         __builtin_amdgcn_s_sleep(4);
       }
     }
@@ -1062,7 +1146,7 @@ __global__ __launch_bounds__(512) void xcc_probe_kernel(unsigned* out) {
 bool fused_geometry(int B, int H, int T, int d, FusedGeom* g) {
   if (H < 1 || d % H != 0) return false;
   const int d_k = d / H;
-  if (d_k % 8 != 0 || d_k > 128 || H > 32 || B > FUSED_MAX_B) return false;   // H > 32 spills registers
+  if (d_k % 8 != 0 || d_k < 16 || d_k > 128 || H > 32 || B > FUSED_MAX_B) return false;   // (16 score columns hold 8 heads of a unit, hi + lo)
   g->lph = d_k / 8;
   int lphp = 1;
   while (lphp < g->lph) lphp <<= 1;
@@ -1087,28 +1171,43 @@ bool fused_geometry(int B, int H, int T, int d, FusedGeom* g) {
   return true;
 }
 
-// True when workgroups i and j of a 256-workgroup launch share an XCD whenever i % 8 == j % 8
-// (checked once per device with a probe launch; the answer is cached).
-bool xcd_round_robin(int device) {
-  static int cached[64];                       // 0 unknown, 1 yes, 2 no
-  if (device < 0 || device >= 64) return false;
-  if (cached[device]) return cached[device] == 1;
-  unsigned* d = nullptr;
+// True when workgroups i and j of a 256-workgroup launch share an XCD whenever i % 8 == j % 8: a probe
+// launch on `st` that records each workgroup's XCD into `dev_buf` (device memory, 256 unsigned), read
+// back with a blocking copy.  The caller caches the answer per device.
+bool probe_xcd_round_robin(unsigned* dev_buf, hipStream_t st) {
   unsigned h[256];
-  bool ok = hipMalloc(&d, sizeof(h)) == hipSuccess;
-  if (ok) {
-    hipLaunchKernelGGL(xcc_probe_kernel, dim3(256), dim3(512), 0, 0, d);
-    ok = hipMemcpy(h, d, sizeof(h), hipMemcpyDeviceToHost) == hipSuccess;
-    (void)hipFree(d);
-  }
+  hipLaunchKernelGGL(xcc_probe_kernel, dim3(256), dim3(512), 0, st, dev_buf);
+  bool ok = hipMemcpyAsync(h, dev_buf, sizeof(h), hipMemcpyDeviceToHost, st) == hipSuccess &&
+            hipStreamSynchronize(st) == hipSuccess;
   if (ok)
     for (int i = 8; i < 256 && ok; ++i) ok = h[i] == h[i & 7];
   if (ok)
     for (int i = 1; i < 8 && ok; ++i)
       for (int j = 0; j < i; ++j) ok = ok && h[i] != h[j];
   (void)hipGetLastError();
-  cached[device] = ok ? 1 : 2;
   return ok;
+}
+
+// Workgroups of the stream kernel one compute unit can hold at once (0 on error): the launch is only
+// safe when all of its workgroups are resident together.
+int fused_blocks_per_cu(const FusedGeom& g, bool rope) {
+  int n = 0;
+  auto ask = [&](auto nt, auto rp, auto lp) {
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, fused_stream_kernel<decltype(nt)::value, decltype(rp)::value, decltype(lp)::value>,
+                                                     g.NP * 64, 0) != hipSuccess) { n = 0; (void)hipGetLastError(); }
+  };
+  auto with_lphp = [&](auto nt, auto rp) {
+    if (g.lphp == 16) ask(nt, rp, std::integral_constant<int, 16>{});
+    else if (g.lphp == 8) ask(nt, rp, std::integral_constant<int, 8>{});
+    else ask(nt, rp, std::integral_constant<int, 0>{});
+  };
+  auto with_rope = [&](auto nt) {
+    if (rope) with_lphp(nt, std::true_type{});
+    else with_lphp(nt, std::false_type{});
+  };
+  if (g.NT == 1) with_rope(std::integral_constant<int, 1>{});
+  else with_rope(std::integral_constant<int, 2>{});
+  return n;
 }
 
 // By-sequence partition: how many equal shares to cut every sequence into so that the shares fill

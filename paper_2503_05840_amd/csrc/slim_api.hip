@@ -31,7 +31,9 @@ struct Plan {
   size_t total = 0;
 };
 
-constexpr int CTRL_INTS = 4096;   // arrival counters + the error word (last int)
+// Control block at the start of every workspace: arrival counters, arrival flags, and in its last two
+// ints the id of the latest stream-kernel launch and the error word (= that id when a wait ran out).
+constexpr int CTRL_INTS = 4096;
 
 int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
 
@@ -43,6 +45,7 @@ Plan make_plan(int B, int H, int T, int width, int e) {
   const long per_split_v = (long)B * ((H + 3) / 4);
   p.nsplit_v = clampi((int)((1024 + per_split_v - 1) / per_split_v), 1, clampi((T + 127) / 128, 1, 256));
   size_t o = 0;
+  p.off_ctrl = o;    o += up(sizeof(int) * CTRL_INTS);
   p.fused_ok = (width == e) && fused_geometry(B, H, T, width, &p.geom);
   p.nsplit_x = xcache_splits(B, H, T, width);
   size_t nparts = (size_t)B * (p.nsplit > p.nsplit_x ? p.nsplit : p.nsplit_x);
@@ -64,9 +67,46 @@ Plan make_plan(int B, int H, int T, int width, int e) {
   p.off_vl = o;     o += up(sizeof(float) * (size_t)B * p.nsplit_v * H);
   if (p.fused_ok) { p.off_exch = o; o += up(fused_exch_bytes(p.geom)); }
   p.off_outpart = o; o += up(sizeof(float) * (size_t)(p.csw > p.csw_f ? p.csw : p.csw_f) * B * e);
-  p.off_ctrl = o;    o += up(sizeof(int) * CTRL_INTS);
   p.total = o;
   return p;
+}
+
+// A scratch array per device, part of the loaded code object (set-up writes its probe result there, so
+// that it needs no allocation).  Host code never uses this name as an address: the address on each device comes
+// from hipGetSymbolAddress at set-up (device_state) and is what kernels, copies and queries are given.
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)64 << 20;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
+// Per-device set-up, done once (slim_init, else the first call that needs it) under a lock: the
+// address of the static scratch, the compute-unit count, whether workgroup i of a launch runs on XCD
+// i % 8 (a probe launch on the null stream and a blocking read-back, no allocation: it writes into
+// the static scratch), and the event used to order stream-kernel launches of different streams.
+struct DeviceState {
+  bool ready = false, xcd_round_robin = false;
+  int cus = 0;
+  void* static_scratch = nullptr;
+  hipEvent_t order_ev = nullptr;
+  hipStream_t last_stream = nullptr;
+  bool any_launch = false;
+  signed char blocks_per_cu[2][2][3] = {};    // [NT - 1][rope][lphp class]: 0 unknown, else 1 + blocks
+};
+DeviceState g_dev[64];
+std::mutex g_dev_mu;
+
+DeviceState* device_state() {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) { (void)hipGetLastError(); return nullptr; }
+  std::lock_guard<std::mutex> lk(g_dev_mu);
+  DeviceState& s = g_dev[dev];
+  if (s.ready) return &s;
+  void* ptr = nullptr;
+  if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) { (void)hipGetLastError(); return nullptr; }
+  s.static_scratch = ptr;
+  if (hipDeviceGetAttribute(&s.cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) { (void)hipGetLastError(); s.cus = 0; }
+  s.xcd_round_robin = s.cus >= 256 && probe_xcd_round_robin((unsigned*)ptr, nullptr);
+  if (hipEventCreateWithFlags(&s.order_ev, hipEventDisableTiming) != hipSuccess) { s.order_ev = nullptr; (void)hipGetLastError(); }
+  s.ready = true;
+  return &s;
 }
 
 // Library-owned scratch: one allocation per device, grown on demand, kept until exit.
@@ -100,22 +140,29 @@ bool misaligned(const void* p) { return (((uintptr_t)p) & 15) != 0; }
 // together: two such launches running side by side (different streams) could each hold half of the chip
 // and starve each other until their waits run out.  Launches that arrive on another stream than the
 // previous one are therefore ordered behind it with an event; on one stream this costs nothing.
-struct StreamOrder { hipStream_t last = nullptr; bool any = false; hipEvent_t ev = nullptr; };
-StreamOrder g_order[64];
-std::mutex g_order_mu;
-
-void order_after_previous_stream_kernel(hipStream_t st) {
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return;
-  std::lock_guard<std::mutex> lk(g_order_mu);
-  StreamOrder& o = g_order[dev];
-  if (o.any && o.last != st) {
-    if (!o.ev && hipEventCreateWithFlags(&o.ev, hipEventDisableTiming) != hipSuccess) { o.ev = nullptr; (void)hipGetLastError(); }
-    if (o.ev && hipEventRecord(o.ev, o.last) == hipSuccess) (void)hipStreamWaitEvent(st, o.ev, 0);
+void order_after_previous_stream_kernel(DeviceState& d, hipStream_t st) {
+  std::lock_guard<std::mutex> lk(g_dev_mu);
+  if (d.any_launch && d.last_stream != st && d.order_ev) {
+    if (hipEventRecord(d.order_ev, d.last_stream) == hipSuccess) (void)hipStreamWaitEvent(st, d.order_ev, 0);
     else (void)hipGetLastError();
   }
-  o.last = st;
-  o.any = true;
+  d.last_stream = st;
+  d.any_launch = true;
+}
+
+// All workgroups of a stream-kernel launch must be resident at once (they wait for each other): the
+// device must hold `grid` of them, by its own occupancy figure for this instantiation.
+bool stream_kernel_fits(DeviceState& d, const FusedGeom& g, bool rope) {
+  const int lc = g.lphp == 16 ? 0 : (g.lphp == 8 ? 1 : 2);
+  signed char& slot = d.blocks_per_cu[g.NT - 1][rope ? 1 : 0][lc];
+  {
+    std::lock_guard<std::mutex> lk(g_dev_mu);
+    if (slot == 0) {
+      const int n = fused_blocks_per_cu(g, rope);
+      slot = (signed char)(1 + (n > 100 ? 100 : (n < 0 ? 0 : n)));
+    }
+  }
+  return (long)(slot - 1) * d.cus >= g.grid;
 }
 
 int check_common(int B, int H, int T, int e, int d_k, int width, const slim_opts* o, int* dtype,
@@ -178,25 +225,19 @@ extern "C" const char* slim_strerror(int code) {
     case SLIM_ERR_ILLCOND: return "W_K ill-conditioned (rcond < 1e-12); W_KV written but unreliable";
     case SLIM_ERR_LAUNCH: return "HIP allocation or launch error";
     case SLIM_ERR_SEQLEN: return "sequence length outside [1, T]";
+    case SLIM_ERR_TIMEOUT: return "a wait between workgroups ran out in the latest stream-kernel launch on this workspace; its outputs are NaN";
     default: return "unknown slim status";
   }
 }
 
-// The stream kernel's workgroups wait for each other: all 256 must be resident at once, one per compute
-// unit.  A device (or partition) with fewer compute units takes the plain kernels.  Unknown (no device
-// visible, e.g. when only sizes are asked for on a build machine) counts as enough.
+// The stream kernel's launch geometry is laid out for 256 compute units in 8 XCDs; a device (or
+// partition) with fewer takes the plain kernels.  Unknown (no device visible, e.g. when only sizes are
+// asked for on a build machine) counts as enough.
 bool chip_holds_stream_kernel() {
-  static std::atomic<int> cached[64];                  // 0 unknown, 1 yes, 2 no
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) { (void)hipGetLastError(); return true; }
-  int c = cached[dev].load();
-  if (c == 0) {
-    int cus = 0;
-    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) { (void)hipGetLastError(); return true; }
-    c = cus >= 256 ? 1 : 2;
-    cached[dev].store(c);
-  }
-  return c == 1;
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return true; }
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) { (void)hipGetLastError(); return true; }
+  return cus >= 256;
 }
 
 // Which implementation runs for a K-cache decode of this shape.
@@ -236,8 +277,12 @@ extern "C" size_t slim_workspace_bytes_xcache(int B, int H, int T, int d_model, 
   return make_plan(B, H, T, d_model, H * d_k).total;
 }
 
-extern "C" int slim_decode(const void* q, const void* Kcache, const void* W_KV, void* out, int B,
-                           int H, int T, int d, const slim_opts* o) {
+namespace {
+
+// slim_decode and slim_decode_static: the same validation, plan and launches; `fixed_ws` (non-null for
+// the static scratch) replaces the workspace lookup.
+int decode_core(const void* q, const void* Kcache, const void* W_KV, void* out, int B, int H, int T, int d,
+                const slim_opts* o, char* fixed_ws, size_t fixed_ws_bytes) {
   if (!q || !Kcache || !W_KV || !out) return SLIM_ERR_ARG;
   if (H < 1 || d < 1 || d % H != 0) return SLIM_ERR_SHAPE;
   const int d_k = d / H;
@@ -248,8 +293,12 @@ extern "C" int slim_decode(const void* q, const void* Kcache, const void* W_KV, 
   if (rope && (d_k & 1)) return SLIM_ERR_SHAPE;
   if (rope && misaligned(rope)) return SLIM_ERR_ALIGN;
   const Plan p = make_plan(B, H, T, d, d);
-  char* ws;
-  if (int rc = get_workspace(o, p.total, &ws)) return rc;
+  char* ws = fixed_ws;
+  if (fixed_ws) {
+    if (p.total > fixed_ws_bytes) return SLIM_ERR_WORKSPACE;
+  } else if (int rc = get_workspace(o, p.total, &ws)) {
+    return rc;
+  }
   hipStream_t st = o ? (hipStream_t)o->stream : nullptr;
   const int32_t* lens = o ? o->seq_lens : nullptr;
   const float scale = 1.0f / sqrtf((float)d_k);
@@ -261,7 +310,13 @@ extern "C" int slim_decode(const void* q, const void* Kcache, const void* W_KV, 
   const long kb = t_stride * d;
 
   StageTimer tm(o, st);
-  const int variant = pick_variant(o ? o->variant : SLIM_VARIANT_AUTO, B, H, T, d, dtype);
+  int variant = pick_variant(o ? o->variant : SLIM_VARIANT_AUTO, B, H, T, d, dtype);
+  DeviceState* dev = nullptr;
+  if (variant == SLIM_VARIANT_FUSED || variant == SLIM_VARIANT_FUSED_SPLIT) {
+    // the stream kernel needs this device's set-up, and all of its workgroups resident together
+    dev = device_state();
+    if (!dev || !stream_kernel_fits(*dev, p.geom, rope != nullptr)) variant = SLIM_VARIANT_GENERIC;
+  }
   if (variant == SLIM_VARIANT_FUSED || variant == SLIM_VARIANT_FUSED_SPLIT) {
     const FusedGeom& g = p.geom;
     int* ctrl = (int*)(ws + p.off_ctrl);
@@ -278,12 +333,10 @@ extern "C" int slim_decode(const void* q, const void* Kcache, const void* W_KV, 
     unsigned lid = g_launch.fetch_add(1);
     if (lid == 0) lid = g_launch.fetch_add(1);
     fa.launch_id = lid;
-    fa.spin_limit = 1 << 15;
-    {
-      int dev = 0;
-      (void)hipGetDevice(&dev);
-      fa.xcd_local = (g.gpx > 0 && xcd_round_robin(dev)) ? 1 : 0;
-    }
+    // every wait for another workgroup: 20 ms of real time (100 MHz ticks) unless the caller says otherwise
+    const long long budget_us = (o && o->wait_budget_us) ? (long long)o->wait_budget_us : 20000;
+    fa.wait_ticks = budget_us < 0 ? 0ull : (unsigned long long)budget_us * 100ull;
+    fa.xcd_local = (g.gpx > 0 && dev->xcd_round_robin) ? 1 : 0;
     fa.rope = rope;
     fa.Cpart = Cpart; fa.mpart = mpart; fa.lpart = lpart;
     fa.err = ctrl + CTRL_INTS - 1; fa.counters = ctrl; fa.ncounters = H * zb;
@@ -304,7 +357,7 @@ extern "C" int slim_decode(const void* q, const void* Kcache, const void* W_KV, 
       pa.crows = proj_rows_per_split(d, p.csw_f);
       fa.fuse = 1; fa.flags = (unsigned*)(ctrl + CTRL_INTS / 2); fa.proj = pa;
     }
-    order_after_previous_stream_kernel(st);
+    order_after_previous_stream_kernel(*dev, st);
     launch_fused_stream(g, fa, st);
     tm.mark();
     if (!one_launch) {
@@ -343,6 +396,40 @@ extern "C" int slim_decode(const void* q, const void* Kcache, const void* W_KV, 
   launch_project(dtype, Cn, W_KV, d, d, H, d_k, (float*)out, B, st);
   tm.mark();
   tm.finish();
+  return launch_status();
+}
+
+}  // namespace
+
+extern "C" int slim_decode(const void* q, const void* Kcache, const void* W_KV, void* out, int B,
+                           int H, int T, int d, const slim_opts* o) {
+  return decode_core(q, Kcache, W_KV, out, B, H, T, d, o, nullptr, 0);
+}
+
+extern "C" int slim_init(void) { return device_state() ? SLIM_OK : SLIM_ERR_LAUNCH; }
+
+extern "C" int slim_status(const void* workspace, void* stream) {
+  const char* ws = (const char*)workspace;
+  if (!workspace) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) { (void)hipGetLastError(); return SLIM_ERR_LAUNCH; }
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    ws = (const char*)g_scratch[dev].ptr;
+    if (!ws) return SLIM_OK;                          // nothing has run on the library's own scratch
+  }
+  int tail[2] = {0, 0};                               // {id of the latest stream-kernel launch, error word}
+  if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess ||
+      hipMemcpy(tail, ws + sizeof(int) * (CTRL_INTS - 2), sizeof(tail), hipMemcpyDeviceToHost) != hipSuccess) {
+    (void)hipGetLastError();
+    return SLIM_ERR_LAUNCH;
+  }
+  return (tail[0] != 0 && tail[1] == tail[0]) ? SLIM_ERR_TIMEOUT : SLIM_OK;
+}
+
+extern "C" int slim_read_probe(const void* buf, size_t bytes, void* stream) {
+  if (!buf || bytes < 16) return SLIM_ERR_ARG;
+  if (misaligned(buf)) return SLIM_ERR_ALIGN;
+  launch_read_probe(buf, bytes, (hipStream_t)stream);
   return launch_status();
 }
 

@@ -46,6 +46,8 @@ void launch_append(int dtype, const float* knew, const float* vnew, void* K, voi
                    const int32_t* seq_lens, int T, int d, int d_k, const float* rope, float* q, int rotate_k,
                    int B, hipStream_t st);
 void launch_zero_ints(int* p, int n, hipStream_t st);
+// Plain streaming read of `bytes` (measurement only).
+void launch_read_probe(const void* buf, size_t bytes, hipStream_t st);
 
 // Vanilla K+V decode: partial (m, l, acc) per (b, split, head) then a merge.
 void launch_vanilla(int dtype, const float* q, const void* K, const void* V, long bstride,
@@ -97,11 +99,11 @@ struct FusedArgs {
   float qscale;                       // log2(e) / sqrt(d_k): scores live in the log2 domain
   unsigned long long* exch;           // [NG][NP][EXCH_SLOTS][2][16*NT][4] 16-byte words {tag, max, 4 bf16 weights}
   unsigned tag_base, launch_id;
-  int spin_limit;
+  unsigned long long wait_ticks;      // budget of every wait for another workgroup, in ticks of the 100 MHz real-time counter
   float* Cpart;                       // [nparts][H][d]
   float* mpart;                       // [nparts][H]  running max, log2 domain
   float* lpart;                       // [nparts][H]
-  int* err;                           // set to launch_id when a wait timed out
+  int* err;                           // set to launch_id when a wait timed out; err[-1] receives launch_id at the start
   int* counters;                      // arrival counters of the projection, zeroed here
   int ncounters;
   int xcd_local;                      // 1: a group's workgroups share an XCD, the exchange stays in its L2
@@ -118,7 +120,8 @@ struct FusedArgs {
 bool fused_geometry(int B, int H, int T, int d, FusedGeom* g);
 int fused_by_sequence(const FusedGeom& g, int B, bool ragged);
 size_t fused_exch_bytes(const FusedGeom& g);
-bool xcd_round_robin(int device);
+bool probe_xcd_round_robin(unsigned* dev_buf, hipStream_t st);
+int fused_blocks_per_cu(const FusedGeom& g, bool rope);
 void launch_fused_stream(const FusedGeom& g, const FusedArgs& a, hipStream_t st);
 int proj_batch_tiles(int B, int rows, int e, int H);
 int proj_row_splits(int H, int rows, int e, int B);
