@@ -146,7 +146,8 @@ int slim_init(void);
  * query waits for `stream` (hipStream_t, null => the null stream), reads the word back and returns
  * SLIM_ERR_TIMEOUT or SLIM_OK.  The fast path needs the chip free of other kernels while it runs.
  *   workspace: the device scratch the call was given; NULL => the library-owned scratch of the
- *              current device. */
+ *              current device; SLIM_STATIC_SCRATCH => the scratch of slim_decode_static. */
+#define SLIM_STATIC_SCRATCH ((const void*)(uintptr_t)1)
 int slim_status(const void* workspace, void* stream);
 
 /* The implementation SLIM_VARIANT_AUTO resolves to for a K-cache decode of this shape
@@ -177,6 +178,23 @@ size_t slim_workspace_bytes_xcache(int B, int H, int T, int d_model, int d_k, in
  * folded into the X-cache scheme's query. */
 int slim_decode(const void* q, const void* Kcache, const void* W_KV, void* out,
                 int B, int H, int T, int d, const slim_opts* opts);
+
+/* slim_decode for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and same results as
+ * slim_decode, but all scratch lives in one array of SLIM_STATIC_SCRATCH_BYTES that is part of the
+ * library's code object (each GPU the library runs on holds it until the process ends), and the call
+ * itself makes no hipMalloc / hipFree or other allocating call (after slim_init on this device, or
+ * its own first call, nothing but kernel launches and an event record / wait).
+ *   - opts->workspace and opts->stage_ms must be null (SLIM_ERR_ARG otherwise).
+ *   - Shapes whose scratch plan exceeds the array (slim_workspace_bytes(B, H, T, d, dtype) >
+ *     slim_static_scratch_bytes()) are refused with SLIM_ERR_WORKSPACE before anything is launched.
+ *   - Every call on a GPU shares that GPU's array: calls that overlap on one GPU (different streams
+ *     or threads) race.  Nothing needs clearing between calls: the kernels zero their own counters
+ *     and tell fresh exchange words from stale ones by per-launch tags. */
+#define SLIM_STATIC_SCRATCH_BYTES (64u << 20)
+size_t slim_static_scratch_bytes(void);
+int slim_decode_static(const void* q, const void* Kcache, const void* W_KV, void* out,
+                       int B, int H, int T, int d, const slim_opts* opts);
 
 /* The same step the vanilla way (eq. 2 with a stored V-cache, Table 2 row "Vanilla"):
  * reads K and V, 2*T*d cache elements per sequence.  The same-GPU comparison kernel. */

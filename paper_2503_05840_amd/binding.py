@@ -22,7 +22,7 @@ DTYPES = {"f32": SLIM_F32, "bf16": SLIM_BF16}
 EXPORTS = ("slim_strerror", "slim_prepare_wkv", "slim_prepare_wkv_nonsquare", "slim_pack_weights", "slim_rope_table", "slim_workspace_bytes",
            "slim_workspace_bytes_xcache", "slim_workspace_bytes_block", "slim_attention_block", "vanilla_attention_block",
            "slim_variant_for", "slim_decode", "vanilla_kv_decode", "slim_decode_xcache", "slim_init", "slim_status",
-           "slim_read_probe")
+           "slim_read_probe", "slim_decode_static", "slim_static_scratch_bytes")
 VARIANT_NAMES = {1: "generic", 2: "fused_split", 3: "fused"}
 
 
@@ -99,6 +99,10 @@ def load():
     lib.slim_init.argtypes = []
     lib.slim_status.restype = ci
     lib.slim_status.argtypes = [vp, vp]
+    lib.slim_decode_static.restype = ci
+    lib.slim_decode_static.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, op]
+    lib.slim_static_scratch_bytes.restype = ctypes.c_size_t
+    lib.slim_static_scratch_bytes.argtypes = []
     lib.slim_read_probe.restype = ci
     lib.slim_read_probe.argtypes = [vp, ctypes.c_size_t, vp]
     _lib = lib
@@ -188,6 +192,7 @@ def to_device(a: np.ndarray):
 
 
 SLIM_ERR_TIMEOUT = -10
+STATIC_SCRATCH = 1          # slim_status: the scratch of slim_decode_static
 
 
 def slim_init():
@@ -198,7 +203,7 @@ def slim_init():
 
 def slim_status(workspace=None) -> int:
     """SLIM_OK or SLIM_ERR_TIMEOUT for the latest fast-path launch on `workspace` (a device tensor, None for
-    the library-owned scratch); waits for the current stream."""
+    the library-owned scratch, STATIC_SCRATCH for slim_decode_static's); waits for the current stream."""
     import torch
     ws = workspace if isinstance(workspace, int) or workspace is None else workspace.data_ptr()
     return int(load().slim_status(ws, torch.cuda.current_stream().cuda_stream))
@@ -254,6 +259,21 @@ def slim_decode(q, Kcache, W_KV, out, B, H, T, d, dtype="bf16", seq_lens=None, s
     if rc != SLIM_OK:
         raise SlimError(rc, "slim_decode")
     return out
+
+
+def slim_decode_static(q, Kcache, W_KV, out, B, H, T, d, dtype="bf16", seq_lens=None, seq_lens_host=None,
+                       t_stride=0, variant=VARIANT_AUTO, rope_table=None):
+    """slim_decode over the library's static device scratch: no allocation inside the call."""
+    o, keep = _opts(dtype, seq_lens, seq_lens_host, t_stride, None, variant, None, rope_table)
+    rc = load().slim_decode_static(_dev_ptr(q), _dev_ptr(Kcache), _dev_ptr(W_KV), _dev_ptr(out), B, H, T, d,
+                                   ctypes.byref(o))
+    if rc != SLIM_OK:
+        raise SlimError(rc, "slim_decode_static")
+    return out
+
+
+def slim_static_scratch_bytes() -> int:
+    return int(load().slim_static_scratch_bytes())
 
 
 def vanilla_kv_decode(q, Kcache, Vcache, out, B, H, T, d, dtype="bf16", seq_lens=None,

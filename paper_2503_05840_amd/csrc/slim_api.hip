@@ -71,10 +71,10 @@ Plan make_plan(int B, int H, int T, int width, int e) {
   return p;
 }
 
-// A scratch array per device, part of the loaded code object (set-up writes its probe result there, so
-// that it needs no allocation).  Host code never uses this name as an address: the address on each device comes
+// Scratch for callers that may not allocate (slim_decode_static): one array per device, part of the
+// loaded code object (set-up also writes its probe result there, so that it needs no allocation).  Host code never uses this name as an address: the address on each device comes
 // from hipGetSymbolAddress at set-up (device_state) and is what kernels, copies and queries are given.
-constexpr size_t STATIC_SCRATCH_BYTES = (size_t)64 << 20;
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)SLIM_STATIC_SCRATCH_BYTES;
 static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
 
 // Per-device set-up, done once (slim_init, else the first call that needs it) under a lock: the
@@ -408,9 +408,23 @@ extern "C" int slim_decode(const void* q, const void* Kcache, const void* W_KV, 
 
 extern "C" int slim_init(void) { return device_state() ? SLIM_OK : SLIM_ERR_LAUNCH; }
 
+extern "C" size_t slim_static_scratch_bytes(void) { return STATIC_SCRATCH_BYTES; }
+
+extern "C" int slim_decode_static(const void* q, const void* Kcache, const void* W_KV, void* out, int B,
+                                  int H, int T, int d, const slim_opts* o) {
+  if (o && (o->workspace || o->stage_ms)) return SLIM_ERR_ARG;     // brings its own scratch; timing events allocate
+  DeviceState* dev = device_state();
+  if (!dev) return SLIM_ERR_LAUNCH;
+  return decode_core(q, Kcache, W_KV, out, B, H, T, d, o, (char*)dev->static_scratch, STATIC_SCRATCH_BYTES);
+}
+
 extern "C" int slim_status(const void* workspace, void* stream) {
   const char* ws = (const char*)workspace;
-  if (!workspace) {
+  if (workspace == SLIM_STATIC_SCRATCH) {
+    DeviceState* dev = device_state();
+    if (!dev) return SLIM_ERR_LAUNCH;
+    ws = (const char*)dev->static_scratch;
+  } else if (!workspace) {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) { (void)hipGetLastError(); return SLIM_ERR_LAUNCH; }
     std::lock_guard<std::mutex> lk(g_scratch_mu);
