@@ -12,6 +12,8 @@
 //   dense_scores  : (q_i W_K,i^T) X^T for the X-cache scheme                (non-square section, Fig. 4)
 #include "slim_kernels.h"
 
+#include <type_traits>
+
 #include <math.h>
 
 namespace slim {
@@ -419,7 +421,7 @@ __global__ __launch_bounds__(256) void vanilla_kernel(
   const int e = H * d_k;
   const int cph = d_k / VEC;                   // vectors per head row
   const int len = seq_len_of(seq_lens, b, T);
-  const int ts = split_rows(T, nsplit);
+  const int ts = split_rows(len, nsplit);          // the splits are cut on the sequence's own length
   const int t0 = sp * ts;
   const int t1 = min(len, t0 + ts);
 
@@ -508,6 +510,148 @@ __global__ __launch_bounds__(256) void vanilla_kernel(
 #pragma unroll
         for (int j = 0; j < VEC; ++j) accp[pb * d_k + (p * 16 + idx) * VEC + j] = acc[p][j];
       }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// vanilla K+V decode, bf16, packed lanes: every lane of a wave carries live columns and a wave's
+// piece of a cache row is a whole number of 128-byte lines, whatever the head width:
+//   d_k = 128, 64, 32, 16, 8: a lane holds 8 columns (16 bytes); a head spans LPH = d_k / 8 lanes and
+//     16 / LPH neighbouring heads share a 16-lane group (256 bytes of the row), four rows per load;
+//   d_k = 96: a lane holds 6 columns (12 bytes), a head spans 16 lanes and two neighbouring heads
+//     make 32 lanes (384 bytes = three lines), two rows per load.
+// Each group of lanes that shares rows keeps its own running (reference, sum, accumulator) in the log2
+// domain (the reference moves only when the maximum has grown by more than 2^6, as in the slim kernels)
+// and the groups are merged at the end.  The context splits are cut on the sequence's own length.
+// ------------------------------------------------------------------------------------------------
+typedef unsigned vu3 __attribute__((ext_vector_type(3)));
+typedef unsigned vu4 __attribute__((ext_vector_type(4)));
+typedef __bf16 vbf2 __attribute__((ext_vector_type(2)));
+
+template <int CTRL>
+__device__ __forceinline__ float vdpp_add(float v) {
+  return v + __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+
+template <int CPL, int LPH>
+__global__ __launch_bounds__(256) void vanilla_packed_kernel(
+    const float* __restrict__ q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V, long bstride,
+    const int32_t* __restrict__ seq_lens, int T, int H, int d_k, int nsplit, float scale_log2,
+    float* __restrict__ accp, float* __restrict__ mpart, float* __restrict__ lpart) {
+  constexpr int HPW = (CPL == 6) ? 2 : 16 / LPH;      // heads of a wave
+  constexpr int LR = LPH * HPW;                       // lanes per cache row: 16 or 32
+  constexpr int RG = 64 / LR;                         // rows per load
+  constexpr int UNR = 16 / RG;                        // loads of K (and of V) in flight: 16 rows per wave and round
+  constexpr int NW = CPL / 2;                         // dwords per lane and row
+  constexpr float SLACK = 6.0f;
+  const int b = blockIdx.z, sp = blockIdx.y;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int h0 = (blockIdx.x * 4 + wave) * HPW;
+  if (h0 >= H) return;
+  const int lr = lane % LR, rg = lane / LR;
+  const int h = h0 + lr / LPH, li = lr % LPH;
+  const bool live = h < H;
+  const int e = H * d_k;
+  const int col = (live ? h : h0) * d_k + li * CPL;   // (heads past the end re-read the first head: weighted with a zero query)
+  const int len = seq_len_of(seq_lens, b, T);
+  const int ts = split_rows(len, nsplit);
+  const int t0 = sp * ts;
+  const int t1 = min(len, t0 + ts);
+
+  // the query of this lane's columns, pre-scaled, as bf16 hi + lo pairs for the packed dot product
+  unsigned qh[NW], ql[NW];
+#pragma unroll
+  for (int c = 0; c < NW; ++c) {
+    const float f0 = live ? q[(long)b * e + col + 2 * c] * scale_log2 : 0.f;
+    const float f1 = live ? q[(long)b * e + col + 2 * c + 1] * scale_log2 : 0.f;
+    const __bf16 a0 = (__bf16)f0, a1 = (__bf16)f1;
+    const vbf2 hi = {a0, a1};
+    const vbf2 lo = {(__bf16)(f0 - (float)a0), (__bf16)(f1 - (float)a1)};
+    qh[c] = __builtin_bit_cast(unsigned, hi);
+    ql[c] = __builtin_bit_cast(unsigned, lo);
+  }
+  float m = NEG_INF, l = 0.f;
+  float acc[CPL];
+#pragma unroll
+  for (int j = 0; j < CPL; ++j) acc[j] = 0.f;
+
+  const char* Kb = reinterpret_cast<const char*>(K + b * bstride + col);
+  const char* Vb = reinterpret_cast<const char*>(V + b * bstride + col);
+  const size_t pitch = (size_t)e * 2;
+  auto load = [&](const char* base, int t, unsigned (&r)[NW]) {
+    if constexpr (CPL == 8) {
+      const vu4 x = __builtin_nontemporal_load(reinterpret_cast<const vu4*>(base + (size_t)t * pitch));
+#pragma unroll
+      for (int c = 0; c < 4; ++c) r[c] = x[c];
+    } else {
+      typedef vu3 vu3_a4 __attribute__((aligned(4)));
+      const vu3 x = __builtin_nontemporal_load(reinterpret_cast<const vu3_a4*>(base + (size_t)t * pitch));
+#pragma unroll
+      for (int c = 0; c < 3; ++c) r[c] = x[c];
+    }
+  };
+
+  for (int tb = t0 + rg; tb < t1; tb += RG * UNR) {
+    unsigned kr[UNR][NW], vr[UNR][NW];
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+      const int t = min(tb + u * RG, t1 - 1);          // rows past the end re-read the last row; they get no weight
+      load(Kb, t, kr[u]);
+      load(Vb, t, vr[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+      float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+      for (int c = 0; c < NW; ++c) {
+        const unsigned kw = kr[u][c];
+        const vbf2 kv = __builtin_bit_cast(vbf2, kw);
+        s0 = __builtin_amdgcn_fdot2_f32_bf16(kv, __builtin_bit_cast(vbf2, qh[c]), s0, false);
+        s1 = __builtin_amdgcn_fdot2_f32_bf16(kv, __builtin_bit_cast(vbf2, ql[c]), s1, false);
+      }
+      float s = s0 + s1;
+      if (LPH > 1) s = vdpp_add<0xB1>(s);              // lane ^ 1
+      if (LPH > 2) s = vdpp_add<0x4E>(s);              // lane ^ 2
+      if (LPH > 4) s = vdpp_add<0x141>(s);             // other quad of the 8-lane half
+      if (LPH > 8) s = vdpp_add<0x140>(s);             // other half of the 16-lane row
+      const bool ok = (tb + u * RG) < t1;
+      const float mn = (ok && s > m + SLACK) ? s : m;
+      if (__any(mn != m)) {                            // the reference of some head moved: rescale (rare)
+        const float alpha = __builtin_amdgcn_exp2f(m - mn);   // 1 where it did not move, 0 the first time
+        l *= alpha;
+#pragma unroll
+        for (int j = 0; j < CPL; ++j) acc[j] *= alpha;
+        m = mn;
+      }
+      const float pw = ok ? __builtin_amdgcn_exp2f(s - m) : 0.f;
+      l += pw;
+#pragma unroll
+      for (int c = 0; c < NW; ++c) {
+        acc[2 * c] = fmaf(pw, __uint_as_float(vr[u][c] << 16), acc[2 * c]);
+        acc[2 * c + 1] = fmaf(pw, __uint_as_float(vr[u][c] & 0xffff0000u), acc[2 * c + 1]);
+      }
+    }
+  }
+  // merge the RG groups of lanes that walked different rows (lanes lr, lr + LR, ...)
+  float mall = m;
+  if (RG > 2) mall = fmaxf(mall, __shfl_xor(mall, 16));
+  mall = fmaxf(mall, __shfl_xor(mall, 32));
+  const float w = (m == NEG_INF) ? 0.f : __builtin_amdgcn_exp2f(m - mall);
+  l *= w;
+  if (RG > 2) l += __shfl_xor(l, 16);
+  l += __shfl_xor(l, 32);
+#pragma unroll
+  for (int j = 0; j < CPL; ++j) {
+    float a = acc[j] * w;
+    if (RG > 2) a += __shfl_xor(a, 16);
+    a += __shfl_xor(a, 32);
+    acc[j] = a;
+  }
+  if (rg == 0 && live) {
+    const long pb = ((long)b * nsplit + sp) * H + h;
+    if (li == 0) { mpart[pb] = mall * 0.6931471805599453f; lpart[pb] = l; }   // (the merge kernel works with natural logarithms)
+#pragma unroll
+    for (int j = 0; j < CPL; ++j) accp[pb * d_k + li * CPL + j] = acc[j];
   }
 }
 
@@ -634,12 +778,37 @@ void launch_zero_ints(int* p, int n, hipStream_t st) {
   hipLaunchKernelGGL(zero_ints_kernel, dim3((n + 255) / 256), dim3(256), 0, st, p, n);
 }
 
+// heads a wave of the packed bf16 kernel covers (0: this head width takes the plain kernel)
+int vanilla_heads_per_wave(int dtype, int d_k) {
+  if (dtype != DT_BF16) return 0;
+  if (d_k == 96) return 2;
+  if (d_k == 8 || d_k == 16 || d_k == 32 || d_k == 64 || d_k == 128) return 128 / d_k;
+  return 0;
+}
+
 void launch_vanilla(int dtype, const float* q, const void* K, const void* V, long bstride,
                     const int32_t* seq_lens, int T, int H, int d_k, int nsplit, float* acc,
                     float* mpart, float* lpart, float* out, int B, hipStream_t st) {
-  dim3 grid((H + 3) / 4, nsplit, B);
   const float scale = 1.0f / sqrtf((float)d_k);
   const int cph = d_k / vec_elems(dtype);
+  if (const int hpw = vanilla_heads_per_wave(dtype, d_k)) {
+    dim3 grid(((H + hpw - 1) / hpw + 3) / 4, nsplit, B);
+    const float sl2 = scale * 1.4426950408889634f;
+    auto go = [&](auto cpl, auto lph) {
+      hipLaunchKernelGGL((vanilla_packed_kernel<decltype(cpl)::value, decltype(lph)::value>), grid, dim3(256), 0, st, q,
+                         (const uint16_t*)K, (const uint16_t*)V, bstride, seq_lens, T, H, d_k, nsplit, sl2, acc, mpart, lpart);
+    };
+    using C8 = std::integral_constant<int, 8>;
+    switch (d_k) {
+      case 96: go(std::integral_constant<int, 6>{}, std::integral_constant<int, 16>{}); break;
+      case 128: go(C8{}, std::integral_constant<int, 16>{}); break;
+      case 64: go(C8{}, std::integral_constant<int, 8>{}); break;
+      case 32: go(C8{}, std::integral_constant<int, 4>{}); break;
+      case 16: go(C8{}, std::integral_constant<int, 2>{}); break;
+      default: go(C8{}, std::integral_constant<int, 1>{}); break;
+    }
+  } else {
+  dim3 grid((H + 3) / 4, nsplit, B);
   if (dtype == DT_BF16) {
     if (cph <= 16)
       hipLaunchKernelGGL((vanilla_kernel<BF16, 1>), grid, dim3(256), 0, st, q, (const uint16_t*)K,
@@ -654,6 +823,7 @@ void launch_vanilla(int dtype, const float* q, const void* K, const void* V, lon
     else
       hipLaunchKernelGGL((vanilla_kernel<F32, 2>), grid, dim3(256), 0, st, q, (const float*)K,
                          (const float*)V, bstride, seq_lens, T, H, d_k, nsplit, scale, acc, mpart, lpart);
+  }
   }
   dim3 g2(H, B);
   hipLaunchKernelGGL(vanilla_combine_kernel, g2, dim3(256), 0, st, acc, mpart, lpart, nsplit, H, d_k, out);

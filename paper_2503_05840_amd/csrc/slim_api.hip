@@ -42,8 +42,11 @@ Plan make_plan(int B, int H, int T, int width, int e) {
   const int ncolblk = (width + 511) / 512, nhb = (H + 31) / 32;
   const long per_split = (long)B * ncolblk * nhb;
   p.nsplit = clampi((int)((1024 + per_split - 1) / per_split), 1, clampi((T + 127) / 128, 1, 64));
-  const long per_split_v = (long)B * ((H + 3) / 4);
-  p.nsplit_v = clampi((int)((1024 + per_split_v - 1) / per_split_v), 1, clampi((T + 127) / 128, 1, 256));
+  // vanilla kernel: workgroups of four waves, a wave per group of heads; about eight workgroups per
+  // compute unit, splits of at least 256 rows
+  const int hpw = vanilla_heads_per_wave(DT_BF16, e / H);      // (the packing of the bf16 kernel; harmless for fp32)
+  const long per_split_v = (long)B * (((H + (hpw ? hpw : 1) - 1) / (hpw ? hpw : 1) + 3) / 4);
+  p.nsplit_v = clampi((int)((2048 + per_split_v - 1) / per_split_v), 1, clampi(T / 256, 1, 256));
   size_t o = 0;
   p.off_ctrl = o;    o += up(sizeof(int) * CTRL_INTS);
   p.fused_ok = (width == e) && fused_geometry(B, H, T, width, &p.geom);

@@ -50,6 +50,7 @@ void launch_zero_ints(int* p, int n, hipStream_t st);
 void launch_read_probe(const void* buf, size_t bytes, hipStream_t st);
 
 // Vanilla K+V decode: partial (m, l, acc) per (b, split, head) then a merge.
+int vanilla_heads_per_wave(int dtype, int d_k);   // heads a wave of the packed bf16 kernel covers (0: plain kernel)
 void launch_vanilla(int dtype, const float* q, const void* K, const void* V, long bstride,
                     const int32_t* seq_lens, int T, int H, int d_k, int nsplit, float* acc,
                     float* mpart, float* lpart, float* out, int B, hipStream_t st);
