@@ -1,8 +1,7 @@
 """GPU parity at the full sizes of the five configs, in the launch configuration bench.py
-times (library-chosen variant, ragged lengths where the config has them).  Where the fp64
-oracle for the whole batch would take too long, a fixed sample of sequences is compared
-(shortest, longest and two seeded picks for config 2; two sequences for config 4) and the
-rest of the batch is checked for finiteness and against the vanilla K+V kernel."""
+times (library-chosen variant, ragged lengths where the config has them).  Configs 2 and 4 have a
+quick test on a sample of sequences (shortest, longest and two seeded picks; two sequences) and a
+slower one that compares every sequence of the batch with the fp64 oracle."""
 import numpy as np
 import pytest
 
@@ -78,6 +77,37 @@ def test_config2_phi3_ragged_batch_sampled():
     cross = head_rel_err(a, v.astype(np.float64), cfg.H)          # all 16 sequences, kernel vs kernel
     say(f"  slim vs vanilla over the whole batch: {cross:.3e}")
     assert cross <= 2 * TOL["bf16"]
+
+
+def test_config2_phi3_ragged_batch_every_sequence():
+    """All 16 sequences of config 2 against the fp64 oracle (the oracle's K and V for the whole batch:
+    about 17 GB of host memory, a few minutes of fp64 products)."""
+    cfg = C[2]
+    say("[case] config 2 full size, oracle on all 16 sequences")
+    k = KCase(cfg)
+    assert len(k.oracle_rows) == cfg.B
+    a = k.run_slim()
+    e = k.err(a)
+    say(f"  slim rel err {e:.3e} over all {cfg.B} sequences")
+    assert e <= TOL["bf16"]
+    ev = k.err(k.run_vanilla())
+    say(f"  vanilla rel err {ev:.3e} over all {cfg.B} sequences")
+    assert ev <= TOL["bf16"]
+
+
+def test_config4_t5_xcache_every_sequence():
+    cfg = C[4]
+    say("[case] config 4 full size, oracle on all 8 sequences")
+    x = XCase(cfg)
+    assert len(x.oracle_rows) == cfg.B
+    out = x.run()
+    e = x.err(out)
+    say(f"  xcache rel err {e:.3e} over all {cfg.B} sequences")
+    assert e <= TOL["bf16"]
+    g = x.run(variant=binding.VARIANT_GENERIC)
+    eg = x.err(g)
+    say(f"  plain kernels rel err {eg:.3e}")
+    assert eg <= TOL["bf16"]
 
 
 def test_config4_t5_xcache_sampled():

@@ -198,19 +198,22 @@ def test_xcache_mfma_path_matches_oracle(name, cfg, q_scale, lens):
     assert np.array_equal(a, x.run()), "two runs of the same launch configuration differ"
 
 
-def test_xcache_mfma_path_agrees_with_plain_kernels_on_very_peaky_scores():
-    """Queries x40 make the softmax nearly one-hot.  At that scale the bf16 rounding of W_K alone
-    moves the result by more than the oracle tolerance (both implementations show the same
-    3.7e-2), so the streaming max / rescale logic of the MFMA path is checked against the plain
-    fp32 vector-ALU kernels, which share its inputs bit for bit."""
+def test_xcache_mfma_path_on_very_peaky_scores():
+    """Queries x40 make the softmax nearly one-hot.  At that scale the bf16 rounding of W_K alone moves
+    the result by more than the tolerance (3.7e-2 in both implementations), so the oracle is given the
+    weights as stored (rounded to bf16): what is then compared is the streaming maximum / rescaling of
+    the MFMA path.  The plain fp32 vector-ALU kernels, which share its inputs bit for bit, ride along as
+    a cross-check."""
     from gpu_harness import head_rel_err
     cfg = synth.scaled(C[4], B=2, H=32, d=1024, d_k=64, T=1100)
-    say("[case] slim_decode_xcache very peaky, MFMA path vs plain kernels")
-    x = XCase(cfg, q_scale=40.0, oracle_seqs=set())
+    say("[case] slim_decode_xcache very peaky (oracle on the stored weights), MFMA path and plain kernels")
+    x = XCase(cfg, q_scale=40.0, oracle_sees_rounded_weights=True)
     a, g = x.run(), x.run(variant=VARIANTS["generic"])
-    assert np.isfinite(a).all() and np.isfinite(g).all()
+    ea, eg = x.err(a), x.err(g)
+    say(f"  MFMA path vs oracle {ea:.3e}, plain kernels vs oracle {eg:.3e}")
+    assert ea <= TOL[cfg.dtype] and eg <= TOL[cfg.dtype]
     e = head_rel_err(a, g.astype(np.float64), cfg.H)
-    say(f"  rel diff {e:.3e}")
+    say(f"  MFMA path vs plain kernels {e:.3e}")
     assert e <= 1e-2          # bf16 weights and bf16 q~ operands vs fp32 arithmetic on the same inputs
 
 
