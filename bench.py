@@ -148,6 +148,61 @@ def bench_xcache(args, cfg, torch, binding, synth):
     print(json.dumps(result), flush=True)
 
 
+def bench_ecache_layers(args, cfg, torch, binding, synth):
+    """--ecache --layers L (config 3): L decoder layers' cross-attention in a row, three ways.  Option 2 of the
+    encoder-decoder section: every layer reads the SAME encoder output E through slim_decode_xcache with its
+    own W_K, W_V.  Option 1: every layer reads its own K-cache through slim_decode with its own W_KV.  Vanilla:
+    its own K and V caches.  Values are random (only shapes and traffic matter here; parity is the tests' job)."""
+    B, H, T, d, d_k = cfg.B, cfg.H, cfg.T, cfg.d, cfg.d_k
+    L = args.layers
+    gen = torch.Generator(device="cuda").manual_seed(20250305)
+    rnd = lambda *shape, std=1.0: (torch.randn(shape, device="cuda", generator=gen) * std).to(torch.bfloat16)
+    E = rnd(B, T, d)
+    Wk = [rnd(d, d, std=d ** -0.5) for _ in range(L)]
+    Wv = [rnd(d, d, std=d ** -0.5) for _ in range(L)]
+    Wkv = [rnd(d, d) for _ in range(L)]
+    Ks = [rnd(B, T, d, std=(1.75 / d) ** 0.5) for _ in range(L)]
+    Vs = [rnd(B, T, d, std=d ** -0.5) for _ in range(L)]
+    q = torch.randn((B, d), device="cuda", generator=gen)
+    out = torch.zeros((B, d), device="cuda", dtype=torch.float32)
+    ws = torch.empty(max(binding.slim_workspace_bytes(B, H, T, d, "bf16"), binding.slim_workspace_bytes_xcache(B, H, T, d, d_k, "bf16")),
+                     dtype=torch.uint8, device="cuda")
+    binding.slim_init()
+
+    def option2(i):
+        for l in range(L):
+            binding.slim_decode_xcache(q, E, Wk[l], Wv[l], out, B, H, T, d, d_k, dtype="bf16", workspace=ws)
+
+    def option1(i):
+        for l in range(L):
+            binding.slim_decode(q, Ks[l], Wkv[l], out, B, H, T, d, dtype="bf16", workspace=ws)
+
+    def vanilla(i):
+        for l in range(L):
+            binding.vanilla_kv_decode(q, Ks[l], Vs[l], out, B, H, T, d, dtype="bf16", workspace=ws)
+
+    steps, warm = max(3, args.steps // 10), 2
+    ms2 = timed(torch, option2, steps, warm) / L
+    ms1 = timed(torch, option1, steps, warm) / L
+    msv = timed(torch, vanilla, steps, warm) / L
+    e_bytes = float(B) * T * d * 2
+    result = {
+        "metric": "per-layer time of the cross-attention decode step over L decoder layers: E-cache (option 2) vs K-only cache (option 1) vs K+V, 1 GPU",
+        "value": round(B / (ms2 * 1e-3), 2), "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": warm,
+        "ms_per_step": round(ms2, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"configs[3] {cfg.name}, {L} layers on one shared E", "B": B, "H": H, "d": d, "d_k": d_k, "T": T, "layers": L},
+        "ecache_option2_ms_per_layer": round(ms2, 5), "kcache_option1_ms_per_layer": round(ms1, 5),
+        "vanilla_kv_ms_per_layer": round(msv, 5),
+        "cache_bytes_per_layer": {"option2_E_shared": e_bytes / L, "option1_K": e_bytes, "vanilla_KV": 2 * e_bytes},
+        "roofline": {"bound": "hbm", "kernel": "all launches of one layer (option 2)", "achieved": round((e_bytes + 2.0 * d * d * 2) / (ms2 * 1e-3) / 1e9, 1),
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round((e_bytes + 2.0 * d * d * 2) / (ms2 * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                     "traffic": None},
+        "cpu_baseline": None,
+    }
+    print(json.dumps(result), flush=True)
+
+
 def bench_block(args, cfg, torch, binding, synth):
     """--block: one generated token per sequence through the whole attention block
     (slim_attention_block: q and k projections, append, decode step, W_O) against
@@ -456,6 +511,8 @@ def main():
     ap.add_argument("--ecache", action="store_true",
                     help="config 3 only: the cross-attention layer reads the encoder output E through slim_decode_xcache "
                          "(option 2 of the encoder-decoder section) instead of a cross K-cache")
+    ap.add_argument("--layers", type=int, default=1,
+                    help="with --ecache: this many decoder layers in a row on one shared encoder output (random values; per-layer times)")
     ap.add_argument("--block", action="store_true",
                     help="time the whole attention block (slim_attention_block vs vanilla_attention_block) instead of the decode step")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -475,6 +532,8 @@ def main():
     if args.ecache:
         if headline != 3:
             sys.exit("bench.py: --ecache applies to config 3 (the encoder-decoder cross-attention shape)")
+        if args.layers > 1:
+            return bench_ecache_layers(args, cfg, torch, binding, synth)
         cfg = synth.scaled(cfg, kind="xcache", name=cfg.name + " as E-cache (option 2)")
     if cfg.kind == "xcache":
         if args.rope or args.block:
