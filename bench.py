@@ -65,6 +65,18 @@ def timed(torch, fn, steps, warmup):
     return (time.perf_counter() - t) * 1e3 / steps
 
 
+def calibration_copy(args, torch):
+    """--calibration-copy: five plain 128 MiB device copies, a kernel of known traffic for scaling byte counters."""
+    if not args.calibration_copy:
+        return
+    src = torch.empty(128 << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
+    dst = torch.empty_like(src)
+    for _ in range(5):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    del src, dst
+
+
 XCACHE_STAGES = ["q_tilde (head_scores on W_K)", "dense_scores", "weighted_sum", "combine", "project"]
 XCACHE_MFMA_STAGES = ["xq_tilde", "xscores", "xweighted", "project_mfma"]
 
@@ -86,6 +98,7 @@ def bench_xcache(args, cfg, torch, binding, synth):
     def slim(i, **extra):
         binding.slim_decode_xcache(q, Xs[i % ncopies], Wk, Wv, out, B, H, T, dm, d_k, dtype=cfg.dtype, **extra)
 
+    calibration_copy(args, torch)
     log("[bench] timing slim_decode_xcache ...")
     ms = timed(torch, slim, args.steps, args.warmup)
     # the same-GPU comparison reads e-wide K and V caches (random values: only the traffic matters)
@@ -378,13 +391,7 @@ def bench_kcache(args, cfg, torch, binding, synth, with_cpu):
     def vanilla(i, **extra):
         binding.vanilla_kv_decode(q, Ks[i % ncopies], Vs[i % ncopies], out_v, B, H, T, d, **kw, **extra)
 
-    if args.calibration_copy:
-        src = torch.empty(128 << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
-        dst = torch.empty_like(src)
-        for _ in range(5):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
+    calibration_copy(args, torch)
     log("[bench] timing slim_decode ...")
     ms_slim = timed(torch, slim, args.steps, args.warmup)
     log("[bench] timing vanilla_kv_decode ...")

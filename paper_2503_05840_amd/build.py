@@ -1,5 +1,5 @@
 """Builds the C-ABI library `libslim_attention.so` in-tree (hipcc for gfx950, g++ for the
-host-only offline transform) and, with `oracle=True`, whatever C the oracle directory holds.
+host-only offline transform).  The oracle is numpy only: there is nothing of it to compile.
 
     python -m paper_2503_05840_amd.build
 """

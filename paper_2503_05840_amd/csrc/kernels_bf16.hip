@@ -11,21 +11,24 @@
 // (512 KB for H=32, d=4096: a whole CU's register file), so the row width has to be split over
 // workgroups; but head h's weights need columns [h d_k, (h+1) d_k) only, which one column owner
 // holds, while every column owner needs every head's weights.  A "group" of G workgroups (one per
-// column unit of <=128 columns) therefore walks the same rows together; a scoring wave computes
-// the scores of the heads inside its unit from the 32-row tile it has just loaded, turns them into
-// softmax numerators against the head's running reference, parks the tile in LDS and publishes
-// 16-byte words {tag, reference, 4 bf16 numerators} to a small ring in global memory; a summing wave
-// gathers all heads' words of the tile, takes the tile out of LDS and feeds it to the MFMA.  No fences
+// column unit of <=128 columns) therefore walks the same rows together; wave w of every workgroup of
+// the group takes the same 32-row tiles: it computes the scores of the heads inside its unit, turns them
+// into softmax numerators against the head's running reference, parks the tile in LDS and publishes
+// 16-byte words {tag, reference, 4 bf16 numerators} to a small ring in global memory; one step later it
+// gathers all heads' words of that tile, takes the tile out of LDS and feeds it to the MFMA.  No fences
 // are needed: every 16-byte word (written by one store) carries the tile's tag, so a reader either
-// sees the values of this tile or gathers again.  Every wait is bounded; a time-out raises an error
-// word instead of hanging.
+// sees the values of this tile or gathers again.  Every wait is bounded in real time; a time-out raises
+// an error word instead of hanging.
 //
 // Register tile.  A wave owns 32 rows x 128 columns: lane l loads 16 bytes (8 columns) of 8 rows,
-// column group l%16, row group l/16.  The MFMA (v_mfma_f32_16x16x32_bf16) contracts over rows,
-// so the 8x8 block of each lane is transposed in registers (v_perm_b32) into 8 A-operands, one
-// per column of the lane: A_i[m = l%16][k = (l/16)*8 + j] = K[row (l/16)*8 + j][col (l%16)*8 + i].
-// The B-operand is P^T: lane (n = l%16, l/16) holds the weights of head n for the same 8 rows.
+// column group l%16, row group l/16.  Both MFMA contractions take their operands from the tile's LDS
+// copy.  Scores (v_mfma_f32_16x16x32_bf16, contraction over columns): A = 16 rows x 32 columns read
+// straight in operand layout, B = the unit's queries.  Weighted sum (contraction over rows): a lane reads
+// its 8 x 8 block back and transposes it in registers (v_perm_b32) into 8 A-operands, one per column:
+// A_i[m = l%16][k = 8 rows of lane group l/16] = K[row][col (l%16)*8 + i]; the B-operand is P^T: lane
+// (n = l%16, l/16) holds the weights of head n for the same 8 rows.
 #include "slim_kernels.h"
+#include "device_common.h"
 
 #include <math.h>
 #include <type_traits>
@@ -33,19 +36,7 @@
 namespace slim {
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-
-constexpr float NEG_INF = -INFINITY;
 constexpr float LOG2E = 1.4426950408889634f;
-
-__device__ __forceinline__ int seq_len_of(const int32_t* lens, int b, int T) {
-  if (!lens) return T;
-  const int n = lens[b];
-  return n < 0 ? 0 : (n > T ? T : n);
-}
 
 __device__ __forceinline__ float bf16_lo(unsigned x) { return __uint_as_float(x << 16); }
 __device__ __forceinline__ float bf16_hi(unsigned x) { return __uint_as_float(x & 0xffff0000u); }
@@ -65,19 +56,6 @@ __device__ __forceinline__ float max_over_row_groups(float v) {
   const unsigned w = __float_as_uint(h);
   const auto b = __builtin_amdgcn_permlane16_swap(w, w, false, false);
   return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
-}
-
-// 8 rows x 8 bf16 columns per lane  ->  8 operands (one per column), each 8 rows of that column.
-__device__ __forceinline__ void transpose8x8(const u32x4 (&kt)[8], u32x4 (&a)[8]) {
-#pragma unroll
-  for (int jp = 0; jp < 4; ++jp) {
-    const u32x4 lo = kt[2 * jp], hi = kt[2 * jp + 1];
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      a[2 * c][jp] = __builtin_amdgcn_perm(hi[c], lo[c], 0x05040100u);      // even column: low halves
-      a[2 * c + 1][jp] = __builtin_amdgcn_perm(hi[c], lo[c], 0x07060302u);  // odd column: high halves
-    }
-  }
 }
 
 // Score exchange accesses.  Readers load at agent scope (never served by the CU's own vector L1).
@@ -115,28 +93,6 @@ __device__ __forceinline__ void st_result4(float* p, f32x4 v, bool write_through
   // (s_nops: see st_exch)
   if (write_through) asm volatile("s_nop 1\n\tglobal_store_dwordx4 %0, %1, off sc0 sc1\n\ts_nop 1" : : "v"(p), "v"(v) : "memory");
   else *reinterpret_cast<f32x4*>(p) = v;
-}
-
-// s_waitcnt vmcnt(n) for a run-time even n <= 30 (the instruction wants a constant).
-__device__ __forceinline__ void wait_vm_outstanding(int n) {
-  switch (n >> 1) {
-#define SLIM_VM_CASE(N) case N / 2: asm volatile("s_waitcnt vmcnt(" #N ")" ::: "memory"); break;
-    SLIM_VM_CASE(0) SLIM_VM_CASE(2) SLIM_VM_CASE(4) SLIM_VM_CASE(6) SLIM_VM_CASE(8) SLIM_VM_CASE(10)
-    SLIM_VM_CASE(12) SLIM_VM_CASE(14) SLIM_VM_CASE(16) SLIM_VM_CASE(18) SLIM_VM_CASE(20) SLIM_VM_CASE(22)
-    SLIM_VM_CASE(24) SLIM_VM_CASE(26) SLIM_VM_CASE(28)
-#undef SLIM_VM_CASE
-    default: asm volatile("s_waitcnt vmcnt(30)" ::: "memory"); break;
-  }
-}
-
-// f(k + I, integral_constant<I>) for I = 0 .. N-1 while k + I < end: loop bodies whose register
-// buffers are chosen by a compile-time index.
-template <int I, int N, class F>
-__device__ __forceinline__ void unrolled_steps(int k, int end, F& f) {
-  if constexpr (I < N) {
-    if (k + I < end) f(k + I, std::integral_constant<int, I>{});
-    unrolled_steps<I + 1, N>(k, end, f);
-  }
 }
 
 // Tiles of 32 rows: prefix[b] = number of tiles of sequences 0..b-1.  One thread, B is small.
