@@ -981,7 +981,10 @@ __global__ __launch_bounds__(FUSED_WAVES * 64) void fused_stream_kernel(const Fu
       {
         using S0 = std::integral_constant<int, 0>;
         using S1 = std::integral_constant<int, 1>;
-        if (ntl > 0) { score_tile(0, S0{}); request(PD, S0{}); }
+        // (the request is unconditional: a path into the loop without it would make the compiler wait for
+        //  every outstanding load at the top of each step)
+        if (ntl > 0) score_tile(0, S0{});
+        request(PD, S0{});
         // Whole rounds of PD steps without a condition between them (a step that may be skipped
         // inside the loop would make the compiler's waits for the tile registers conservative).
         int k = 1;
