@@ -338,8 +338,14 @@ def bench_kcache(args, cfg, torch, binding, synth, with_cpu):
     p = synth.make_problem(cfg)
     lens = p.lengths
     el = np.uint16 if cfg.dtype == "bf16" else np.float32
-    Kh = np.zeros((B, T, d), dtype=el)
-    Vh = np.zeros((B, T, d), dtype=el)
+    # The K-cache the slim step reads is banded (bands of 32 rows, head-major inside a band: SLIM_K_BANDED)
+    # unless --k-layout rowmajor or a variant whose kernels read row-major caches only; the same step on the
+    # row-major cache is timed beside it, and the vanilla kernel always reads row-major K and V.
+    which = os.environ.get("SLIM_BENCH_STAGES") or (args.variant if args.variant != "auto" else binding.auto_variant_name(B, H, T, d, cfg.dtype))
+    banded = args.k_layout == "banded" and which in ("fused", "fused_split")
+    ts = (T + 31) // 32 * 32 if banded else T          # whole bands per sequence
+    Kh = np.zeros((B, ts, d), dtype=el)
+    Vh = np.zeros((B, ts, d), dtype=el)
     K64 = V64 = None
     for b, sq in enumerate(p.seqs):
         n = int(lens[b])
@@ -358,6 +364,11 @@ def bench_kcache(args, cfg, torch, binding, synth, with_cpu):
     ncopies = args.copies or max(2, int(np.ceil(512e6 / k_bytes_alloc)) + 1)
     Ks = [to_device(Kh) for _ in range(ncopies)]
     Vs = [to_device(Vh) for _ in range(ncopies)]
+    Kbs = None
+    if banded:
+        Kbh = binding.slim_band_kcache(Kh, H)
+        Kbs = [to_device(Kbh) for _ in range(ncopies)]
+        del Kbh
     del Kh, Vh
     q = to_device(p.q.astype(np.float32))
     # W_KV rotates with the cache copies: at small batch it is a quarter of the step's bytes and one
@@ -371,7 +382,7 @@ def bench_kcache(args, cfg, torch, binding, synth, with_cpu):
     out_v = torch.zeros_like(out)
     ws = torch.empty(binding.slim_workspace_bytes(B, H, T, d, cfg.dtype), dtype=torch.uint8, device="cuda")
     ragged = bool((lens != T).any())
-    kw = dict(dtype=cfg.dtype, workspace=ws)
+    kw = dict(dtype=cfg.dtype, workspace=ws, t_stride=ts)
     if ragged:
         kw.update(seq_lens=lens_dev, seq_lens_host=lens)
     rope_bytes = 0.0
@@ -386,7 +397,14 @@ def bench_kcache(args, cfg, torch, binding, synth, with_cpu):
     binding.slim_init()
 
     def slim(i, variant=variant, **extra):
-        binding.slim_decode(q, Ks[i % ncopies], Wkvs[i % wcopies], out, B, H, T, d, variant=variant, **kw, **kw_rope, **extra)
+        if banded:
+            binding.slim_decode(q, Kbs[i % ncopies], Wkvs[i % wcopies], out, B, H, T, d, variant=variant,
+                                k_layout=binding.K_BANDED, **kw, **kw_rope, **extra)
+        else:
+            binding.slim_decode(q, Ks[i % ncopies], Wkvs[i % wcopies], out, B, H, T, d, variant=variant, **kw, **kw_rope, **extra)
+
+    def slim_rowmajor(i):
+        binding.slim_decode(q, Ks[i % ncopies], Wkvs[i % wcopies], out, B, H, T, d, variant=variant, **kw, **kw_rope)
 
     def vanilla(i, **extra):
         binding.vanilla_kv_decode(q, Ks[i % ncopies], Vs[i % ncopies], out_v, B, H, T, d, **kw, **extra)
@@ -394,6 +412,7 @@ def bench_kcache(args, cfg, torch, binding, synth, with_cpu):
     calibration_copy(args, torch)
     log("[bench] timing slim_decode ...")
     ms_slim = timed(torch, slim, args.steps, args.warmup)
+    ms_slim_rowmajor = timed(torch, slim_rowmajor, args.steps, args.warmup) if banded else None
     log("[bench] timing vanilla_kv_decode ...")
     ms_van = timed(torch, vanilla, args.steps, args.warmup)
     # hot numbers (one buffer, may be served by the memory-side cache)
@@ -417,7 +436,6 @@ def bench_kcache(args, cfg, torch, binding, synth, with_cpu):
         vacc += vstage[0]
     vacc /= args.steps
 
-    which = os.environ.get("SLIM_BENCH_STAGES") or (args.variant if args.variant != "auto" else binding.auto_variant_name(B, H, T, d, cfg.dtype))
     names = list(STAGES[which])
     k_bytes = float(lens.astype(np.int64).sum()) * d * es            # K-cache rows read once
     w_bytes = float(d) * d * es                                       # W_KV once per step
@@ -479,7 +497,9 @@ def bench_kcache(args, cfg, torch, binding, synth, with_cpu):
         "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"configs[{cfg.index}] {cfg.name}" + (" + rotary keys (RoPE option 1, raw keys cached)" if args.rope else ""),
                    "B": B, "H": H, "d": d, "d_k": d_k, "T": T,
-                   "sum_len": int(lens.sum()), "variant": which, "k_cache_copies_rotated": ncopies, "w_kv_copies_rotated": wcopies},
+                   "sum_len": int(lens.sum()), "variant": which,
+                   "k_layout": "banded (32-row bands, head-major)" if banded else "row-major",
+                   "k_cache_copies_rotated": ncopies, "w_kv_copies_rotated": wcopies},
         "k_cache_gbps": round(k_gbps, 1),
         "k_cache_frac_of_hbm_peak": round(k_gbps / HBM_PEAK_GBPS, 4),
         "measured_read_stream_gbps": round(probe_gbps, 1),
@@ -491,13 +511,18 @@ def bench_kcache(args, cfg, torch, binding, synth, with_cpu):
         "bytes_ratio_vanilla_over_slim": round(2 * k_bytes / (k_bytes + w_bytes), 3),
         "roofline": roofline, "cpu_baseline": cpu,
     }
+    if ms_slim_rowmajor is not None:
+        # the same step on the row-major cache [B][T][d]
+        result["rowmajor_k_cache"] = {"ms_per_step": round(ms_slim_rowmajor, 5),
+                                      "k_cache_gbps": round(k_bytes / (ms_slim_rowmajor * 1e-3) / 1e9, 1),
+                                      "speedup_vs_vanilla_kv": round(ms_van / ms_slim_rowmajor, 3)}
     if split_ms is not None:
         # K1 + K2 (the K stream) apart from K3 (merge + W_KV projection), as two launches
         result["k_stream_only_ms"] = round(split_ms[0], 5)
         result["k_stream_only_gbps"] = round(k_bytes / (split_ms[0] * 1e-3) / 1e9, 1)
         result["k_stream_only_frac_of_hbm_peak"] = round(k_bytes / (split_ms[0] * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)
         result["merge_projection_ms"] = round(split_ms[1], 5)
-    del Ks, Vs, Wkvs, ws
+    del Ks, Vs, Kbs, Wkvs, ws
     torch.cuda.empty_cache()
     return result
 
@@ -512,6 +537,8 @@ def main():
                          "with configs[1] nested in the same line)")
     ap.add_argument("--variant", default="auto", choices=["auto", "generic", "fused", "fused_split"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--k-layout", default="banded", choices=["banded", "rowmajor"],
+                    help="layout of the K-cache slim_decode reads (the fast path only; vanilla_kv_decode reads row-major K and V)")
     ap.add_argument("--copies", type=int, default=0, help="K-cache copies to rotate over (0 = enough to exceed 512 MB)")
     ap.add_argument("--rope", action="store_true",
                     help="keys carry rotary positions: slim_decode rotates the raw cached keys for the scores (K-cache configs)")

@@ -47,6 +47,8 @@ extern "C" {
 #define SLIM_ERR_LAUNCH     -8   /* HIP reported an error at allocation or launch             */
 #define SLIM_ERR_SEQLEN     -9   /* a host-side sequence length is < 1 or > T                 */
 #define SLIM_ERR_TIMEOUT   -10   /* slim_status: a wait between workgroups ran out (outputs NaN) */
+#define SLIM_ERR_LAYOUT    -11   /* opts->k_layout: rows per sequence not a multiple of 32, or a shape or
+                                    dtype whose kernels read row-major caches only              */
 
 /* ---- element types of the cache and of packed weights -------------------------------- */
 #define SLIM_F32   0
@@ -80,6 +82,12 @@ int slim_prepare_wkv_nonsquare(const double* Wk, const double* Wv, double* Wkv, 
  * (d x d) and the X-cache weights (d_model x e) are handed to the decode calls; the
  * caller copies `dst_host` (rows*cols*elemsize bytes, host) to the device. */
 int slim_pack_weights(const double* W, void* dst_host, int rows, int cols, int dtype);
+
+/* Host copy of a row-major K-cache [B][t_stride][H*d_k] into the banded layout (SLIM_K_BANDED) of the same
+ * size; elem_bytes = 2 or 4; t_stride % 32 == 0 (SLIM_ERR_LAYOUT otherwise).  src and dst are host
+ * buffers of B * t_stride * H * d_k elements and must not overlap. */
+int slim_band_kcache(const void* src_host, void* dst_host, int B, int64_t t_stride, int H, int d_k,
+                     int elem_bytes);
 
 /* The look-up table of the RoPE appendix, one table for encoding and decoding:
  *   table[t][j] = { cos(t * theta_j), sin(t * theta_j) },  theta_j = base^(-2j/d_k),
@@ -118,7 +126,25 @@ typedef struct slim_opts {
                                     microseconds of real time: 0 => 20000; negative => no waiting at
                                     all (every wait that is not satisfied at once gives up: for tests
                                     of the failure path, see slim_status)                          */
+  int            k_layout;       /* SLIM_K_ROWMAJOR (0) | SLIM_K_BANDED: layout of Kcache in slim_decode,
+                                    slim_decode_static and slim_attention_block (see SLIM_K_BANDED)  */
 } slim_opts;
+
+/* Layouts of the K-cache of one sequence (sequences are t_stride * d elements apart in both).
+ * Which elements a step reads is the method's (the first seq_lens[b] rows, eq. 7); where they sit in
+ * memory is the cache's own business, and the kernel that streams them is bound by HBM:
+ *   SLIM_K_ROWMAJOR  [t][d]: element (t, h, j) at t*d + h*d_k + j.
+ *   SLIM_K_BANDED    [t / 32][H][32][d_k]: bands of 32 rows, head-major inside a band, element
+ *                    (t, h, j) at ((t / 32) * H + h) * 32 * d_k + (t % 32) * d_k + j.  A head's 32 x d_k
+ *                    block (the unit a wave of the stream kernel loads) is one contiguous run of
+ *                    64 * d_k bytes instead of 32 row pieces of 2 * d_k bytes, which for head widths
+ *                    that are not a multiple of 64 elements (d_k = 96: 192-byte pieces, one and a half
+ *                    cache lines) is the difference between 4.4 and 5.0 TB/s on the long batch.
+ *                    t_stride % 32 == 0; bf16 shapes the stream kernel takes (H <= 32, 16 <= d_k <= 128
+ *                    on a device where it fits), else SLIM_ERR_LAYOUT.  slim_attention_block appends
+ *                    the new row in this layout; slim_band_kcache converts a host copy. */
+#define SLIM_K_ROWMAJOR 0
+#define SLIM_K_BANDED   1
 
 #define SLIM_MAX_STAGES 8
 

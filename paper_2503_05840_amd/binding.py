@@ -17,12 +17,13 @@ LIB_PATH = os.environ.get("SLIM_ATTENTION_LIB") or os.path.join(_PKG, "libslim_a
 SLIM_OK = 0
 SLIM_F32, SLIM_BF16 = 0, 1
 VARIANT_AUTO, VARIANT_GENERIC, VARIANT_FUSED_SPLIT, VARIANT_FUSED = 0, 1, 2, 3
+K_ROWMAJOR, K_BANDED = 0, 1       # slim_opts.k_layout
 DTYPES = {"f32": SLIM_F32, "bf16": SLIM_BF16}
 
 EXPORTS = ("slim_strerror", "slim_prepare_wkv", "slim_prepare_wkv_nonsquare", "slim_pack_weights", "slim_rope_table", "slim_workspace_bytes",
            "slim_workspace_bytes_xcache", "slim_workspace_bytes_block", "slim_attention_block", "vanilla_attention_block",
            "slim_variant_for", "slim_decode", "vanilla_kv_decode", "slim_decode_xcache", "slim_init", "slim_status",
-           "slim_read_probe", "slim_decode_static", "slim_static_scratch_bytes")
+           "slim_read_probe", "slim_decode_static", "slim_static_scratch_bytes", "slim_band_kcache")
 VARIANT_NAMES = {1: "generic", 2: "fused_split", 3: "fused"}
 
 
@@ -39,6 +40,7 @@ class SlimOpts(ctypes.Structure):
         ("stage_ms", ctypes.POINTER(ctypes.c_float)),
         ("rope_table", ctypes.c_void_p),
         ("wait_budget_us", ctypes.c_int64),
+        ("k_layout", ctypes.c_int),
     ]
 
 
@@ -103,6 +105,8 @@ def load():
     lib.slim_decode_static.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, op]
     lib.slim_static_scratch_bytes.restype = ctypes.c_size_t
     lib.slim_static_scratch_bytes.argtypes = []
+    lib.slim_band_kcache.restype = ci
+    lib.slim_band_kcache.argtypes = [vp, vp, ci, ctypes.c_int64, ci, ci, ci]
     lib.slim_read_probe.restype = ci
     lib.slim_read_probe.argtypes = [vp, ctypes.c_size_t, vp]
     _lib = lib
@@ -156,6 +160,17 @@ def slim_pack_weights(W: np.ndarray, dtype: str) -> np.ndarray:
     return out
 
 
+def slim_band_kcache(K: np.ndarray, H: int) -> np.ndarray:
+    """Host K-cache (B, t_stride, d) row-major -> the banded layout (K_BANDED), same shape and dtype."""
+    K = np.ascontiguousarray(K)
+    B, t_stride, d = K.shape
+    out = np.empty_like(K)
+    rc = load().slim_band_kcache(K.ctypes.data, out.ctypes.data, B, t_stride, H, d // H, K.dtype.itemsize)
+    if rc != SLIM_OK:
+        raise SlimError(rc, "slim_band_kcache")
+    return out
+
+
 def slim_rope_table(T: int, d_k: int, base: float = 10000.0) -> np.ndarray:
     """(T, d_k/2, 2) float32 table of cos / sin(t * theta_j) for opts.rope_table."""
     out = np.empty((T, max(d_k // 2, 0), 2), dtype=np.float32)
@@ -191,7 +206,16 @@ def to_device(a: np.ndarray):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
+def to_host(t) -> np.ndarray:
+    """device tensor -> numpy array; bf16 tensors come back as their uint16 bit patterns."""
+    import torch
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).cpu().numpy().view(np.uint16)
+    return t.cpu().numpy()
+
+
 SLIM_ERR_TIMEOUT = -10
+SLIM_ERR_LAYOUT = -11
 STATIC_SCRATCH = 1          # slim_status: the scratch of slim_decode_static
 
 
@@ -217,7 +241,8 @@ def slim_read_probe(buf) -> None:
         raise SlimError(rc, "slim_read_probe")
 
 
-def _opts(dtype, seq_lens, seq_lens_host, t_stride, workspace, variant, stage_ms=None, rope_table=None, wait_budget_us=0):
+def _opts(dtype, seq_lens, seq_lens_host, t_stride, workspace, variant, stage_ms=None, rope_table=None, wait_budget_us=0,
+          k_layout=0):
     import torch
     o = SlimOpts()
     o.dtype = DTYPES[dtype]
@@ -237,6 +262,7 @@ def _opts(dtype, seq_lens, seq_lens_host, t_stride, workspace, variant, stage_ms
     if rope_table is not None:
         o.rope_table = _dev_ptr(rope_table)
     o.wait_budget_us = int(wait_budget_us)
+    o.k_layout = int(k_layout)
     return o, keep
 
 
@@ -252,8 +278,10 @@ def _dev_ptr(t):
 
 
 def slim_decode(q, Kcache, W_KV, out, B, H, T, d, dtype="bf16", seq_lens=None, seq_lens_host=None,
-                t_stride=0, workspace=None, variant=VARIANT_AUTO, stage_ms=None, rope_table=None, wait_budget_us=0):
-    o, keep = _opts(dtype, seq_lens, seq_lens_host, t_stride, workspace, variant, stage_ms, rope_table, wait_budget_us)
+                t_stride=0, workspace=None, variant=VARIANT_AUTO, stage_ms=None, rope_table=None, wait_budget_us=0,
+                k_layout=K_ROWMAJOR):
+    o, keep = _opts(dtype, seq_lens, seq_lens_host, t_stride, workspace, variant, stage_ms, rope_table, wait_budget_us,
+                    k_layout)
     rc = load().slim_decode(_dev_ptr(q), _dev_ptr(Kcache), _dev_ptr(W_KV), _dev_ptr(out), B, H, T, d,
                             ctypes.byref(o))
     if rc != SLIM_OK:
@@ -262,9 +290,9 @@ def slim_decode(q, Kcache, W_KV, out, B, H, T, d, dtype="bf16", seq_lens=None, s
 
 
 def slim_decode_static(q, Kcache, W_KV, out, B, H, T, d, dtype="bf16", seq_lens=None, seq_lens_host=None,
-                       t_stride=0, variant=VARIANT_AUTO, rope_table=None):
+                       t_stride=0, variant=VARIANT_AUTO, rope_table=None, k_layout=K_ROWMAJOR):
     """slim_decode over the library's static device scratch: no allocation inside the call."""
-    o, keep = _opts(dtype, seq_lens, seq_lens_host, t_stride, None, variant, None, rope_table)
+    o, keep = _opts(dtype, seq_lens, seq_lens_host, t_stride, None, variant, None, rope_table, 0, k_layout)
     rc = load().slim_decode_static(_dev_ptr(q), _dev_ptr(Kcache), _dev_ptr(W_KV), _dev_ptr(out), B, H, T, d,
                                    ctypes.byref(o))
     if rc != SLIM_OK:
@@ -298,8 +326,8 @@ def slim_decode_xcache(q, X, W_K, W_V, out, B, H, T, d_model, d_k, dtype="bf16",
 
 def slim_attention_block(x, W_Q, W_K, W_KV, W_O, Kcache, y, B, H, T, d, dtype="bf16", seq_lens=None,
                          seq_lens_host=None, t_stride=0, workspace=None, variant=VARIANT_AUTO, stage_ms=None,
-                         rope_table=None):
-    o, keep = _opts(dtype, seq_lens, seq_lens_host, t_stride, workspace, variant, stage_ms, rope_table)
+                         rope_table=None, k_layout=K_ROWMAJOR):
+    o, keep = _opts(dtype, seq_lens, seq_lens_host, t_stride, workspace, variant, stage_ms, rope_table, 0, k_layout)
     rc = load().slim_attention_block(_dev_ptr(x), _dev_ptr(W_Q), _dev_ptr(W_K), _dev_ptr(W_KV), _dev_ptr(W_O),
                                      _dev_ptr(Kcache), _dev_ptr(y), B, H, T, d, ctypes.byref(o))
     if rc != SLIM_OK:

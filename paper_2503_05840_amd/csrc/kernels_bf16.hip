@@ -95,15 +95,29 @@ __device__ __forceinline__ void st_result4(float* p, f32x4 v, bool write_through
   else *reinterpret_cast<f32x4*>(p) = v;
 }
 
-// Tiles of 32 rows: prefix[b] = number of tiles of sequences 0..b-1.  One thread, B is small.
-__device__ void build_tile_prefix(int* prefix, const int32_t* lens, int B, int T) {
-  if (threadIdx.x == 0) {
-    int acc = 0;
-    prefix[0] = 0;
-    for (int b = 0; b < B; ++b) {
-      acc += (seq_len_of(lens, b, T) + TILE_ROWS - 1) / TILE_ROWS;
-      prefix[b + 1] = acc;
+// Tiles of 32 rows: prefix[b] = number of tiles of sequences 0..b-1; lens_s[b] (if given) = rows of
+// sequence b.  The first wave takes 64 sequences at a time, one per lane (one memory round trip per 64
+// sequences instead of one per sequence), and adds them up with a scan over the lanes.
+__device__ void build_tile_prefix(int* prefix, int* lens_s, const int32_t* lens, int B, int T) {
+  if (threadIdx.x < 64) {
+    const int lane = threadIdx.x;
+    int carry = 0;
+    for (int b0 = 0; b0 < B; b0 += 64) {
+      const int b = b0 + lane;
+      const int len = b < B ? seq_len_of(lens, b, T) : 0;
+      int v = (len + TILE_ROWS - 1) / TILE_ROWS;
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const int up = __shfl_up(v, o);
+        v += (lane >= o) ? up : 0;
+      }
+      if (b < B) {
+        prefix[b + 1] = carry + v;
+        if (lens_s) lens_s[b] = len;
+      }
+      carry += __shfl(v, 63);
     }
+    if (lane == 0) prefix[0] = 0;
   }
   __syncthreads();
 }
@@ -361,7 +375,11 @@ __device__ __forceinline__ void project_work(const ProjArgs& a, int hx, int cs, 
         r = (j & 1) ? fmaf(val, cs[0], -other * cs[1]) : fmaf(val, cs[0], other * cs[1]);
       }
       if (role == 1) { outp[b * a.e + col] = r; return; }
-      uint16_t* dst = (role == 2 ? a.Kc : a.Vc) + b * a.c_bstride + (size_t)pos * a.e + col;
+      // (banded K-cache: bands of 32 rows, a head's 32 x d_k block contiguous inside its band)
+      const size_t at = (role == 2 && a.k_banded)
+                            ? ((size_t)(pos >> 5) * a.H + h) * (32 * (size_t)a.d_k) + (size_t)(pos & 31) * a.d_k + j
+                            : (size_t)pos * a.e + col;
+      uint16_t* dst = (role == 2 ? a.Kc : a.Vc) + b * a.c_bstride + at;
       *dst = __builtin_bit_cast(uint16_t, (__bf16)r);
     }
   };
@@ -422,7 +440,7 @@ __global__ __launch_bounds__(512) void project_mfma_kernel(const ProjArgs a) {
   __shared__ ProjShared<NBT> sm;
   __shared__ float red[8 * 8 * 4 * 64];
   project_work<NBT, false, DENSE>(a, blockIdx.x, blockIdx.y, blockIdx.z, prefix, sm, red, [&]() {
-    if (!DENSE && a.mode == 0) build_tile_prefix(prefix, a.seq_lens, a.B, a.T);
+    if (!DENSE && a.mode == 0) build_tile_prefix(prefix, nullptr, a.seq_lens, a.B, a.T);
   });
 }
 
@@ -461,6 +479,7 @@ __global__ __launch_bounds__(FUSED_WAVES * 64) void fused_stream_kernel(const Fu
   constexpr int HP = NT * 16;                       // heads padded to the MFMA N tile
   static_assert(NP == 8 && NS == 2 && PD == 2, "the step structure and the thread mappings below assume these");
   __shared__ int prefix[FUSED_MAX_B + 1];
+  __shared__ int lens_s[FUSED_MAX_B];               // rows per sequence
   __shared__ float marr[NP][NT][16];
   __shared__ float larr[NP][NT][16];
   // Per wave: NS landing slots of 8 KB for K tiles.  By-context partition: the end-of-share merge of
@@ -503,7 +522,7 @@ __global__ __launch_bounds__(FUSED_WAVES * 64) void fused_stream_kernel(const Fu
   if (blockIdx.x == 0 && a.counters)                // the projection's arrival counters start at 0
     for (int i = tid; i < a.ncounters; i += NTHR) st_result(a.counters + i, 0, fuse);
 
-  build_tile_prefix(prefix, a.seq_lens, a.B, a.T);     // (ends with a workgroup barrier)
+  build_tile_prefix(prefix, lens_s, a.seq_lens, a.B, a.T);     // (ends with a workgroup barrier)
   const int VT = prefix[a.B];
   const int Qt = (VT + a.NG - 1) / a.NG;            // tiles per group
   const int v0 = g * Qt, v1 = min(VT, v0 + Qt);
@@ -584,7 +603,7 @@ __global__ __launch_bounds__(FUSED_WAVES * 64) void fused_stream_kernel(const Fu
       seg_b += a.NG * NP;
       const int tiles_b = prefix[b + 1] - prefix[b], per = (tiles_b + shares - 1) / shares;
       sg.b = b; sg.t0 = j * per; sg.stride = 1; sg.pid = q;
-      sg.len = seq_len_of(a.seq_lens, b, a.T);
+      sg.len = lens_s[b];
       sg.Kb = a.K + (size_t)b * a.k_bstride;
       sg.ntl = max(0, min(per, tiles_b - j * per));
       sg.it0 = seg_it;
@@ -598,7 +617,7 @@ __global__ __launch_bounds__(FUSED_WAVES * 64) void fused_stream_kernel(const Fu
       if (s0 >= s1) continue;
       sg.b = b; sg.pid = b + g;
       sg.t0 = s0 + p; sg.stride = NP;                 // this wave's tiles are s0+p, s0+p+NP, ...
-      sg.len = seq_len_of(a.seq_lens, b, a.T);
+      sg.len = lens_s[b];
       sg.Kb = a.K + (size_t)b * a.k_bstride;
       sg.ntl = max(0, (s1 - s0 - p + NP - 1) / NP);
       sg.it0 = seg_it;                                // tile k carries tag tag_base + it0 + k + 1
@@ -660,8 +679,16 @@ __global__ __launch_bounds__(FUSED_WAVES * 64) void fused_stream_kernel(const Fu
       unsigned ph[4], pl[4];                          // (-q2, q1) of every pair, same split (rotary keys)
       // (lanes without live columns re-read the unit's first columns: finite values that meet a zero
       //  query in the scores and accumulator rows nobody reads in the weighted sum)
-      const unsigned lane_col_off = (unsigned)(col_active ? mycol : ucol0) * 2u;
-      const unsigned lane_off = (unsigned)(rg * 8) * pitchB + lane_col_off;
+      // Byte offset of element (row r, this lane's first column) from the sequence's start:
+      //   (r / 32) * bandB + (r % 32) * rowB + lane_col_off
+      // row-major cache: rowB = the row pitch; banded cache (32-row bands, head-major inside a band: a
+      // head's 32 x d_k block is contiguous): rowB = d_k * 2 and the head's block offset joins the lane's.
+      const unsigned bandB = TILE_ROWS * pitchB;
+      const unsigned rowB = a.k_banded ? (unsigned)a.d_k * 2u : pitchB;
+      const int lane_head = col_active ? myhead : u * a.hpu, lane_li = col_active ? li : 0;
+      const unsigned lane_col_off = a.k_banded ? (unsigned)lane_head * TILE_ROWS * (unsigned)a.d_k * 2u + (unsigned)lane_li * 16u
+                                               : (unsigned)(col_active ? mycol : ucol0) * 2u;
+      const unsigned lane_off = (unsigned)(rg * 8) * rowB + lane_col_off;
       float mrun = NEG_INF;                           // running maximum of this lane's head (log2 domain)
       bf16x8 bq[4];                                   // B operands of the score MFMA (filled below, behind the first tile requests)
       // softmax state of the weighted sum and its accumulators; accl: sum of the weights (an all-ones A operand)
@@ -691,10 +718,10 @@ __global__ __launch_bounds__(FUSED_WAVES * 64) void fused_stream_kernel(const Fu
         }
         if (k < ntl && (st + 1) * TILE_ROWS <= len) {
           // full tile: uniform row base + per-lane 32-bit offset
-          const char* tb = reinterpret_cast<const char*>(Kb) + (size_t)st * TILE_ROWS * pitchB;
+          const char* tb = reinterpret_cast<const char*>(Kb) + (size_t)st * bandB;
 #pragma unroll
           for (int j = 0; j < 8; ++j)
-            t[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tb + (size_t)j * pitchB + lane_off));
+            t[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tb + (size_t)j * rowB + lane_off));
         } else {
           // last, partial tile (rows past the end re-read the last row; masked in the scores) or no tile
           const int r0 = st * TILE_ROWS + rg * 8;
@@ -702,7 +729,7 @@ __global__ __launch_bounds__(FUSED_WAVES * 64) void fused_stream_kernel(const Fu
 #pragma unroll
           for (int j = 0; j < 8; ++j) {
             const int rr = max(min(r0 + j, len - 1), 0);
-            t[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(cb + (size_t)rr * pitchB));
+            t[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(cb + (size_t)(rr >> 5) * bandB + (size_t)(rr & 31) * rowB));
           }
         }
       };
@@ -820,7 +847,6 @@ __global__ __launch_bounds__(FUSED_WAVES * 64) void fused_stream_kernel(const Fu
         }
       };
       // ---- the scoring half of a step: tile k parked, its numerators published
-      constexpr int LOADS_PER_TILE = ROPE ? 10 : 8;
       auto score_tile = [&](int k, auto SI) {
         unsigned pw[4];
         if constexpr (ROPE) {
@@ -855,10 +881,10 @@ __global__ __launch_bounds__(FUSED_WAVES * 64) void fused_stream_kernel(const Fu
           am[3][jp] = __builtin_amdgcn_perm(hi[2 * jp + 1], hi[2 * jp], 0x07060302u);
         }
       };
-      auto sum_finish = [&](int k, u32x4 (&am)[4]) {    // am: the first half, already out of the slot
+      // ---- every word of tile k must carry its tag; gather again while any is missing
+      auto await_words = [&](int k) {
         const unsigned tag = a.tag_base + sg.it0 + (unsigned)k + 1u;
         pin_gq();
-        // every word of tile k must carry its tag; gather again while any is missing
         unsigned long long since = ~0ull;
         for (;;) {
           unsigned bad = 0;
@@ -874,6 +900,8 @@ __global__ __launch_bounds__(FUSED_WAVES * 64) void fused_stream_kernel(const Fu
           asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
           pin_gq();
         }
+      };
+      auto sum_finish = [&](int k, u32x4 (&am)[4]) {    // am: the first half, already out of the slot
         bf16x8 pb[NT];
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
@@ -914,7 +942,10 @@ __global__ __launch_bounds__(FUSED_WAVES * 64) void fused_stream_kernel(const Fu
       // One step (k >= 1).  Tile k is scored and published first; only then are the words of tile k-1
       // requested (every workgroup of the group published them a scoring time ago), and behind them
       // tile k+2 (LOADS_PER_TILE loads, the only vector-memory operations younger than the gather when it
-      // is waited for).  The tile comes out of its slot while the words travel.
+      // is waited for).  The tile comes out of its slot while the words travel.  (Requesting the words
+      // before the scoring instead, and tile k+2 only after they have been checked, was measured: no
+      // faster at 8 tiles per wave, 4 % slower on long sequences.)
+      constexpr int LOADS_PER_TILE = ROPE ? 10 : 8;
       auto step = [&](int k, auto SI) {
         u32x4 am[4];
         score_tile(k, SI);
@@ -924,6 +955,7 @@ __global__ __launch_bounds__(FUSED_WAVES * 64) void fused_stream_kernel(const Fu
         if constexpr (ROPE) asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
         else asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
         static_assert(LOADS_PER_TILE == (ROPE ? 10 : 8), "the wait above counts the loads of one tile");
+        await_words(k - 1);
         sum_finish(k - 1, am);
       };
 
@@ -999,6 +1031,7 @@ __global__ __launch_bounds__(FUSED_WAVES * 64) void fused_stream_kernel(const Fu
           gather(ntl - 1);
           tile_half(ntl - 1, std::integral_constant<int, 0>{}, am);
           asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+          await_words(ntl - 1);
           sum_finish(ntl - 1, am);
         }
       }

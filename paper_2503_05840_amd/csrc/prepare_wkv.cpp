@@ -319,6 +319,22 @@ extern "C" int slim_pack_weights(const double* W, void* dst_host, int rows, int 
   return SLIM_ERR_DTYPE;
 }
 
+extern "C" int slim_band_kcache(const void* src_host, void* dst_host, int B, int64_t t_stride, int H, int d_k,
+                                int elem_bytes) {
+  if (!src_host || !dst_host) return SLIM_ERR_ARG;
+  if (B < 1 || t_stride < 1 || H < 1 || d_k < 1 || (elem_bytes != 2 && elem_bytes != 4)) return SLIM_ERR_SHAPE;
+  if (t_stride % 32 != 0) return SLIM_ERR_LAYOUT;
+  const size_t row = (size_t)H * d_k * elem_bytes, piece = (size_t)d_k * elem_bytes;
+  const char* src = (const char*)src_host;
+  char* dst = (char*)dst_host;
+  for (int64_t r = 0; r < (int64_t)B * t_stride; ++r) {      // bands never straddle sequences: t_stride % 32 == 0
+    const size_t band = (size_t)(r / 32), rin = (size_t)(r % 32);
+    for (int h = 0; h < H; ++h)
+      std::memcpy(dst + ((band * H + h) * 32 + rin) * piece, src + (size_t)r * row + (size_t)h * piece, piece);
+  }
+  return SLIM_OK;
+}
+
 // RoPE appendix: the one table both rotation directions use.
 extern "C" int slim_rope_table(float* table_host, int T, int d_k, double base) {
   if (!table_host) return SLIM_ERR_ARG;

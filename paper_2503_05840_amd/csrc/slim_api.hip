@@ -228,6 +228,7 @@ extern "C" const char* slim_strerror(int code) {
     case SLIM_ERR_ILLCOND: return "W_K ill-conditioned (rcond < 1e-12); W_KV written but unreliable";
     case SLIM_ERR_LAUNCH: return "HIP allocation or launch error";
     case SLIM_ERR_SEQLEN: return "sequence length outside [1, T]";
+    case SLIM_ERR_LAYOUT: return "banded K-cache: rows per sequence not a multiple of 32, or no kernel reads that layout for this shape / dtype / call";
     case SLIM_ERR_TIMEOUT: return "a wait between workgroups ran out in the latest stream-kernel launch on this workspace; its outputs are NaN";
     default: return "unknown slim status";
   }
@@ -320,6 +321,11 @@ int decode_core(const void* q, const void* Kcache, const void* W_KV, void* out, 
     dev = device_state();
     if (!dev || !stream_kernel_fits(*dev, p.geom, rope != nullptr)) variant = SLIM_VARIANT_GENERIC;
   }
+  const int k_layout = o ? o->k_layout : SLIM_K_ROWMAJOR;
+  if (k_layout != SLIM_K_ROWMAJOR && k_layout != SLIM_K_BANDED) return SLIM_ERR_ARG;
+  if (k_layout == SLIM_K_BANDED &&
+      (t_stride % 32 != 0 || (variant != SLIM_VARIANT_FUSED && variant != SLIM_VARIANT_FUSED_SPLIT)))
+    return SLIM_ERR_LAYOUT;                              // only the stream kernel reads banded caches
   if (variant == SLIM_VARIANT_FUSED || variant == SLIM_VARIANT_FUSED_SPLIT) {
     const FusedGeom& g = p.geom;
     int* ctrl = (int*)(ws + p.off_ctrl);
@@ -327,6 +333,7 @@ int decode_core(const void* q, const void* Kcache, const void* W_KV, void* out, 
     const int zb = (B + per - 1) / per;
     FusedArgs fa{};
     fa.q = (const float*)q; fa.K = (const uint16_t*)Kcache; fa.k_bstride = kb; fa.seq_lens = lens;
+    fa.k_banded = k_layout == SLIM_K_BANDED;
     fa.T = T; fa.B = B; fa.H = H; fa.d = d; fa.d_k = d_k;
     fa.G = g.G; fa.NG = g.NG; fa.gpx = g.gpx; fa.lph = g.lph; fa.lphp = g.lphp; fa.hpu = g.hpu;
     fa.qscale = scale * 1.4426950408889634f;
@@ -454,6 +461,7 @@ extern "C" int vanilla_kv_decode(const void* q, const void* Kcache, const void* 
                                  int B, int H, int T, int d, const slim_opts* o) {
   if (!q || !Kcache || !Vcache || !out) return SLIM_ERR_ARG;
   if (o && o->rope_table) return SLIM_ERR_ARG;        // a vanilla cache stores rotated keys
+  if (o && o->k_layout) return SLIM_ERR_ARG;          // K and V caches are row-major here
   if (H < 1 || d < 1 || d % H != 0) return SLIM_ERR_SHAPE;
   const int d_k = d / H;
   int dtype; long t_stride;
@@ -478,6 +486,7 @@ extern "C" int slim_decode_xcache(const void* q, const void* X, const void* W_K,
                                   const slim_opts* o) {
   if (!q || !X || !W_K || !W_V || !out) return SLIM_ERR_ARG;
   if (o && o->rope_table) return SLIM_ERR_ARG;        // no rotary positions in the X-cache scheme
+  if (o && o->k_layout) return SLIM_ERR_ARG;          // the X-cache is row-major
   if (H < 1 || d_k < 1 || d_model < 1) return SLIM_ERR_SHAPE;
   const int e = H * d_k;
   int dtype; long t_stride;
@@ -596,6 +605,14 @@ int attention_block(bool slim_path, const BlockCall& c, int B, int H, int T, int
   const int zb = (B + 15) / 16;
   const int nmat = slim_path ? 2 : 3;
   const bool fast = variant != SLIM_VARIANT_GENERIC && H * nmat * zb < CTRL_INTS / 2;
+  const int k_layout = o ? o->k_layout : SLIM_K_ROWMAJOR;
+  if (k_layout != SLIM_K_ROWMAJOR && k_layout != SLIM_K_BANDED) return SLIM_ERR_ARG;
+  if (k_layout == SLIM_K_BANDED) {
+    // decided before anything is appended: the decode step inside must be the stream kernel's
+    if (!slim_path) return SLIM_ERR_ARG;
+    DeviceState* dev = device_state();
+    if (!fast || t_stride % 32 != 0 || !dev || !stream_kernel_fits(*dev, p.geom, rope != nullptr)) return SLIM_ERR_LAYOUT;
+  }
   ProjArgs pa{};
   pa.Cpart = (const float*)c.x; pa.outpart = (float*)(ws + bb.off_dpart); pa.counters = (int*)(ws + p.off_ctrl);
   pa.seq_lens = lens; pa.B = B; pa.T = T; pa.H = H; pa.d_k = d_k; pa.rows = d; pa.e = d;
@@ -610,6 +627,7 @@ int attention_block(bool slim_path, const BlockCall& c, int B, int H, int T, int
     pa.Wm[1] = (const uint16_t*)c.W_K; pa.outm[1] = nullptr; pa.role[1] = 2;
     pa.Wm[2] = (const uint16_t*)c.W_V; pa.outm[2] = nullptr; pa.role[2] = 3;
     pa.Kc = (uint16_t*)c.Kcache; pa.Vc = (uint16_t*)c.Vcache; pa.c_bstride = t_stride * d;
+    pa.k_banded = k_layout == SLIM_K_BANDED;
     pa.rope = rope; pa.rotate_k = slim_path ? 0 : 1;
     launch_dense_mfma(pa, st);
   } else {

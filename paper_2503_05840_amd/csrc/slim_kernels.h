@@ -87,6 +87,7 @@ struct ProjArgs {
   int nmat;
   const uint16_t* Wm[3]; float* outm[3]; int role[3];
   uint16_t* Kc; uint16_t* Vc; long c_bstride;
+  int k_banded;                       // Kc is a banded cache (see FusedArgs::k_banded)
   const float* rope; int rotate_k;
 };
 
@@ -94,6 +95,7 @@ struct FusedArgs {
   const float* q;
   const uint16_t* K;
   long k_bstride;
+  int k_banded;                       // 0: [t][d] row-major per sequence; 1: [t / 32][H][32][d_k] (32-row bands, head-major)
   const int32_t* seq_lens;
   int T, B, H, d, d_k;
   int G, NG, gpx, lph, lphp, hpu;

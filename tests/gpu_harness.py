@@ -40,6 +40,12 @@ def head_rel_err(out: np.ndarray, ref: np.ndarray, H: int) -> float:
     return float((num / den).max())
 
 
+def unband(Kb: np.ndarray, H: int) -> np.ndarray:
+    """Banded cache (B, t_stride, d) back to row-major: the inverse of slim_band_kcache, as index shuffling."""
+    B, ts, d = Kb.shape
+    return np.ascontiguousarray(Kb.reshape(B, ts // 32, H, 32, d // H).transpose(0, 1, 3, 2, 4)).reshape(B, ts, d)
+
+
 class KCase:
     """A K-cache problem resident on the device, with its oracle result.
 
@@ -119,13 +125,23 @@ class KCase:
         d.update(kw)
         return d
 
-    def run_slim(self, **kw):
+    def banded_cache(self):
+        """The same cache in the banded layout (bands of 32 rows, head-major inside a band), on the device."""
+        if getattr(self, "K_banded", None) is None:
+            self.K_banded = to_device(binding.slim_band_kcache(binding.to_host(self.K), self.cfg.H))
+        return self.K_banded
+
+    def run_slim(self, banded=False, **kw):
         import torch
         c = self.cfg
         out = torch.full((c.B, c.d), float("nan"), device="cuda", dtype=torch.float32)
         if self.rope_table is not None:
             kw.setdefault("rope_table", self.rope_table)
-        binding.slim_decode(self.q, self.K, self.Wkv, out, c.B, c.H, c.T, c.d, **self._kw(**kw))
+        K = self.K
+        if banded:
+            K = self.banded_cache()
+            kw["k_layout"] = binding.K_BANDED
+        binding.slim_decode(self.q, K, self.Wkv, out, c.B, c.H, c.T, c.d, **self._kw(**kw))
         torch.cuda.synchronize()
         return out.cpu().numpy()
 
@@ -252,14 +268,20 @@ class BlockCase:
         rows = cache[torch.arange(self.cfg.B, device="cuda"), idx]
         return rows.float().cpu().numpy().astype(np.float64)
 
-    def run_slim(self, **kw):
+    def run_slim(self, banded=False, **kw):
         import torch
         c = self.cfg
         y = torch.full((c.B, c.d), float("nan"), device="cuda", dtype=torch.float32)
-        binding.slim_attention_block(self.x, self.Wq, self.Wk, self.Wkv, self.Wo, self.K, y, c.B, c.H, c.T, c.d,
+        K = self.K
+        if banded:       # the cache (with its hole) in the banded layout; the appended row is read back from there
+            K = to_device(binding.slim_band_kcache(binding.to_host(self.K), c.H))
+            kw["k_layout"] = binding.K_BANDED
+        binding.slim_attention_block(self.x, self.Wq, self.Wk, self.Wkv, self.Wo, K, y, c.B, c.H, c.T, c.d,
                                      **self._kw(**kw))
         torch.cuda.synchronize()
-        return y.cpu().numpy(), self._new_rows(self.K)
+        if banded:
+            K = to_device(unband(binding.to_host(K), c.H))
+        return y.cpu().numpy(), self._new_rows(K)
 
     def run_vanilla(self, **kw):
         import torch
