@@ -21,6 +21,7 @@ def test_config1_codellama_16k_full():
     say(f"  slim rel err {e:.3e}")
     assert e <= TOL["bf16"]
     assert np.array_equal(a, k.run_slim())                       # bitwise repeatable
+    assert np.array_equal(a, k.run_slim(banded=True))            # the banded cache: other addresses, same arithmetic
     ev = k.err(k.run_vanilla())
     say(f"  vanilla rel err {ev:.3e}")
     assert ev <= TOL["bf16"]
@@ -50,10 +51,12 @@ def test_config1_with_rotary_keys_full():
 
 def test_config3_whisper_cross_attention_full():
     say("[case] config 3 full size (B=64 H=20 d=1280 T=1500 bf16)")
-    k = KCase(C[3])
-    e = k.err(k.run_slim())
+    k = KCase(C[3], t_stride=1504)                               # whole 32-row bands per sequence
+    a = k.run_slim()
+    e = k.err(a)
     say(f"  slim rel err {e:.3e} over all 64 sequences")
     assert e <= TOL["bf16"]
+    assert np.array_equal(a, k.run_slim(banded=True))
     ev = k.err(k.run_vanilla())
     say(f"  vanilla rel err {ev:.3e}")
     assert ev <= TOL["bf16"]
@@ -90,6 +93,10 @@ def test_config2_phi3_ragged_batch_every_sequence():
     e = k.err(a)
     say(f"  slim rel err {e:.3e} over all {cfg.B} sequences")
     assert e <= TOL["bf16"]
+    ab = k.run_slim(banded=True)
+    eb = k.err(ab)
+    say(f"  slim on the banded cache: rel err {eb:.3e}")
+    assert eb <= TOL["bf16"] and np.array_equal(a, ab)
     ev = k.err(k.run_vanilla())
     say(f"  vanilla rel err {ev:.3e} over all {cfg.B} sequences")
     assert ev <= TOL["bf16"]
