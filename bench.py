@@ -412,7 +412,7 @@ def bench_kcache(args, cfg, torch, binding, synth, with_cpu):
     calibration_copy(args, torch)
     log("[bench] timing slim_decode ...")
     ms_slim = timed(torch, slim, args.steps, args.warmup)
-    ms_slim_rowmajor = timed(torch, slim_rowmajor, args.steps, args.warmup) if banded else None
+    ms_slim_rowmajor = timed(torch, slim_rowmajor, args.steps, args.warmup) if (banded and not args.no_rowmajor_leg) else None
     log("[bench] timing vanilla_kv_decode ...")
     ms_van = timed(torch, vanilla, args.steps, args.warmup)
     # hot numbers (one buffer, may be served by the memory-side cache)
@@ -537,6 +537,8 @@ def main():
                          "with configs[1] nested in the same line)")
     ap.add_argument("--variant", default="auto", choices=["auto", "generic", "fused", "fused_split"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-rowmajor-leg", action="store_true",
+                    help="with the banded layout: do not also time the step on the row-major cache (keeps a profile's per-kernel averages to one layout)")
     ap.add_argument("--k-layout", default="banded", choices=["banded", "rowmajor"],
                     help="layout of the K-cache slim_decode reads (the fast path only; vanilla_kv_decode reads row-major K and V)")
     ap.add_argument("--copies", type=int, default=0, help="K-cache copies to rotate over (0 = enough to exceed 512 MB)")
