@@ -102,8 +102,9 @@ typedef struct slim_opts {
   int            dtype;          /* SLIM_F32 | SLIM_BF16: elements of Kcache/Vcache/X and weights */
   const int32_t* seq_lens;       /* device [B], nullable => every sequence attends T rows;
                                     1 <= seq_lens[b] <= T (ragged batches)                        */
-  const int32_t* seq_lens_host;  /* host copy of seq_lens, nullable; lets the host balance
-                                    work across the chip for ragged batches and is validated      */
+  const int32_t* seq_lens_host;  /* host copy of seq_lens, nullable; only validated (1 <= len <= T,
+                                    SLIM_ERR_SEQLEN): the work is partitioned on the device from
+                                    seq_lens, a call without the host copy is as fast             */
   int64_t        t_stride;       /* cache rows between consecutive sequences, 0 => T              */
   void*          workspace;      /* device scratch, nullable => library-owned, grown on demand
                                     with hipMalloc and kept per device until process exit.  Calls
