@@ -409,7 +409,8 @@ __device__ __forceinline__ void project_work(const ProjArgs& a, int hx, int cs, 
   }
   __syncthreads();
   if (!sm.is_last) return;
-  const bool bad = a.err && __hip_atomic_load(a.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (int)a.launch_id;
+  // (the error word travels with the partial sums: requested here, looked at behind their wait)
+  const int errv = a.err ? __hip_atomic_load(a.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
   for (int v0 = 0; v0 < nb * a.d_k; v0 += NTHR) {
     if (v0 + (tid & ~63) >= nb * a.d_k) break;           // (whole waves: the columns of a pair sit in neighbour lanes)
     const int v = min(v0 + tid, nb * a.d_k - 1);
@@ -429,6 +430,7 @@ __device__ __forceinline__ void project_work(const ProjArgs& a, int hx, int cs, 
       for (int q = 0; q < 8; ++q) if (s0 + q < a.csw) sum += part[q];
     }
     const float other = DENSE ? __shfl_xor(sum, 1) : 0.f;
+    const bool bad = a.err && errv == (int)a.launch_id;
     if (v0 + tid < nb * a.d_k) emit(bl, j, sum, other, bad);               // NaN: the stream kernel gave up waiting
   }
   if (tid == 0) a.counters[bz * nhx + hx] = 0;
@@ -1111,9 +1113,13 @@ __global__ __launch_bounds__(FUSED_WAVES * 64) void fused_stream_kernel(const Fu
     if (wu == 0) {
       unsigned long long since = ~0ull;
       for (;;) {
-        bool ok = true;
-        for (int i = lane; i < (int)gridDim.x; i += 64)
-          ok = ok && (__hip_atomic_load(a.flags + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == a.launch_id);
+        // all flags of a poll in one round trip (a chain of "ok && load" would take one trip per 64 flags)
+        unsigned seen[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          seen[j] = __hip_atomic_load(a.flags + min(lane + 64 * j, (int)gridDim.x - 1), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const bool ok = seen[0] == a.launch_id && seen[1] == a.launch_id && seen[2] == a.launch_id && seen[3] == a.launch_id;
+        static_assert(FUSED_MAX_GRID <= 256, "four flags per lane cover the grid");
         if (__all(ok)) break;
         if (dead || out_of_time(since)) { give_up(); break; }
         __builtin_amdgcn_s_sleep(4);
@@ -1147,7 +1153,7 @@ bool fused_geometry(int B, int H, int T, int d, FusedGeom* g) {
   g->G = (H + g->hpu - 1) / g->hpu;
   g->NT = H <= 16 ? 1 : 2;
   g->NP = FUSED_WAVES;
-  const int cus = 256;
+  const int cus = FUSED_MAX_GRID;
   if (g->G > cus) return false;
   if (g->G <= 32) {
     g->gpx = 32 / g->G;

@@ -59,6 +59,7 @@ void launch_vanilla(int dtype, const float* q, const void* K, const void* V, lon
 constexpr int TILE_ROWS = 32;        // cache rows per wave tile
 constexpr int EXCH_SLOTS = 16;       // ring depth of the score exchange (a power of two >= 2 * FUSED_SLOTS)
 constexpr int FUSED_MAX_B = 1024;    // sequences per call the fast path handles
+constexpr int FUSED_MAX_GRID = 256;  // workgroups of a stream-kernel launch at most (one per compute unit)
 constexpr int FUSED_WAVES = 8;       // waves per workgroup of the stream kernel, each with tiles of its own
 constexpr int FUSED_SLOTS = 2;       // LDS landing slots (8 KB tiles) per wave
 constexpr int FUSED_AHEAD = 2;       // register sets of a wave: one tile being scored, the other in flight
