@@ -1,4 +1,4 @@
-// Device helpers shared by the bf16 kernel files (kernels_bf16.hip, kernels_xcache.hip): vector types,
+// Device helpers shared by the kernel files (kernels_bf16.hip, kernels_xcache.hip, kernels_generic.hip): vector types,
 // the clamped sequence length, the in-register 8 x 8 transposition that turns a lane's block of a
 // row-major tile into MFMA operands, and loop helpers whose register buffers are picked at compile time.
 #pragma once

@@ -11,6 +11,7 @@
 //   vanilla_*     : softmax(.) V_i reading both caches                      (eq. 2; Table 2 "Vanilla")
 //   dense_scores  : (q_i W_K,i^T) X^T for the X-cache scheme                (non-square section, Fig. 4)
 #include "slim_kernels.h"
+#include "device_common.h"
 
 #include <type_traits>
 
@@ -73,13 +74,6 @@ struct BF16 {
   }
 };
 
-__device__ __forceinline__ int seq_len_of(const int32_t* lens, int b, int T) {
-  if (!lens) return T;
-  int n = lens[b];
-  return n < 0 ? 0 : (n > T ? T : n);
-}
-
-constexpr float NEG_INF = -INFINITY;
 
 // ------------------------------------------------------------------------------------------------
 // head_scores: one wave per row; lanes stride over the row in 16-byte vectors, partial dot
