@@ -45,11 +45,15 @@ def test_shape_sweep_matches_oracle(i):
     rope = 10000.0 if i % 4 == 1 else None
     say(f"[case] sweep {i}: B={B} H={H} d_k={d_k} T={T} len_lo={lo} q x{q_scale} rope={rope} "
         f"-> {binding.auto_variant_name(B, H, T, H * d_k, 'bf16')}")
-    k = KCase(cfg, q_scale=q_scale, rope_base=rope)
+    k = KCase(cfg, q_scale=q_scale, rope_base=rope, t_stride=(T + 31) // 32 * 32)    # whole 32-row bands per sequence
+    fast = binding.auto_variant_name(B, H, T, H * d_k, "bf16") == "fused"
     for variant in (binding.VARIANT_AUTO, binding.VARIANT_GENERIC, binding.VARIANT_FUSED_SPLIT):
-        e = k.err(k.run_slim(variant=variant))
+        o = k.run_slim(variant=variant)
+        e = k.err(o)
         say(f"  variant {variant}: {e:.3e}")
         assert e <= TOL["bf16"]
+        if fast and variant != binding.VARIANT_GENERIC:           # the banded cache: same arithmetic, other addresses
+            assert np.array_equal(o, k.run_slim(variant=variant, banded=True))
     assert k.err(k.run_vanilla()) <= TOL["bf16"]
     if i % 5 == 2 and T > 1:
         b = BlockCase(cfg, rope_base=rope, q_gain=q_scale)
@@ -111,7 +115,7 @@ def test_partition_sweep_matches_oracle(i):
     rope = 10000.0 if i % 3 == 0 else None
     say(f"[case] partition sweep {i}: B={B} H={H} d_k={d_k} T={T} len_lo={lo} rope={rope} "
         f"-> {binding.auto_variant_name(B, H, T, H * d_k, 'bf16')}")
-    k = KCase(cfg, q_scale=8.0, rope_base=rope, need_v=False)
+    k = KCase(cfg, q_scale=8.0, rope_base=rope, need_v=False, t_stride=(T + 31) // 32 * 32)
     outs = []
     for variant in (binding.VARIANT_AUTO, binding.VARIANT_FUSED_SPLIT, binding.VARIANT_GENERIC):
         o = k.run_slim(variant=variant)
@@ -120,3 +124,6 @@ def test_partition_sweep_matches_oracle(i):
         assert e <= TOL["bf16"]
         outs.append(o)
     assert np.array_equal(outs[0], k.run_slim())                  # repeatable
+    if binding.auto_variant_name(B, H, T, H * d_k, "bf16") == "fused":
+        assert np.array_equal(outs[0], k.run_slim(banded=True))   # and the same from the banded cache
+        assert np.array_equal(outs[1], k.run_slim(variant=binding.VARIANT_FUSED_SPLIT, banded=True))
