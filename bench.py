@@ -81,7 +81,7 @@ XCACHE_STAGES = ["q_tilde (head_scores on W_K)", "dense_scores", "weighted_sum",
 XCACHE_MFMA_STAGES = ["xq_tilde", "xscores", "xweighted", "project_mfma"]
 
 
-def bench_xcache(args, cfg, torch, binding, synth):
+def bench_xcache(args, cfg, torch, binding, synth, emit=True):
     """configs[4]: the X-cache scheme for projection width e > d_model (absorbed form)."""
     B, H, T, dm, d_k, e = cfg.B, cfg.H, cfg.T, cfg.d, cfg.d_k, cfg.e
     log(f"[bench] building inputs for config {cfg.index} ({cfg.name}) ...")
@@ -124,7 +124,7 @@ def bench_xcache(args, cfg, torch, binding, synth):
     flops = {"xscores": dense, "xweighted": dense, "dense_scores": dense, "weighted_sum": dense}.get(names[dom], 2.0 * B * dm * e)
     achieved = flops / (acc[dom] * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": names[dom], "achieved": round(achieved, 2), "peak": 2500.0, "unit": "TFLOP/s",
-                "frac": round(achieved / 2500.0, 5), "traffic": None, "kernel_ms": round(float(acc[dom]), 5),
+                "frac": round(achieved / 2500.0, 5), "traffic": measured_traffic(cfg.index, names[dom]), "kernel_ms": round(float(acc[dom]), 5),
                 "algorithmic_flops": flops,
                 "stage_ms": {n: round(float(acc[i]), 5) for i, n in enumerate(names)}}
     cpu = None
@@ -158,7 +158,9 @@ def bench_xcache(args, cfg, torch, binding, synth):
         "vanilla_kv_ms_per_step": round(ms_van, 5), "speedup_vs_vanilla_kv": round(ms_van / ms, 3),
         "roofline": roofline, "cpu_baseline": cpu,
     }
-    print(json.dumps(result), flush=True)
+    if emit:
+        print(json.dumps(result), flush=True)
+    return result
 
 
 def bench_ecache_layers(args, cfg, torch, binding, synth):
@@ -585,6 +587,14 @@ def main():
                 "measured_read_stream_gbps", "vanilla_kv_ms_per_step", "speedup_vs_vanilla_kv", "bytes_ratio_vanilla_over_slim",
                 "k_stream_only_ms", "k_stream_only_frac_of_hbm_peak", "merge_projection_ms", "roofline", "config")
         result["other_configs"] = {"configs[1]": {k: extra[k] for k in keep if k in extra}}
+        # and, GPU figures only (a few seconds each), the cross-attention batch and the X-cache config
+        extra = bench_kcache(args, synth.CONFIGS[3], torch, binding, synth, with_cpu=False)
+        result["other_configs"]["configs[3]"] = {k: extra[k] for k in keep if k in extra}
+        saved, args.no_cpu_baseline = args.no_cpu_baseline, True
+        extra = bench_xcache(args, synth.CONFIGS[4], torch, binding, synth, emit=False)
+        args.no_cpu_baseline = saved
+        result["other_configs"]["configs[4]"] = {k: extra[k] for k in ("ms_per_step", "value", "x_cache_gbps", "vanilla_kv_ms_per_step",
+                                                                          "speedup_vs_vanilla_kv", "roofline", "config") if k in extra}
     result["paper_context"] = ("paper reports no measurement; analytical: up to 2x for long context (memory-bound), "
                                "Whisper B=64 1.8x (K-only) / 5.3x (E-cache)")
     print(json.dumps(result), flush=True)
