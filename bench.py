@@ -78,7 +78,8 @@ def calibration_copy(args, torch):
 
 
 XCACHE_STAGES = ["q_tilde (head_scores on W_K)", "dense_scores", "weighted_sum", "combine", "project"]
-XCACHE_MFMA_STAGES = ["xq_tilde", "xscores", "xweighted", "project_mfma"]
+XCACHE_MFMA_STAGES = ["xq_tilde", "xscores", "xweighted", "project_mfma"]     # two passes over X
+XCACHE_ONEPASS_STAGES = ["xq_tilde", "xfused", "project_mfma"]               # d_model <= 1024
 
 
 def bench_xcache(args, cfg, torch, binding, synth, emit=True):
@@ -115,13 +116,14 @@ def bench_xcache(args, cfg, torch, binding, synth, emit=True):
         slim(i, stage_ms=stage)
         acc += np.array(list(stage))
     acc /= args.steps
-    mfma_path = acc[4] == 0.0                      # four launches: the bf16 MFMA kernels; five: the plain ones
-    names = XCACHE_MFMA_STAGES if mfma_path else XCACHE_STAGES
+    # three launches: q~, the one-pass kernel, projection; four: two passes over X; five: the plain kernels
+    names = XCACHE_ONEPASS_STAGES if acc[3] == 0.0 else (XCACHE_MFMA_STAGES if acc[4] == 0.0 else XCACHE_STAGES)
     dom = int(np.argmax(acc[:len(names)]))
     # dense contractions over all heads: priced against the bf16 MFMA peak with the method's own
     # flop counts (the hi + lo split of q~ doubles the MFMA work of the scores; not counted)
     dense = 2.0 * B * H * T * dm
-    flops = {"xscores": dense, "xweighted": dense, "dense_scores": dense, "weighted_sum": dense}.get(names[dom], 2.0 * B * dm * e)
+    flops = {"xscores": dense, "xweighted": dense, "dense_scores": dense, "weighted_sum": dense,
+             "xfused": 2.0 * dense}.get(names[dom], 2.0 * B * dm * e)
     achieved = flops / (acc[dom] * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": names[dom], "achieved": round(achieved, 2), "peak": 2500.0, "unit": "TFLOP/s",
                 "frac": round(achieved / 2500.0, 5), "traffic": measured_traffic(cfg.index, names[dom]), "kernel_ms": round(float(acc[dom]), 5),

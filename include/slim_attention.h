@@ -152,7 +152,8 @@ typedef struct slim_opts {
 #define SLIM_VARIANT_AUTO      0
 #define SLIM_VARIANT_GENERIC   1   /* plain vector-ALU kernels, any supported shape            */
 #define SLIM_VARIANT_FUSED_SPLIT 2 /* as FUSED, but the merge + projection always runs as a launch of
-                                      its own                                                  */
+                                      its own; slim_decode_xcache: scores and weighted sum as two
+                                      passes over X even where the one-pass kernel applies     */
 #define SLIM_VARIANT_FUSED     3   /* bf16, H <= 32, d_k <= 128: single pass over K with the weighted
                                       sum and the projection on MFMA (one launch when B <= 16, else
                                       two); falls back to GENERIC when the shape does not qualify */

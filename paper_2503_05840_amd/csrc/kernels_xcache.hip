@@ -410,6 +410,223 @@ __global__ __launch_bounds__(512) void xweighted_kernel(const float* S, const ui
   }
 }
 
+
+// ------------------------------------------------------------------------------------------------
+// One pass over X for 512 <= d_model <= 1024: scores, softmax numerators and the weighted sum of one
+// (sequence, context split, group of 32 heads) in one kernel, so X leaves memory once per head group,
+// no score matrix is written, and the exponentials of a row are computed once instead of once per
+// column block.  The accumulators (32 heads x d_model fp32 = 128 KB at 1024 columns) stay in the
+// workgroup's registers for its whole row range, which is why the COLUMNS are split over the 8 waves
+// (wave w owns columns [128 w, 128 w + 128): its slice of q~ as resident B operands, its 32 x 128 slice
+// of every row tile, its 32 x 128 accumulator block) and the waves meet twice per 32-row tile in LDS --
+// the same exchange of numerators between column owners as in the K-cache stream kernel, but inside
+// one workgroup, with barriers:
+//   1. park the slice in LDS (row-padded), read it back in A-operand order, partial scores of all 32
+//      heads over the wave's columns on MFMA (query hi + lo: 32 MFMAs), partials to LDS;  -- barrier --
+//   2. wave w sums the partials of heads 4w .. 4w+3 over the column owners (lane = row), keeps those
+//      heads' running reference and sum of weights, writes bf16 numerators and the rescale factors;
+//      -- barrier --
+//   3. every wave rescales if a reference moved, transposes its slice in registers and adds
+//      P^T X on MFMA (16 MFMAs).
+// Rows are not split over the waves, so nothing is merged at the end: a wave writes its columns of the
+// partial straight from its registers.  grid (context splits, head groups, B): blockIdx.x is the split, so
+// with 8 splits the head groups that read the same rows run on the same XCD and share them in its L2.
+// ------------------------------------------------------------------------------------------------
+// max over the 32 lanes that share lane / 32: four DPP steps inside the 16-lane row (lane ^ 1, lane ^ 2,
+// the other quad of the 8-lane half, the other half of the row), then the row 16 lanes away by a register swap
+template <int CTRL>
+__device__ __forceinline__ float dpp_max(float v) {
+  return fmaxf(v, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true)));
+}
+__device__ __forceinline__ float max_over_32(float v) {
+  v = dpp_max<0xB1>(v);
+  v = dpp_max<0x4E>(v);
+  v = dpp_max<0x141>(v);
+  v = dpp_max<0x140>(v);
+  const unsigned u = __float_as_uint(v);
+  const auto sw = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  return fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+}
+
+constexpr int XF_PITCH = 272;            // bytes per parked row: 256 + 16 of padding
+constexpr int XF_RED_HS = 36;            // floats per head row of a wave's partial scores (32 rows + padding that keeps 16-byte stores)
+constexpr int XF_P_HS = 40;              // bf16 per head row of the numerators (32 rows + padding)
+
+__global__ __launch_bounds__(512) void xfused_kernel(const uint16_t* qt, const uint16_t* X, long x_bstride,
+                                                     const int32_t* seq_lens, int T, int B, int H, int dm, int nsplit,
+                                                     float* Cpart, float* mpart, float* lpart) {
+  constexpr int NW = 8, NT = 2;
+  __shared__ __align__(16) unsigned char slot[NW][32 * XF_PITCH];
+  __shared__ __align__(16) float red[NW][32][XF_RED_HS];
+  __shared__ __align__(16) uint16_t P_s[32][XF_P_HS];
+  __shared__ float alpha_s[32];
+  const int s = blockIdx.x, hg = blockIdx.y, b = blockIdx.z;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int idx = lane & 15, rg = lane >> 4;           // column group / row group of the register tile
+  const int n = idx, kg = rg;                          // MFMA: N index (head) or M index (row), k group
+  const int ncb = dm / 128;                            // column owners: waves 0 .. ncb - 1
+  const bool has_cols = w < ncb;
+  const int len = seq_len_of(seq_lens, b, T);
+  const int rows_per = ((len + nsplit - 1) / nsplit + 31) / 32 * 32;
+  const int r_lo = s * rows_per, r_hi = min(len, r_lo + rows_per);
+  const int pid = b * nsplit + s;
+  const int ntile = r_lo < r_hi ? (r_hi - r_lo + 31) / 32 : 0;
+  const int NHT = (H + 15) / 16;
+
+  // q~ of the group's 32 heads over this wave's columns, hi + lo, resident as B operands
+  u32x4 bqh[NT][4], bql[NT][4];
+  {
+    const size_t lo_off = (size_t)B * NHT * 16 * dm;
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      const int ht = min(hg * NT + t, NHT - 1);        // (a tile past the last one repeats it; its heads are masked)
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        const uint16_t* src = qt + ((((size_t)b * NHT + ht) * (dm / 32) + (size_t)((has_cols ? w : 0) * 4 + ks)) * 64 + lane) * 8;
+        bqh[t][ks] = *reinterpret_cast<const u32x4*>(src);
+        bql[t][ks] = *reinterpret_cast<const u32x4*>(src + lo_off);
+      }
+    }
+  }
+  const char* Xb = reinterpret_cast<const char*>(X + (size_t)b * x_bstride + (has_cols ? w * 128 : 0) + idx * 8);
+  const unsigned pitchB = (unsigned)dm * 2u;
+  // (rows past the end re-read the last row: finite values that meet a zero weight)
+  auto load_tile = [&](u32x4 (&t)[8], int r0) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const unsigned off = __umul24((unsigned)max(min(r0 + rg * 8 + j, len - 1), 0), pitchB);
+      t[j] = *reinterpret_cast<const u32x4*>(Xb + off);
+    }
+  };
+  f32x4 acc[8][NT];
+#pragma unroll
+  for (int t = 0; t < NT; ++t)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+  // softmax state of the heads this wave owns: lane (r = lane % 32, hp = lane / 32) looks after row r of
+  // heads 4 w + 2 hp + {0, 1} of the group; m is the same in all 32 lanes, l is the lane's own share
+  const int r = lane & 31, hp = lane >> 5;
+  float m[2] = {NEG_INF, NEG_INF}, l[2] = {0.f, 0.f};
+
+  u32x4 xt[1][8];                                      // (one set: it is free again as soon as the tile is parked and transposed)
+  auto tile_row = [&](int k) { return r_lo + 32 * min(k, max(ntile - 1, 0)); };
+  load_tile(xt[0], tile_row(0));
+  char* const sl = reinterpret_cast<char*>(slot[w]);
+
+  u32x4 (&cur)[8] = xt[0];
+  u32x4 am[8];                                         // the parked tile, transposed: A operands of its weighted sum
+  // 1. the slice into LDS; partial scores of the 32 heads over this wave's 128 columns
+  auto scores = [&](int k) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) *reinterpret_cast<u32x4*>(sl + (rg * 8 + j) * XF_PITCH + idx * 16) = cur[j];
+    f32x4 sp[2][NT];
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+      for (int t = 0; t < NT; ++t) sp[mt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt) {
+        const bf16x8 a8 = *reinterpret_cast<const bf16x8*>(sl + (mt * 16 + n) * XF_PITCH + (ks * 4 + kg) * 16);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+          sp[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a8, __builtin_bit_cast(bf16x8, bqh[t][ks]), sp[mt][t], 0, 0, 0);
+          sp[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a8, __builtin_bit_cast(bf16x8, bql[t][ks]), sp[mt][t], 0, 0, 0);
+        }
+      }
+    if (has_cols) {                                    // D: column n = head, rows kg*4 + i
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int t = 0; t < NT; ++t) *reinterpret_cast<f32x4*>(&red[w][t * 16 + n][mt * 16 + kg * 4]) = sp[mt][t];
+    }
+  };
+  // 2. this wave's four heads: sum over the column owners, reference, numerators
+  auto numerators = [&](int k) {
+    const int r0 = r_lo + 32 * k;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int hl = 4 * w + 2 * hp + i;
+      float part[NW];                                  // (all reads issued before the first is used)
+#pragma unroll
+      for (int ws = 0; ws < NW; ++ws) part[ws] = red[min(ws, ncb - 1)][hl][r];
+      float sc = 0.f;
+#pragma unroll
+      for (int ws = 0; ws < NW; ++ws) sc += ws < ncb ? part[ws] : 0.f;
+      const bool live = (hg * 32 + hl < H) && (r0 + r < r_hi);
+      const float x = live ? sc : NEG_INF;
+      const float tmax = max_over_32(x);
+      // (the reference moves only when the maximum has grown by more than XW_SLACK, as in xweighted_kernel)
+      const float mn = (tmax > m[i] + XW_SLACK) ? tmax : m[i];
+      const float ref = (mn == NEG_INF) ? 0.f : mn;
+      const float alpha = (m[i] == NEG_INF) ? 1.f : __builtin_amdgcn_exp2f(m[i] - ref);   // (nothing accumulated yet: nothing to rescale)
+      const __bf16 pw = (__bf16)__builtin_amdgcn_exp2f(x - ref);
+      l[i] = l[i] * alpha + (float)pw;                 // the weight as the MFMA will see it
+      m[i] = mn;
+      P_s[hl][r] = __builtin_bit_cast(uint16_t, pw);
+      if (r == 0) alpha_s[hl] = alpha;
+    }
+  };
+  // 3. rescale where a reference moved; P^T X for this wave's columns (the tile in am, its numerators in LDS)
+  auto weighted_sum = [&]() {
+    bf16x8 pb[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      const float al = alpha_s[t * 16 + n];
+      pb[t] = *reinterpret_cast<const bf16x8*>(&P_s[t * 16 + n][kg * 8]);
+      if (__any(al != 1.f)) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i][t] *= al;
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const bf16x8 av = __builtin_bit_cast(bf16x8, am[i]);
+#pragma unroll
+      for (int t = 0; t < NT; ++t) acc[i][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, pb[t], acc[i][t], 0, 0, 0);
+    }
+  };
+  // (Letting the weighted sum of tile k - 1 share a barrier interval with the scores of tile k, the two waves
+  //  of a SIMD in opposite order, was measured: 68 against 58 us on the T5-11B-shaped configuration.)
+  for (int k = 0; k < ntile; ++k) {
+    scores(k);
+    transpose8x8(cur, am);                             // (cur is parked: its registers go to the next tile)
+    load_tile(cur, tile_row(k + 1));                   // past the end: the last tile again, unused
+    lds_barrier();
+    numerators(k);
+    lds_barrier();
+    weighted_sum();
+  }
+
+  // ---- the partial of this (sequence, split): every wave its own columns, the owners their heads' (m, l)
+  if (has_cols) {
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      const int h = hg * 32 + t * 16 + n;
+      if (h >= H) continue;
+      float* dst = Cpart + ((size_t)pid * H + h) * dm + w * 128;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {                    // accumulator row i: column group rg*4 + i of the block
+        float* d8 = dst + (rg * 4 + i) * 8;
+        *reinterpret_cast<f32x4*>(d8) = f32x4{acc[0][t][i], acc[1][t][i], acc[2][t][i], acc[3][t][i]};
+        *reinterpret_cast<f32x4*>(d8 + 4) = f32x4{acc[4][t][i], acc[5][t][i], acc[6][t][i], acc[7][t][i]};
+      }
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    float lt = l[i];
+#pragma unroll
+    for (int o = 1; o < 32; o <<= 1) lt += __shfl_xor(lt, o);
+    const int h = hg * 32 + 4 * w + 2 * hp + i;
+    if (r == 0 && h < H) {
+      mpart[(size_t)pid * H + h] = m[i];
+      lpart[(size_t)pid * H + h] = lt;
+    }
+  }
+}
+
 }  // namespace
 
 // Head tiles in flight for H heads: 1, 2, 4 or 8.
@@ -432,6 +649,25 @@ int xcache_splits(int B, int H, int T, int d_model) {
   if (s > cap) s = cap;
   if (s > PROJ_MAX_PARTS) s = PROJ_MAX_PARTS;
   return s < 1 ? 1 : s;
+}
+
+bool xfused_ok(int d_model) { return d_model % 128 == 0 && d_model >= 512 && d_model <= 1024; }
+
+int xfused_splits(int B, int H, int T) {
+  // one workgroup per (split, 32 heads, sequence): split the context as far as it takes to fill the chip
+  const int per = B * ((H + 31) / 32);
+  int s = (256 + per - 1) / per;
+  const int cap = (T + 255) / 256;
+  if (s > cap) s = cap;
+  if (s > PROJ_MAX_PARTS) s = PROJ_MAX_PARTS;
+  return s < 1 ? 1 : s;
+}
+
+void launch_xfused(const float* qt, const void* X, long x_bstride, const int32_t* seq_lens, int T, int H, int d_model,
+                   int nsplit, float* Cpart, float* mpart, float* lpart, int B, hipStream_t st) {
+  dim3 grid(nsplit, (H + 31) / 32, B);
+  hipLaunchKernelGGL(xfused_kernel, grid, dim3(512), 0, st, (const uint16_t*)qt, (const uint16_t*)X, x_bstride, seq_lens, T, B, H,
+                     d_model, nsplit, Cpart, mpart, lpart);
 }
 
 void launch_xq_tilde(const float* q, const void* Wk, float* qt, int B, int H, int d_k, int d_model, int e,

@@ -20,7 +20,8 @@ inline size_t up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
 struct Plan {
   int nsplit = 1;      // context splits of the weighted-sum step
   int nsplit_v = 1;    // context splits of the vanilla kernel
-  int nsplit_x = 1;    // context splits of the X-cache MFMA path
+  int nsplit_x = 1;    // context splits of the X-cache MFMA path (two passes over X)
+  int nsplit_xf = 0;   // context splits of the one-pass X-cache kernel (0: the shape does not take it)
   size_t off_S = 0, off_Cpart = 0, off_m = 0, off_l = 0, off_Cn = 0, off_qt = 0;
   size_t off_vacc = 0, off_vm = 0, off_vl = 0;
   size_t off_exch = 0, off_outpart = 0, off_ctrl = 0;   // bf16 fast path
@@ -51,7 +52,9 @@ Plan make_plan(int B, int H, int T, int width, int e) {
   p.off_ctrl = o;    o += up(sizeof(int) * CTRL_INTS);
   p.fused_ok = (width == e) && fused_geometry(B, H, T, width, &p.geom);
   p.nsplit_x = xcache_splits(B, H, T, width);
+  p.nsplit_xf = xfused_ok(width) ? xfused_splits(B, H, T) : 0;
   size_t nparts = (size_t)B * (p.nsplit > p.nsplit_x ? p.nsplit : p.nsplit_x);
+  if ((size_t)B * p.nsplit_xf > nparts) nparts = (size_t)B * p.nsplit_xf;
   if (p.fused_ok && (size_t)p.geom.nparts > nparts) nparts = p.geom.nparts;
   if (p.fused_ok && (size_t)B * 4 > nparts && fused_by_sequence(p.geom, B, false)) nparts = (size_t)B * 4;
   p.csw = proj_row_splits(H, width, e, B);
@@ -517,16 +520,24 @@ extern "C" int slim_decode_xcache(const void* q, const void* X, const void* W_K,
     const int zb = (B + per - 1) / per;
     launch_xq_tilde((const float*)q, W_K, qt, B, H, d_k, d_model, e, scale * 1.4426950408889634f, ctrl, H * zb, st);
     tm.mark();
-    launch_xscores(qt, X, xb, lens, T, H, d_model, S, B, st);
-    tm.mark();
-    launch_xweighted(S, X, xb, lens, T, H, d_model, p.nsplit_x, Cpart, mpart, lpart, B, st);
-    tm.mark();
+    int nsplit = p.nsplit_x;
+    if (p.nsplit_xf > 0 && req != SLIM_VARIANT_FUSED_SPLIT) {
+      // d_model <= 1024: scores, numerators and weighted sum in one pass over X
+      nsplit = p.nsplit_xf;
+      launch_xfused(qt, X, xb, lens, T, H, d_model, nsplit, Cpart, mpart, lpart, B, st);
+      tm.mark();
+    } else {
+      launch_xscores(qt, X, xb, lens, T, H, d_model, S, B, st);
+      tm.mark();
+      launch_xweighted(S, X, xb, lens, T, H, d_model, nsplit, Cpart, mpart, lpart, B, st);
+      tm.mark();
+    }
     ProjArgs pa{};
     pa.Cpart = Cpart; pa.mpart = mpart; pa.lpart = lpart; pa.W = (const uint16_t*)W_V;
     pa.out = (float*)out; pa.outpart = (float*)(ws + p.off_outpart); pa.counters = ctrl;
     pa.err = nullptr; pa.launch_id = 0; pa.seq_lens = lens;
     pa.B = B; pa.T = T; pa.H = H; pa.d_k = d_k; pa.rows = d_model; pa.e = e;
-    pa.NG = 0; pa.nsplit = p.nsplit_x; pa.mode = 1; pa.mscale = 1.0f;
+    pa.NG = 0; pa.nsplit = nsplit; pa.mode = 1; pa.mscale = 1.0f;
     pa.csw = proj_row_splits(H, d_model, e, B);
     launch_project_mfma(pa, st);
     tm.mark();

@@ -115,6 +115,10 @@ def test_config4_t5_xcache_every_sequence():
     eg = x.err(g)
     say(f"  plain kernels rel err {eg:.3e}")
     assert eg <= TOL["bf16"]
+    e2 = x.err(x.run(variant=binding.VARIANT_FUSED_SPLIT))
+    say(f"  two passes over X rel err {e2:.3e}")
+    assert e2 <= TOL["bf16"]
+    assert np.array_equal(out, x.run())                          # repeatable
 
 
 def test_config4_t5_xcache_sampled():

@@ -93,7 +93,7 @@ def test_xcache_shape_sweep_matches_oracle(i):
     q_scale = [1.0, 2.0, 4.0][i % 3]
     say(f"[case] xcache sweep {i}: B={B} H={H} d_model={dm} d_k={d_k} T={T} lens={None if lens is None else lens.tolist()} q x{q_scale}")
     x = XCase(cfg, q_scale=q_scale, lens=lens)
-    for variant in (binding.VARIANT_AUTO, binding.VARIANT_GENERIC):
+    for variant in (binding.VARIANT_AUTO, binding.VARIANT_GENERIC, binding.VARIANT_FUSED_SPLIT):   # (FUSED_SPLIT: two passes over X)
         e = x.err(x.run(variant=variant))
         say(f"  variant {variant}: {e:.3e}")
         assert e <= TOL["bf16"]
