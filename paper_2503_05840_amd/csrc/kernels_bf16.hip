@@ -450,18 +450,17 @@ __global__ __launch_bounds__(512) void project_mfma_kernel(const ProjArgs a) {
 // fused stream kernel
 //
 // A workgroup is FUSED_WAVES waves that all do the same work on tiles of their own.  In step k a wave
-//   1. requests all heads' words of its tile k-1 (published by the same wave of every workgroup of the
-//      group one step earlier),
-//   2. scores tile k (in registers since two steps ago): scores of its unit's heads, softmax numerators
-//      against the head's running maximum (bf16, the precision the MFMA consumes anyway), parks the
-//      tile in one of its two LDS slots, publishes {tag, running max, 4 numerators} words, and requests
-//      tile k+2 into the registers that have just become free,
-//   3. takes tile k-1 out of its LDS slot, rescales its accumulators when a maximum moved and does the
-//      MFMA contraction with the words gathered in 1.
-// Scoring is the long part of a step and every wave does it, so all eight waves of a compute unit share
-// it; the gather travels while the wave scores, and because it is requested before the next tile (a
-// wave's vector-memory operations complete in issue order) it only ever waits for tiles that were
-// requested a whole step earlier.  A wave never waits for another wave of its workgroup.
+//   1. parks tile k (in registers since two steps ago) in one of its two LDS slots and scores it from
+//      there on MFMA (with rotary keys: on the vector ALU from the registers, before parking): scores of
+//      its unit's heads, softmax numerators against the head's running maximum (bf16, the precision the
+//      MFMA consumes anyway); publishes {tag, running max, 4 numerators} words,
+//   2. requests all heads' words of its tile k-1 (published by the same wave of every workgroup of the
+//      group one step earlier) and, behind them, tile k+2 into the registers that became free in 1,
+//   3. takes tile k-1 out of its LDS slot while the words travel, waits for them (a wave's vector-memory
+//      operations complete in issue order: the wait lets exactly the loads of tile k+2 stay in flight),
+//      rescales its accumulators when a maximum moved and does the MFMA contraction.
+// Every wave does both halves, so all eight waves of a compute unit share the scoring work and the
+// loads.  A wave never waits for another wave of its workgroup.
 // ------------------------------------------------------------------------------------------------
 //
 // ROPE (RoPE appendix, option 1): the cache holds raw keys and row t sits at position t.  The
@@ -1209,7 +1208,7 @@ int fused_blocks_per_cu(const FusedGeom& g, bool rope) {
 }
 
 // By-sequence partition: how many equal shares to cut every sequence into so that the shares fill
-// the wave-pair slots evenly (1..4), or 0 to keep the balanced by-context partition.  Ragged
+// the wave slots (groups x waves) evenly (1..4), or 0 to keep the balanced by-context partition.  Ragged
 // batches qualify only with many shares per slot.
 int fused_by_sequence(const FusedGeom& g, int B, bool ragged) {
   const long slots = (long)g.NG * FUSED_WAVES;
