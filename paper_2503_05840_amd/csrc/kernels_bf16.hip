@@ -2,8 +2,9 @@
 //
 //   fused_stream_kernel : one pass over the K-cache.  Softmax arguments (eq. 2), online softmax
 //                         and the full-width weighted sum [softmax(.) K] of eq. 7 option 2, the
-//                         latter as one MFMA contraction for all heads ("all heads in parallel as
-//                         a single matrix-matrix multiplication").  K is read from HBM once.
+//                         latter as one MFMA contraction for all heads at once (the text under
+//                         eq. 7 points out that the heads need not be handled one by one).  K is
+//                         read from HBM once.
 //   project_mfma_kernel : log-sum-exp merge of the context splits and the per-head product with
 //                         W_KV,i (eq. 7 option 2, second factor) on MFMA; W_KV is read once.
 //
