@@ -96,8 +96,12 @@ def bench_xcache(args, cfg, torch, binding, synth, emit=True):
     Wv = to_device(binding.slim_pack_weights(p.w.W_V, cfg.dtype))
     out = torch.zeros((B, e), device="cuda", dtype=torch.float32)
 
+    # --variant fused_split: scores and weighted sum as two passes over X; generic: the plain kernels
+    variant = {"auto": binding.VARIANT_AUTO, "generic": binding.VARIANT_GENERIC,
+               "fused": binding.VARIANT_FUSED, "fused_split": binding.VARIANT_FUSED_SPLIT}[args.variant]
+
     def slim(i, **extra):
-        binding.slim_decode_xcache(q, Xs[i % ncopies], Wk, Wv, out, B, H, T, dm, d_k, dtype=cfg.dtype, **extra)
+        binding.slim_decode_xcache(q, Xs[i % ncopies], Wk, Wv, out, B, H, T, dm, d_k, dtype=cfg.dtype, variant=variant, **extra)
 
     calibration_copy(args, torch)
     log("[bench] timing slim_decode_xcache ...")
