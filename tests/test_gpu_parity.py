@@ -180,6 +180,10 @@ def test_xcache_decode_matches_oracle(name, cfg):
     ("xcache-peaky", synth.scaled(C[4], B=2, H=32, d=1024, d_k=64, T=1100), 8.0, None),
     ("xcache-ragged-padded-heads", synth.scaled(C[4], B=3, H=24, d=512, d_k=32, T=900), 4.0, [900, 1, 333]),
     ("xcache-two-column-blocks", synth.scaled(C[4], B=1, H=8, d=1280, d_k=32, T=200), 1.0, None),
+    # the one-pass kernel's corners: one row, one row more than a tile, fewer column owners than waves, five heads
+    ("xcache-onepass-one-row", synth.scaled(C[4], B=2, H=5, d=512, d_k=32, T=1), 2.0, None),
+    ("xcache-onepass-tile-plus-one", synth.scaled(C[4], B=3, H=5, d=640, d_k=32, T=33), 2.0, [33, 1, 32]),
+    ("xcache-onepass-many-splits", synth.scaled(C[4], B=1, H=40, d=768, d_k=32, T=2500), 1.0, None),
     # the encoder-decoder section's option 2: the cross-attention K and V of a Whisper-large-shaped layer
     # (square projections, 20 heads: 16 heads per score workgroup, a padded head tile) from the encoder output
     ("ecache-whisper-shape", synth.scaled(C[3], kind="xcache", B=3, T=333), 4.0, None),
