@@ -40,49 +40,87 @@ __device__ __forceinline__ void lds_barrier() {
 // so that a wave reads one operand as 1 KB of consecutive bytes.
 // grid (H / XQ_HEADS, d_model / 128, batch chunks of 16); a wave owns 16 rows c of W_K for XQ_HEADS heads.
 // MFMA: A = W_K block (M = 16 rows c, K = the head's columns j), B = q^T (N = sequences) as hi + lo.
+// The 8 waves share their B operands: the workgroup fetches its slice of q once (consecutive threads on
+// consecutive floats), splits it and lays the operands out in LDS.  (Fetched per wave in operand order --
+// a lane per sequence, rows of q 4 e bytes apart -- q cost more time than W_K: 16 lines per instruction that
+// fall on few L2 channels, and every workgroup of a head asks for the same ones.)
 // ------------------------------------------------------------------------------------------------
 constexpr int XQ_HEADS = 4;
+constexpr int XQ_QROW = 16 * 16 + 16;    // bytes per (head, k-step, k-group) of B operands in LDS: 16 sequences x 16 bytes + padding
 
 __global__ __launch_bounds__(512) void xq_tilde_kernel(const float* q, const uint16_t* Wk, uint16_t* qt, int B,
                                                        int H, int d_k, int dm, int e, float scale, int* counters,
                                                        int ncounters) {
+  __shared__ __align__(16) unsigned char qs[2][XQ_HEADS * 4 * 4 * XQ_QROW];   // hi, lo
   // (the arrival counters of the projection that ends this call start at 0)
   if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0)
     for (int i = threadIdx.x; i < ncounters; i += 512) counters[i] = 0;
   const int bbase = blockIdx.z * 16;
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int n = lane & 15, kq = lane >> 4;
-  const int c0 = (blockIdx.y * 8 + w) * 16;
-  if (c0 >= dm) return;
+  const int c0 = (blockIdx.y * 8 + w) * 16;            // (d_model is a multiple of 128: every wave has rows)
+  const int h0 = blockIdx.x * XQ_HEADS;
   const int b = bbase + n;
   const int nks = d_k / 32;                            // 1..4 k-steps per head
-  // XQ_HEADS heads per wave: all their loads of W_K are issued before the first MFMA
+  // all loads of W_K are issued before anything else: they come from HBM
   u32x4 av[XQ_HEADS][4];
 #pragma unroll
   for (int hh = 0; hh < XQ_HEADS; ++hh) {
-    const int h = min(blockIdx.x * XQ_HEADS + hh, H - 1);
+    const int h = min(h0 + hh, H - 1);
     const uint16_t* wrow = Wk + (size_t)(c0 + n) * e + (size_t)h * d_k + kq * 8;
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) av[hh][ks] = *reinterpret_cast<const u32x4*>(wrow + min(ks, nks - 1) * 32);
   }
+  // q of the workgroup's heads and sequences: 16 x XQ_HEADS d_k floats = nks pieces of 4 floats per thread
+  {
+    const int upq = d_k / 4;                           // pieces per head
+    f32x4 qraw[4];
+    int off[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      qraw[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+      off[i] = 0;
+      if (i < nks) {
+        const int g = i * 512 + tid, bl = g / d_k, rem = g - bl * d_k, hh = rem / upq, j0 = (rem - hh * upq) * 4;
+        // (heads past H and sequences past B: zeros)
+        if (bbase + bl < B && h0 + hh < H)
+          qraw[i] = *reinterpret_cast<const f32x4*>(q + (size_t)(bbase + bl) * e + (size_t)(h0 + hh) * d_k + j0);
+        off[i] = ((hh * 4 + (j0 >> 5)) * 4 + ((j0 & 31) >> 3)) * XQ_QROW + bl * 16 + (j0 & 7) * 2;
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if (i < nks) {
+        unsigned hw[2], lw[2];
+#pragma unroll
+        for (int r = 0; r < 4; r += 2) {
+          const float x0 = qraw[i][r], x1 = qraw[i][r + 1];
+          const __bf16 hb0 = (__bf16)x0, hb1 = (__bf16)x1;
+          const __bf16 l0 = (__bf16)(x0 - (float)hb0), l1 = (__bf16)(x1 - (float)hb1);
+          hw[r / 2] = (unsigned)__builtin_bit_cast(uint16_t, hb0) | ((unsigned)__builtin_bit_cast(uint16_t, hb1) << 16);
+          lw[r / 2] = (unsigned)__builtin_bit_cast(uint16_t, l0) | ((unsigned)__builtin_bit_cast(uint16_t, l1) << 16);
+        }
+        *reinterpret_cast<uint2*>(&qs[0][off[i]]) = make_uint2(hw[0], hw[1]);
+        *reinterpret_cast<uint2*>(&qs[1][off[i]]) = make_uint2(lw[0], lw[1]);
+      }
+    }
+  }
+  __syncthreads();
 #pragma unroll
   for (int hh = 0; hh < XQ_HEADS; ++hh) {
-    const int h = blockIdx.x * XQ_HEADS + hh;
+    const int h = h0 + hh;
     if (h >= H) break;
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
-      if (ks >= nks) break;
-      float x[8];
-      const float* qsrc = q + (size_t)min(b, B - 1) * e + (size_t)h * d_k + ks * 32 + kq * 8;
-      const f32x4 lo4 = *reinterpret_cast<const f32x4*>(qsrc), hi4 = *reinterpret_cast<const f32x4*>(qsrc + 4);
-#pragma unroll
-      for (int j = 0; j < 4; ++j) { x[j] = (b < B) ? lo4[j] : 0.f; x[4 + j] = (b < B) ? hi4[j] : 0.f; }
-      bf16x8 hi, lo;
-      split_hi_lo(x, hi, lo);
-      const bf16x8 a8 = __builtin_bit_cast(bf16x8, av[hh][ks]);
-      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a8, hi, acc, 0, 0, 0);
-      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a8, lo, acc, 0, 0, 0);
+      if (ks < nks) {
+        const int qo = ((hh * 4 + ks) * 4 + kq) * XQ_QROW + n * 16;
+        const bf16x8 hi = *reinterpret_cast<const bf16x8*>(&qs[0][qo]);
+        const bf16x8 lo = *reinterpret_cast<const bf16x8*>(&qs[1][qo]);
+        const bf16x8 a8 = __builtin_bit_cast(bf16x8, av[hh][ks]);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a8, hi, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a8, lo, acc, 0, 0, 0);
+      }
     }
     // D: column n = sequence, rows kq*4 + r = c0 + ...; stored scaled, as bf16 hi and lo halves
     if (b < B) {
