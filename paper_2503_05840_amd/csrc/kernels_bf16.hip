@@ -22,7 +22,8 @@
 // an error word instead of hanging.
 //
 // Register tile.  A wave owns 32 rows x 128 columns: lane l loads 16 bytes (8 columns) of 8 rows,
-// column group l%16, row group l/16.  Both MFMA contractions take their operands from the tile's LDS
+// column group l%16; the rows are 4 j + l/16 (one load instruction = four consecutive rows) or, with
+// rotary keys, 8 (l/16) + j.  Both MFMA contractions take their operands from the tile's LDS
 // copy.  Scores (v_mfma_f32_16x16x32_bf16, contraction over columns): A = 16 rows x 32 columns read
 // straight in operand layout, B = the unit's queries.  Weighted sum (contraction over rows): a lane reads
 // its 8 x 8 block back and transposes it in registers (v_perm_b32) into 8 A-operands, one per column:
@@ -552,11 +553,17 @@ __global__ __launch_bounds__(FUSED_WAVES * 64) void fused_stream_kernel(const Fu
   // chunk of padding per row (17 chunks), so that all three access patterns are free of bank conflicts
   // and each is one per-lane base plus compile-time offsets: the store and the read for the weighted sum
   // (the 16 chunks of a row) and the A operands of the score MFMA (one chunk of 16 consecutive rows).
-  //   store of row rg*8 + j, chunk idx ........................ wpos + j * ROW_PITCH
+  //   store of register j (row j*RJ + rg*RR), chunk idx ....... wpos + j * RJ * ROW_PITCH
   //   score A operand, rows mt*16 + idx, chunk ks*4 + rg ...... spos + mt * 16 * ROW_PITCH + ks * 64
   //   sum, rows jh*16 + kg*4 + jl, chunk idx (no rotary keys) . ppos + (jh * 16 + jl) * ROW_PITCH
   constexpr unsigned ROW_PITCH = 272, SLOT_PITCH = TILE_ROWS * ROW_PITCH;
-  const unsigned wpos = (unsigned)(rg * 8) * ROW_PITCH + (unsigned)idx * 16u;
+  // Which row of the tile a lane's register j holds: j * RJ + rg * RR.  With rotary keys the scores are taken
+  // from the registers and a lane needs eight consecutive positions (rows rg*8 + j).  Otherwise the registers
+  // only carry the tile to its slot, and row j*4 + rg makes one load instruction cover four consecutive rows:
+  // in the banded cache 4 d_k x 2 contiguous bytes, whole cache lines that no other instruction touches
+  // (with rows eight apart and d_k = 96, every second line is shared by two instructions).
+  constexpr int RJ = ROPE ? 1 : 4, RR = ROPE ? 8 : 1;
+  const unsigned wpos = (unsigned)(rg * RR) * ROW_PITCH + (unsigned)idx * 16u;
   const unsigned spos = (unsigned)idx * ROW_PITCH + (unsigned)rg * 16u;
   const unsigned ppos = (unsigned)(kg * 4) * ROW_PITCH + (unsigned)idx * 16u;
   // Scores on MFMA (no rotary keys): column n = 2 * (head in unit) + {0: query hi, 1: query lo}; the lane
@@ -690,7 +697,7 @@ __global__ __launch_bounds__(FUSED_WAVES * 64) void fused_stream_kernel(const Fu
       const int lane_head = col_active ? myhead : u * a.hpu, lane_li = col_active ? li : 0;
       const unsigned lane_col_off = a.k_banded ? (unsigned)lane_head * TILE_ROWS * (unsigned)a.d_k * 2u + (unsigned)lane_li * 16u
                                                : (unsigned)(col_active ? mycol : ucol0) * 2u;
-      const unsigned lane_off = (unsigned)(rg * 8) * rowB + lane_col_off;
+      const unsigned lane_off = (unsigned)(rg * RR) * rowB + lane_col_off;
       float mrun = NEG_INF;                           // running maximum of this lane's head (log2 domain)
       bf16x8 bq[4];                                   // B operands of the score MFMA (filled below, behind the first tile requests)
       // softmax state of the weighted sum and its accumulators; accl: sum of the weights (an all-ones A operand)
@@ -723,14 +730,14 @@ __global__ __launch_bounds__(FUSED_WAVES * 64) void fused_stream_kernel(const Fu
           const char* tb = reinterpret_cast<const char*>(Kb) + (size_t)st * bandB;
 #pragma unroll
           for (int j = 0; j < 8; ++j)
-            t[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tb + (size_t)j * rowB + lane_off));
+            t[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(tb + (size_t)(j * RJ) * rowB + lane_off));
         } else {
           // last, partial tile (rows past the end re-read the last row; masked in the scores) or no tile
-          const int r0 = st * TILE_ROWS + rg * 8;
+          const int r0 = st * TILE_ROWS + rg * RR;
           const char* cb = reinterpret_cast<const char*>(Kb) + lane_col_off;
 #pragma unroll
           for (int j = 0; j < 8; ++j) {
-            const int rr = max(min(r0 + j, len - 1), 0);
+            const int rr = max(min(r0 + j * RJ, len - 1), 0);
             t[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(cb + (size_t)(rr >> 5) * bandB + (size_t)(rr & 31) * rowB));
           }
         }
@@ -755,7 +762,7 @@ __global__ __launch_bounds__(FUSED_WAVES * 64) void fused_stream_kernel(const Fu
         u32x4 (&cur)[8] = ts[decltype(SI)::value];
         char* sl = myslots + (k & (NS - 1)) * SLOT_PITCH + wpos;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) *reinterpret_cast<u32x4*>(sl + j * ROW_PITCH) = cur[j];
+        for (int j = 0; j < 8; ++j) *reinterpret_cast<u32x4*>(sl + j * RJ * ROW_PITCH) = cur[j];
       };
       auto request = [&](int k, auto SI) { load_tile(ts[decltype(SI)::value], tr[decltype(SI)::value], k); };
       // ---- softmax numerators of the unit's heads from the 8 scores of a lane (row of score jj given by
