@@ -474,8 +474,10 @@ __global__ __launch_bounds__(512) void project_mfma_kernel(const ProjArgs a) {
 constexpr float SOFTMAX_SLACK = 6.0f;
 
 // LPHP: lanes reserved per head as a compile-time constant (16 or 8: heads of 128 or 64 columns), or 0
-// for the run-time value.
-template <int NT, bool ROPE, int LPHP>
+// for the run-time value.  BYSEQ: the by-sequence partition (a.by_sequence != 0), which has no merge of the
+// waves and never runs the projection; an instantiation of its own keeps each partition's code out of the
+// other's registers.
+template <int NT, bool ROPE, int LPHP, bool BYSEQ>
 __global__ __launch_bounds__(FUSED_WAVES * 64) void fused_stream_kernel(const FusedArgs a) {
   constexpr int NP = FUSED_WAVES, NS = FUSED_SLOTS, PD = FUSED_AHEAD;
   constexpr int NTHR = NP * 64;
@@ -521,7 +523,7 @@ __global__ __launch_bounds__(FUSED_WAVES * 64) void fused_stream_kernel(const Fu
   const int wu = __builtin_amdgcn_readfirstlane(w);
   const int p = wu;                                 // this wave's team: wave p of every workgroup of the group
 
-  const bool fuse = a.fuse != 0;
+  const bool fuse = !BYSEQ && a.fuse != 0;
   if (blockIdx.x == 0 && a.counters)                // the projection's arrival counters start at 0
     for (int i = tid; i < a.ncounters; i += NTHR) st_result(a.counters + i, 0, fuse);
 
@@ -529,7 +531,7 @@ __global__ __launch_bounds__(FUSED_WAVES * 64) void fused_stream_kernel(const Fu
   const int VT = prefix[a.B];
   const int Qt = (VT + a.NG - 1) / a.NG;            // tiles per group
   const int v0 = g * Qt, v1 = min(VT, v0 + Qt);
-  if (a.by_sequence ? (g * NP >= a.B * a.by_sequence) : (v0 >= v1)) has_work = false;
+  if (BYSEQ ? (g * NP >= a.B * a.by_sequence) : (v0 >= v1)) has_work = false;
   if (!has_work && !fuse) return;
 
   // ---- lane -> column mapping inside the unit --------------------------------------------------
@@ -599,7 +601,7 @@ __global__ __launch_bounds__(FUSED_WAVES * 64) void fused_stream_kernel(const Fu
   //    takes shares round-robin; no merge inside the workgroup, one partial per share.  For batches
   //    whose shares fill the slots evenly (many short sequences).
   struct Seg { int b, t0, stride, ntl, len, pid; unsigned it0; const uint16_t* Kb; };   // it0: tiles of earlier segments
-  const bool by_seq = a.by_sequence != 0;
+  constexpr bool by_seq = BYSEQ;
   int seg_b = by_seq ? g * NP + p : 0;
   unsigned seg_it = 0;                              // tiles this wave has been through so far
   if (has_work && !by_seq)
@@ -1047,20 +1049,43 @@ __global__ __launch_bounds__(FUSED_WAVES * 64) void fused_stream_kernel(const Fu
 
       // ---- end of this sequence's share ---------------------------------------------------------------
       if (by_seq) {
-        // the whole share was this wave's: its partial goes out straight from the accumulators (a lane
-        // holds 8 consecutive columns of a head per accumulator row: two 16-byte stores)
+        // the whole share was this wave's: its partial needs no merge.  A lane holds 8 consecutive columns
+        // of a head per accumulator row; stored from there, an instruction writes 64 16-byte pieces into 64
+        // different cache lines (7 of 71 us at 64 sequences of 1500 rows).  So head tile t goes through the
+        // wave's (idle) slot t and leaves with a head's columns on consecutive lanes.
+        constexpr int OP = 128 + 4;                     // floats per head row in the slot (padding: no bank conflicts)
+        static_assert(16 * OP * 4 <= SLOT_PITCH && NT <= NS, "a head tile's block must fit one slot");
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+          float* const ob = reinterpret_cast<float*>(myslots + t * SLOT_PITCH) + n * OP;
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            if (ocol[r] < 0) continue;
+            *reinterpret_cast<f32x4*>(ob + ocol[r]) = f32x4{acc[0][t][r], acc[1][t][r], acc[2][t][r], acc[3][t][r]};
+            *reinterpret_cast<f32x4*>(ob + ocol[r] + 4) = f32x4{acc[4][t][r], acc[5][t][r], acc[6][t][r], acc[7][t][r]};
+          }
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // (LDS operations of one wave complete in order)
+        {
+          // head hl of the block on lanes 32 (hl % 2) .. +31, four columns per lane; two heads per instruction
+          const int c4 = (lane & 31) * 4;
+          const float* src = reinterpret_cast<const float*>(myslots) + (lane >> 5) * OP + c4;
+          float* dst = a.Cpart + ((size_t)sg.pid * a.H + (lane >> 5)) * a.d + ucol0 + c4;
+          const int nh = min(a.H, HP);
+#pragma unroll 1
+          for (int hl = lane >> 5; hl < nh; hl += 2) {
+            const int t = hl >> 4;
+            const f32x4 v = *reinterpret_cast<const f32x4*>(src + (t * (SLOT_PITCH / 4 - 16 * OP)));
+            if (c4 < uwc) st_result4(dst, v, fuse);
+            src += 2 * OP;
+            dst += 2 * (size_t)a.d;
+          }
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // (the next share parks its tiles in these slots)
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
           const int h = t * 16 + n;
-          if (h < a.H) {
-            float* dst = a.Cpart + ((size_t)sg.pid * a.H + h) * a.d + ucol0;
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-              if (ocol[r] < 0) continue;
-              st_result4(dst + ocol[r], f32x4{acc[0][t][r], acc[1][t][r], acc[2][t][r], acc[3][t][r]}, fuse);
-              st_result4(dst + ocol[r] + 4, f32x4{acc[4][t][r], acc[5][t][r], acc[6][t][r], acc[7][t][r]}, fuse);
-            }
-          }
           if (u == 0 && kg == 0 && h < a.H) {
             st_result(a.mpart + (size_t)sg.pid * a.H + h, m[t], fuse);
             st_result(a.lpart + (size_t)sg.pid * a.H + h, accl[t][0], fuse);
@@ -1197,9 +1222,13 @@ bool probe_xcd_round_robin(unsigned* dev_buf, hipStream_t st) {
 // safe when all of its workgroups are resident together.
 int fused_blocks_per_cu(const FusedGeom& g, bool rope) {
   int n = 0;
-  auto ask = [&](auto nt, auto rp, auto lp) {
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, fused_stream_kernel<decltype(nt)::value, decltype(rp)::value, decltype(lp)::value>,
-                                                     g.NP * 64, 0) != hipSuccess) { n = 0; (void)hipGetLastError(); }
+  auto ask = [&](auto nt, auto rp, auto lp) {                 // (the smaller figure of the two partitions' instantiations)
+    int n0 = 0, n1 = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n0, fused_stream_kernel<decltype(nt)::value, decltype(rp)::value, decltype(lp)::value, false>,
+                                                     g.NP * 64, 0) != hipSuccess) { n0 = 0; (void)hipGetLastError(); }
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n1, fused_stream_kernel<decltype(nt)::value, decltype(rp)::value, decltype(lp)::value, true>,
+                                                     g.NP * 64, 0) != hipSuccess) { n1 = 0; (void)hipGetLastError(); }
+    n = n0 < n1 ? n0 : n1;
   };
   auto with_lphp = [&](auto nt, auto rp) {
     if (g.lphp == 16) ask(nt, rp, std::integral_constant<int, 16>{});
@@ -1239,7 +1268,10 @@ size_t fused_exch_bytes(const FusedGeom& g) {
 void launch_fused_stream(const FusedGeom& g, const FusedArgs& a, hipStream_t st) {
   dim3 grid(g.grid), block(g.NP * 64);
   auto go = [&](auto nt, auto rope, auto lphp) {
-    hipLaunchKernelGGL((fused_stream_kernel<decltype(nt)::value, decltype(rope)::value, decltype(lphp)::value>), grid, block, 0, st, a);
+    if (a.by_sequence)
+      hipLaunchKernelGGL((fused_stream_kernel<decltype(nt)::value, decltype(rope)::value, decltype(lphp)::value, true>), grid, block, 0, st, a);
+    else
+      hipLaunchKernelGGL((fused_stream_kernel<decltype(nt)::value, decltype(rope)::value, decltype(lphp)::value, false>), grid, block, 0, st, a);
   };
   auto with_lphp = [&](auto nt, auto rope) {
     if (g.lphp == 16) go(nt, rope, std::integral_constant<int, 16>{});
