@@ -554,9 +554,11 @@ __global__ __launch_bounds__(512) void xfused_kernel(const uint16_t* qt, const u
   u32x4 (&cur)[8] = xt[0];
   u32x4 am[8];                                         // the parked tile, transposed: A operands of its weighted sum
   // 1. the slice into LDS; partial scores of the 32 heads over this wave's 128 columns
-  auto scores = [&](int k) {
+  auto park = [&]() {
 #pragma unroll
     for (int j = 0; j < 8; ++j) *reinterpret_cast<u32x4*>(sl + (rg * 8 + j) * XF_PITCH + idx * 16) = cur[j];
+  };
+  auto scores = [&](int k) {
     f32x4 sp[2][NT];
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt)
@@ -628,9 +630,10 @@ __global__ __launch_bounds__(512) void xfused_kernel(const uint16_t* qt, const u
   // (Letting the weighted sum of tile k - 1 share a barrier interval with the scores of tile k, the two waves
   //  of a SIMD in opposite order, was measured: 68 against 58 us on the T5-11B-shaped configuration.)
   for (int k = 0; k < ntile; ++k) {
+    park();
+    transpose8x8(cur, am);                             // (cur is parked: its registers go to the next tile,
+    load_tile(cur, tile_row(k + 1));                   //  requested before the scores so that it has a whole step to arrive; past the end: the last tile again, unused)
     scores(k);
-    transpose8x8(cur, am);                             // (cur is parked: its registers go to the next tile)
-    load_tile(cur, tile_row(k + 1));                   // past the end: the last tile again, unused
     lds_barrier();
     numerators(k);
     lds_barrier();
