@@ -33,6 +33,23 @@ __device__ __forceinline__ void lds_barrier() {
   asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
+// Workgroup i of a one-dimensional launch -> (unit, inner): a unit is a set of `ninner` workgroups that read
+// the same data (a sequence's q~ or scores, the same rows of X).  Workgroups are dealt to the 8 XCDs round
+// robin, each with an L2 of its own, so with `colocate` a unit's workgroups are the ones with the same
+// i % 8 and consecutive i / 8: what they share is fetched into one L2 instead of up to eight.  (Where the
+// dealing differs the mapping is still a bijection: only the sharing is lost.)  False: no such unit.
+__device__ __forceinline__ bool unit_of_workgroup(int i, int ninner, int nunits, bool colocate, int& unit, int& inner) {
+  if (colocate) {
+    const int slot = i >> 3;
+    unit = (slot / ninner) * 8 + (i & 7);
+    inner = slot % ninner;
+  } else {
+    unit = i / ninner;
+    inner = i % ninner;
+  }
+  return unit < nunits;
+}
+
 // ------------------------------------------------------------------------------------------------
 // q~[b][h][c] = scale * sum_j q[b][h d_k + j] W_K[c][h d_k + j]   (scale = log2(e) / sqrt(d_k)), written
 // as two bf16 arrays, hi = bf16(q~) and lo = bf16(q~ - hi), in the order the scores kernel's MFMA B operands
@@ -162,11 +179,15 @@ constexpr int XL_AHEAD = 4;              // chunks of X in flight from HBM (regi
 
 template <int P>
 __global__ __launch_bounds__(512) void xscores_kernel(const uint16_t* qt, const uint16_t* X, long x_bstride,
-                                                      const int32_t* seq_lens, int T, int B, int H, int dm, float* S) {
+                                                      const int32_t* seq_lens, int T, int B, int H, int dm, float* S,
+                                                      int colocate) {
   __shared__ __align__(16) uint16_t xs[2][XL_RB * XL_PITCH];
   constexpr int RS = 8 / P;                            // waves per head tile = row subsets
   constexpr int D = XL_AHEAD;
-  const int b = blockIdx.y, row_base = blockIdx.x * XL_RB;
+  // unit = sequence (its row blocks read the same q~), inner = block of XL_RB rows
+  int b, rbk;
+  if (!unit_of_workgroup(blockIdx.x, (T + XL_RB - 1) / XL_RB, B, colocate != 0, b, rbk)) return;
+  const int row_base = rbk * XL_RB;
   const int len = seq_len_of(seq_lens, b, T);
   if (row_base >= len) return;                         // (workgroup-uniform)
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -248,9 +269,13 @@ __global__ __launch_bounds__(512) void xscores_kernel(const uint16_t* qt, const 
           for (int mi = 0; mi < P; ++mi) {
             const int t0 = row_base + (rs + mi * RS) * 16 + kq * 4;
             float* dst = S + ((size_t)b * H + h) * Tp + t0;
+            if (t0 + 3 < len) {                         // (rows of S are padded to 32: 16-byte aligned)
+              *reinterpret_cast<f32x4*>(dst) = acc[mi];
+            } else {
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
-              if (t0 + r < len) dst[r] = acc[mi][r];
+              for (int r = 0; r < 4; ++r)
+                if (t0 + r < len) dst[r] = acc[mi][r];
+            }
           }
         }
       }
@@ -281,14 +306,18 @@ __global__ __launch_bounds__(512) void xscores_kernel(const uint16_t* qt, const 
 constexpr float XW_SLACK = 6.0f;
 
 __global__ __launch_bounds__(512) void xweighted_kernel(const float* S, const uint16_t* X, long x_bstride,
-                                                        const int32_t* seq_lens, int T, int H, int dm, int nsplit,
-                                                        float* Cpart, float* mpart, float* lpart) {
+                                                        const int32_t* seq_lens, int T, int B, int H, int dm, int nsplit,
+                                                        float* Cpart, float* mpart, float* lpart, int colocate) {
   constexpr int NT = 2, NW = 8;
   __shared__ float red[NW][NT][4][8][64];              // [wave][head tile][r][i][lane]: 128 KB
   __shared__ float msh[NW][NT * 16], lsh[NW][NT * 16];
-  const int b = blockIdx.z, s = blockIdx.x;
+  // unit = (sequence, context split): its workgroups read the same rows of X (one column block each, for
+  // every head group) and the same scores (one head group each, for every column block)
   const int ncb = dm / 128;
-  const int cbk = blockIdx.y % ncb, hg = blockIdx.y / ncb;   // (the head groups of a column block: same XCD when ncb % 8 == 0)
+  int unit, inner;
+  if (!unit_of_workgroup(blockIdx.x, ((H + 31) / 32) * ncb, B * nsplit, colocate != 0, unit, inner)) return;
+  const int b = unit / nsplit, s = unit - b * nsplit;
+  const int cbk = inner % ncb, hg = inner / ncb;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int idx = lane & 15, rg = lane >> 4;
   const int n = idx, kg = rg;
@@ -724,6 +753,12 @@ void launch_xfused(const float* qt, const void* X, long x_bstride, const int32_t
                      d_model, nsplit, Cpart, mpart, lpart);
 }
 
+// Units dealt to the 8 XCDs (unit_of_workgroup): only when they spread evenly, within a quarter
+static int colocate_units(int nunits) { return (nunits % 8 == 0 || nunits >= 32) ? 1 : 0; }
+static unsigned unit_grid(int nunits, int ninner, int colocate) {
+  return colocate ? 8u * (unsigned)ninner * (unsigned)((nunits + 7) / 8) : (unsigned)nunits * (unsigned)ninner;
+}
+
 void launch_xq_tilde(const float* q, const void* Wk, float* qt, int B, int H, int d_k, int d_model, int e,
                      float scale, int* counters, int ncounters, hipStream_t st) {
   dim3 grid((H + XQ_HEADS - 1) / XQ_HEADS, (d_model + 127) / 128, (B + 15) / 16);
@@ -733,22 +768,24 @@ void launch_xq_tilde(const float* q, const void* Wk, float* qt, int B, int H, in
 
 void launch_xscores(const float* qt, const void* X, long x_bstride, const int32_t* seq_lens, int T, int H,
                     int d_model, float* S, int B, hipStream_t st) {
-  dim3 grid((T + XL_RB - 1) / XL_RB, B);
+  const int ninner = (T + XL_RB - 1) / XL_RB, colocate = colocate_units(B);
+  dim3 grid(unit_grid(B, ninner, colocate));
   const uint16_t* q16 = (const uint16_t*)qt;
   const uint16_t* X16 = (const uint16_t*)X;
   switch (head_tiles_in_flight(H)) {
-    case 1: hipLaunchKernelGGL(xscores_kernel<1>, grid, dim3(512), 0, st, q16, X16, x_bstride, seq_lens, T, B, H, d_model, S); break;
-    case 2: hipLaunchKernelGGL(xscores_kernel<2>, grid, dim3(512), 0, st, q16, X16, x_bstride, seq_lens, T, B, H, d_model, S); break;
-    case 4: hipLaunchKernelGGL(xscores_kernel<4>, grid, dim3(512), 0, st, q16, X16, x_bstride, seq_lens, T, B, H, d_model, S); break;
-    default: hipLaunchKernelGGL(xscores_kernel<8>, grid, dim3(512), 0, st, q16, X16, x_bstride, seq_lens, T, B, H, d_model, S); break;
+    case 1: hipLaunchKernelGGL(xscores_kernel<1>, grid, dim3(512), 0, st, q16, X16, x_bstride, seq_lens, T, B, H, d_model, S, colocate); break;
+    case 2: hipLaunchKernelGGL(xscores_kernel<2>, grid, dim3(512), 0, st, q16, X16, x_bstride, seq_lens, T, B, H, d_model, S, colocate); break;
+    case 4: hipLaunchKernelGGL(xscores_kernel<4>, grid, dim3(512), 0, st, q16, X16, x_bstride, seq_lens, T, B, H, d_model, S, colocate); break;
+    default: hipLaunchKernelGGL(xscores_kernel<8>, grid, dim3(512), 0, st, q16, X16, x_bstride, seq_lens, T, B, H, d_model, S, colocate); break;
   }
 }
 
 void launch_xweighted(const float* S, const void* X, long x_bstride, const int32_t* seq_lens, int T, int H,
                       int d_model, int nsplit, float* Cpart, float* mpart, float* lpart, int B, hipStream_t st) {
-  dim3 grid(nsplit, ((H + 31) / 32) * (d_model / 128), B);
-  hipLaunchKernelGGL(xweighted_kernel, grid, dim3(512), 0, st, S, (const uint16_t*)X, x_bstride, seq_lens, T, H,
-                     d_model, nsplit, Cpart, mpart, lpart);
+  const int ninner = ((H + 31) / 32) * (d_model / 128), colocate = colocate_units(B * nsplit);
+  dim3 grid(unit_grid(B * nsplit, ninner, colocate));
+  hipLaunchKernelGGL(xweighted_kernel, grid, dim3(512), 0, st, S, (const uint16_t*)X, x_bstride, seq_lens, T, B, H,
+                     d_model, nsplit, Cpart, mpart, lpart, colocate);
 }
 
 }  // namespace slim
