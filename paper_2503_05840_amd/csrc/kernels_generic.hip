@@ -319,30 +319,47 @@ __global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ 
 
 // ------------------------------------------------------------------------------------------------
 // project: out[b][n] = sum_c Cn[b][n/d_k][c] W[c][n].  Workgroup = 64 output columns x 4 batch
-// rows; its 4 waves interleave over c and are summed through LDS.
+// rows; its 16 waves interleave over c, eight rows of W in flight per wave, and are summed through
+// LDS in a fixed order.
 // ------------------------------------------------------------------------------------------------
+constexpr int PROJ_WAVES = 16, PROJ_UNROLL = 8;
+
 template <class ET>
-__global__ __launch_bounds__(256) void project_kernel(const float* __restrict__ Cn,
-                                                      const typename ET::elem* __restrict__ W,
-                                                      int rows, int e, int H, int d_k,
-                                                      float* __restrict__ out, int B) {
-  __shared__ float red[4][4][64];
+__global__ __launch_bounds__(PROJ_WAVES * 64) void project_kernel(const float* __restrict__ Cn,
+                                                                 const typename ET::elem* __restrict__ W,
+                                                                 int rows, int e, int H, int d_k,
+                                                                 float* __restrict__ out, int B) {
+  __shared__ float red[PROJ_WAVES][4][64];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int n = blockIdx.x * 64 + lane;
   const int b0 = blockIdx.y * 4;
   float acc[4] = {0.f, 0.f, 0.f, 0.f};
   if (n < e) {
     const int h = n / d_k;
-    const float* c0p = Cn + ((long)min(b0 + 0, B - 1) * H + h) * rows;
-    const float* c1p = Cn + ((long)min(b0 + 1, B - 1) * H + h) * rows;
-    const float* c2p = Cn + ((long)min(b0 + 2, B - 1) * H + h) * rows;
-    const float* c3p = Cn + ((long)min(b0 + 3, B - 1) * H + h) * rows;
-    for (int c = wave; c < rows; c += 4) {
-      const float w = ET::one(W + (long)c * e + n);
-      acc[0] = fmaf(c0p[c], w, acc[0]);
-      acc[1] = fmaf(c1p[c], w, acc[1]);
-      acc[2] = fmaf(c2p[c], w, acc[2]);
-      acc[3] = fmaf(c3p[c], w, acc[3]);
+    const float* cp[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) cp[j] = Cn + ((long)min(b0 + j, B - 1) * H + h) * rows;
+    const typename ET::elem* wn = W + n;
+    int c = wave;
+    const bool one_row = b0 + 1 >= B;                  // (a single sequence: no loads for the three rows that repeat it)
+    for (; c + (PROJ_UNROLL - 1) * PROJ_WAVES < rows; c += PROJ_UNROLL * PROJ_WAVES) {
+      float w[PROJ_UNROLL];
+#pragma unroll
+      for (int u = 0; u < PROJ_UNROLL; ++u) w[u] = ET::one(wn + (long)(c + u * PROJ_WAVES) * e);
+      if (one_row) {
+#pragma unroll
+        for (int u = 0; u < PROJ_UNROLL; ++u) acc[0] = fmaf(cp[0][c + u * PROJ_WAVES], w[u], acc[0]);
+      } else {
+#pragma unroll
+        for (int u = 0; u < PROJ_UNROLL; ++u)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) acc[j] = fmaf(cp[j][c + u * PROJ_WAVES], w[u], acc[j]);
+      }
+    }
+    for (; c < rows; c += PROJ_WAVES) {
+      const float w = ET::one(wn + (long)c * e);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[j] = fmaf(cp[j][c], w, acc[j]);
     }
   }
 #pragma unroll
@@ -351,8 +368,11 @@ __global__ __launch_bounds__(256) void project_kernel(const float* __restrict__ 
   if (wave == 0 && n < e) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      if (b0 + j < B)
-        out[(long)(b0 + j) * e + n] = (red[0][j][lane] + red[1][j][lane]) + (red[2][j][lane] + red[3][j][lane]);
+      if (b0 + j >= B) continue;
+      float sum = 0.f;
+#pragma unroll
+      for (int ww = 0; ww < PROJ_WAVES; ++ww) sum += red[ww][j][lane];
+      out[(long)(b0 + j) * e + n] = sum;
     }
   }
 }
@@ -751,9 +771,9 @@ void launch_project(int dtype, const float* Cn, const void* W, int rows, int e, 
                     float* out, int B, hipStream_t st) {
   dim3 grid((e + 63) / 64, (B + 3) / 4);
   if (dtype == DT_BF16)
-    hipLaunchKernelGGL(project_kernel<BF16>, grid, dim3(256), 0, st, Cn, (const uint16_t*)W, rows, e, H, d_k, out, B);
+    hipLaunchKernelGGL(project_kernel<BF16>, grid, dim3(PROJ_WAVES * 64), 0, st, Cn, (const uint16_t*)W, rows, e, H, d_k, out, B);
   else
-    hipLaunchKernelGGL(project_kernel<F32>, grid, dim3(256), 0, st, Cn, (const float*)W, rows, e, H, d_k, out, B);
+    hipLaunchKernelGGL(project_kernel<F32>, grid, dim3(PROJ_WAVES * 64), 0, st, Cn, (const float*)W, rows, e, H, d_k, out, B);
 }
 
 void launch_append(int dtype, const float* knew, const float* vnew, void* K, void* V, long bstride,
