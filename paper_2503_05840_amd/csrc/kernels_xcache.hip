@@ -479,25 +479,27 @@ __global__ __launch_bounds__(512) void xweighted_kernel(const float* S, const ui
 
 
 // ------------------------------------------------------------------------------------------------
-// One pass over X for 512 <= d_model <= 1024: scores, softmax numerators and the weighted sum of one
-// (sequence, context split, group of 32 heads) in one kernel, so X leaves memory once per head group,
+// One pass over X for 512 <= d_model <= 1280: scores, softmax numerators and the weighted sum of one
+// (sequence, context split, group of heads) in one kernel, so X leaves memory once per head group,
 // no score matrix is written, and the exponentials of a row are computed once instead of once per
 // column block.  The accumulators (32 heads x d_model fp32 = 128 KB at 1024 columns) stay in the
-// workgroup's registers for its whole row range, which is why the COLUMNS are split over the 8 waves
+// workgroup's registers for its whole row range, which is why the COLUMNS are split over the waves
 // (wave w owns columns [128 w, 128 w + 128): its slice of q~ as resident B operands, its 32 x 128 slice
-// of every row tile, its 32 x 128 accumulator block) and the waves meet twice per 32-row tile in LDS --
+// of every row tile, its accumulator block) and the waves meet twice per 32-row tile in LDS --
 // the same exchange of numerators between column owners as in the K-cache stream kernel, but inside
 // one workgroup, with barriers:
-//   1. park the slice in LDS (row-padded), read it back in A-operand order, partial scores of all 32
-//      heads over the wave's columns on MFMA (query hi + lo: 32 MFMAs), partials to LDS;  -- barrier --
-//   2. wave w sums the partials of heads 4w .. 4w+3 over the column owners (lane = row), keeps those
-//      heads' running reference and sum of weights, writes bf16 numerators and the rescale factors;
+//   1. park the slice in LDS (row-padded), transpose it in registers for step 3, request the next tile,
+//      read the slice back in A-operand order, partial scores of the group's heads over the wave's
+//      columns on MFMA (query hi + lo), partials to LDS;  -- barrier --
+//   2. waves 0..7 sum the partials of their heads over the column owners (lane = row), keep those
+//      heads' running reference and sum of weights, write bf16 numerators and the rescale factors;
 //      -- barrier --
-//   3. every wave rescales if a reference moved, transposes its slice in registers and adds
-//      P^T X on MFMA (16 MFMAs).
-// Rows are not split over the waves, so nothing is merged at the end: a wave writes its columns of the
-// partial straight from its registers.  grid (context splits, head groups, B): blockIdx.x is the split, so
-// with 8 splits the head groups that read the same rows run on the same XCD and share them in its L2.
+//   3. every wave rescales if a reference moved and adds P^T X on MFMA.
+// Rows are not split over the waves, so nothing is merged at the end.  A one-dimensional launch: the head
+// groups of a (sequence, context split) read the same rows and are mapped to one XCD (unit_of_workgroup).
+// Two shapes: 8 waves x 32 heads (d_model <= 1024; 32 + 16 MFMAs per wave and tile) and 10 waves x 16
+// heads (d_model <= 1280: three waves on two of the four SIMDs, hence 168 registers, which hold half
+// the accumulators and the hi halves of q~; the lo halves wait in LDS).
 // ------------------------------------------------------------------------------------------------
 // max over the 32 lanes that share lane / 32: four DPP steps inside the 16-lane row (lane ^ 1, lane ^ 2,
 // the other quad of the 8-lane half, the other half of the row), then the row 16 lanes away by a register swap
@@ -519,15 +521,29 @@ constexpr int XF_PITCH = 272;            // bytes per parked row: 256 + 16 of pa
 constexpr int XF_RED_HS = 36;            // floats per head row of a wave's partial scores (32 rows + padding that keeps 16-byte stores)
 constexpr int XF_P_HS = 40;              // bf16 per head row of the numerators (32 rows + padding)
 
-__global__ __launch_bounds__(512) void xfused_kernel(const uint16_t* qt, const uint16_t* X, long x_bstride,
-                                                     const int32_t* seq_lens, int T, int B, int H, int dm, int nsplit,
-                                                     float* Cpart, float* mpart, float* lpart) {
-  constexpr int NW = 8, NT = 2;
+// NW waves, each the owner of 128 columns (d_model <= 128 NW); NT head tiles of 16 per group.  Two shapes are
+// built: 8 waves x 32 heads (two waves per SIMD, 256 registers each) and 10 waves x 16 heads for rows of up to
+// 1280 columns (three waves on two of the SIMDs: 168 registers, which half the accumulators and half the
+// resident q~ fit).  The softmax state of the group's heads is looked after by waves 0..7, HG / 8 heads each.
+template <int NW, int NT>
+__global__ __launch_bounds__(NW * 64) void xfused_kernel(const uint16_t* qt, const uint16_t* X, long x_bstride,
+                                                         const int32_t* seq_lens, int T, int B, int H, int dm, int nsplit,
+                                                         float* Cpart, float* mpart, float* lpart, int colocate) {
+  constexpr int HG = 16 * NT;                          // heads per group
+  constexpr int HPL = HG / 16;                         // heads per lane of an owner wave (lane = (row, half): 2 x 32 lanes)
+  static_assert(NW >= 8 && (NT == 1 || NT == 2), "owners are waves 0..7");
   __shared__ __align__(16) unsigned char slot[NW][32 * XF_PITCH];
-  __shared__ __align__(16) float red[NW][32][XF_RED_HS];
-  __shared__ __align__(16) uint16_t P_s[32][XF_P_HS];
-  __shared__ float alpha_s[32];
-  const int s = blockIdx.x, hg = blockIdx.y, b = blockIdx.z;
+  __shared__ __align__(16) float red[NW][HG][XF_RED_HS];
+  __shared__ __align__(16) uint16_t P_s[HG][XF_P_HS];
+  __shared__ float alpha_s[HG];
+  // With three waves per SIMD the lo halves of q~ do not fit the registers: they wait in LDS (a wave's own
+  // 4 KB, read back one operand at a time); with two waves per SIMD they stay resident.
+  constexpr bool LO_IN_LDS = NW > 8;
+  __shared__ __align__(16) u32x4 qlo[LO_IN_LDS ? NW : 1][LO_IN_LDS ? NT * 4 : 1][64];
+  // unit = (sequence, context split): its head groups read the same rows of X, from one XCD's L2
+  int unit, hg;
+  if (!unit_of_workgroup(blockIdx.x, (H + HG - 1) / HG, B * nsplit, colocate != 0, unit, hg)) return;
+  const int b = unit / nsplit, s = unit - b * nsplit;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int idx = lane & 15, rg = lane >> 4;           // column group / row group of the register tile
   const int n = idx, kg = rg;                          // MFMA: N index (head) or M index (row), k group
@@ -541,7 +557,7 @@ __global__ __launch_bounds__(512) void xfused_kernel(const uint16_t* qt, const u
   const int NHT = (H + 15) / 16;
 
   // q~ of the group's 32 heads over this wave's columns, hi + lo, resident as B operands
-  u32x4 bqh[NT][4], bql[NT][4];
+  u32x4 bqh[NT][4], bql[LO_IN_LDS ? 1 : NT][4];
   {
     const size_t lo_off = (size_t)B * NHT * 16 * dm;
 #pragma unroll
@@ -551,7 +567,8 @@ __global__ __launch_bounds__(512) void xfused_kernel(const uint16_t* qt, const u
       for (int ks = 0; ks < 4; ++ks) {
         const uint16_t* src = qt + ((((size_t)b * NHT + ht) * (dm / 32) + (size_t)((has_cols ? w : 0) * 4 + ks)) * 64 + lane) * 8;
         bqh[t][ks] = *reinterpret_cast<const u32x4*>(src);
-        bql[t][ks] = *reinterpret_cast<const u32x4*>(src + lo_off);
+        if constexpr (LO_IN_LDS) qlo[w][t * 4 + ks][lane] = *reinterpret_cast<const u32x4*>(src + lo_off);
+        else bql[t][ks] = *reinterpret_cast<const u32x4*>(src + lo_off);
       }
     }
   }
@@ -570,10 +587,14 @@ __global__ __launch_bounds__(512) void xfused_kernel(const uint16_t* qt, const u
   for (int t = 0; t < NT; ++t)
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc[i][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-  // softmax state of the heads this wave owns: lane (r = lane % 32, hp = lane / 32) looks after row r of
-  // heads 4 w + 2 hp + {0, 1} of the group; m is the same in all 32 lanes, l is the lane's own share
+  // softmax state of the heads this wave owns (waves 0..7): lane (r = lane % 32, hp = lane / 32) looks after
+  // row r of heads (2 w + hp) HPL + {0 .. HPL - 1} of the group; m is the same in all 32 lanes, l is the
+  // lane's own share
   const int r = lane & 31, hp = lane >> 5;
-  float m[2] = {NEG_INF, NEG_INF}, l[2] = {0.f, 0.f};
+  const bool owner = w < 8;
+  float m[HPL], l[HPL];
+#pragma unroll
+  for (int i = 0; i < HPL; ++i) { m[i] = NEG_INF; l[i] = 0.f; }
 
   u32x4 xt[1][8];                                      // (one set: it is free again as soon as the tile is parked and transposed)
   auto tile_row = [&](int k) { return r_lo + 32 * min(k, max(ntile - 1, 0)); };
@@ -601,8 +622,12 @@ __global__ __launch_bounds__(512) void xfused_kernel(const uint16_t* qt, const u
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
           sp[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a8, __builtin_bit_cast(bf16x8, bqh[t][ks]), sp[mt][t], 0, 0, 0);
-          sp[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a8, __builtin_bit_cast(bf16x8, bql[t][ks]), sp[mt][t], 0, 0, 0);
+          const u32x4 lo = LO_IN_LDS ? qlo[w][t * 4 + ks][lane] : bql[t][ks];
+          sp[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a8, __builtin_bit_cast(bf16x8, lo), sp[mt][t], 0, 0, 0);
         }
+        // (three waves per SIMD: keep the scheduler from fetching all operands of the tile ahead, which
+        //  would push the accumulators out of the registers)
+        if constexpr (LO_IN_LDS) __builtin_amdgcn_sched_barrier(0);
       }
     if (has_cols) {                                    // D: column n = head, rows kg*4 + i
 #pragma unroll
@@ -613,17 +638,22 @@ __global__ __launch_bounds__(512) void xfused_kernel(const uint16_t* qt, const u
   };
   // 2. this wave's four heads: sum over the column owners, reference, numerators
   auto numerators = [&](int k) {
+    if (!owner) return;
     const int r0 = r_lo + 32 * k;
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int hl = 4 * w + 2 * hp + i;
-      float part[NW];                                  // (all reads issued before the first is used)
-#pragma unroll
-      for (int ws = 0; ws < NW; ++ws) part[ws] = red[min(ws, ncb - 1)][hl][r];
+    for (int i = 0; i < HPL; ++i) {
+      const int hl = (2 * w + hp) * HPL + i;
       float sc = 0.f;
 #pragma unroll
-      for (int ws = 0; ws < NW; ++ws) sc += ws < ncb ? part[ws] : 0.f;
-      const bool live = (hg * 32 + hl < H) && (r0 + r < r_hi);
+      for (int w0 = 0; w0 < NW; w0 += 8) {             // (the reads of a batch are issued before the first is used)
+        float part[8];
+#pragma unroll
+        for (int ws = 0; ws < 8; ++ws)                 // (waves without columns leave their block unwritten: read, not used)
+          part[ws] = red[min(w0 + ws, NW - 1)][hl][r];
+#pragma unroll
+        for (int ws = 0; ws < 8; ++ws) sc += w0 + ws < ncb ? part[ws] : 0.f;
+      }
+      const bool live = (hg * HG + hl < H) && (r0 + r < r_hi);
       const float x = live ? sc : NEG_INF;
       const float tmax = max_over_32(x);
       // (the reference moves only when the maximum has grown by more than XW_SLACK, as in xweighted_kernel)
@@ -661,7 +691,9 @@ __global__ __launch_bounds__(512) void xfused_kernel(const uint16_t* qt, const u
   for (int k = 0; k < ntile; ++k) {
     park();
     transpose8x8(cur, am);                             // (cur is parked: its registers go to the next tile,
-    load_tile(cur, tile_row(k + 1));                   //  requested before the scores so that it has a whole step to arrive; past the end: the last tile again, unused)
+    // requested before the scores so that it has a whole step to arrive; past the end: the last tile again,
+    // unused)
+    load_tile(cur, tile_row(k + 1));
     scores(k);
     lds_barrier();
     numerators(k);
@@ -691,19 +723,19 @@ __global__ __launch_bounds__(512) void xfused_kernel(const uint16_t* qt, const u
 #pragma unroll
       for (int k2 = 0; k2 < 8; ++k2) {
         const int hl = 2 * k2 + (lane >> 5), c4 = (lane & 31) * 4;
-        const int h = hg * 32 + t * 16 + hl;
+        const int h = hg * HG + t * 16 + hl;
         const f32x4 v = *reinterpret_cast<const f32x4*>(ob + hl * OP + c4);
         if (h < H) *reinterpret_cast<f32x4*>(Cpart + ((size_t)pid * H + h) * dm + w * 128 + c4) = v;
       }
     }
   }
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
+  for (int i = 0; i < HPL; ++i) {
     float lt = l[i];
 #pragma unroll
     for (int o = 1; o < 32; o <<= 1) lt += __shfl_xor(lt, o);
-    const int h = hg * 32 + 4 * w + 2 * hp + i;
-    if (r == 0 && h < H) {
+    const int h = hg * HG + (2 * w + hp) * HPL + i;
+    if (owner && r == 0 && h < H) {
       mpart[(size_t)pid * H + h] = m[i];
       lpart[(size_t)pid * H + h] = lt;
     }
@@ -734,11 +766,15 @@ int xcache_splits(int B, int H, int T, int d_model) {
   return s < 1 ? 1 : s;
 }
 
-bool xfused_ok(int d_model) { return d_model % 128 == 0 && d_model >= 512 && d_model <= 1024; }
+bool xfused_ok(int d_model) { return d_model % 128 == 0 && d_model >= 512 && d_model <= 1280; }
 
-int xfused_splits(int B, int H, int T) {
-  // one workgroup per (split, 32 heads, sequence): split the context as far as it takes to fill the chip
-  const int per = B * ((H + 31) / 32);
+// heads per workgroup of the one-pass kernel: 32 with 8 column owners, 16 with 10 (rows wider than 1024)
+static int xfused_head_group(int d_model) { return d_model <= 1024 ? 32 : 16; }
+
+int xfused_splits(int B, int H, int T, int d_model) {
+  // one workgroup per (split, head group, sequence): split the context as far as it takes to fill the chip
+  const int hg = xfused_head_group(d_model);
+  const int per = B * ((H + hg - 1) / hg);
   int s = (256 + per - 1) / per;
   const int cap = (T + 255) / 256;
   if (s > cap) s = cap;
@@ -746,17 +782,23 @@ int xfused_splits(int B, int H, int T) {
   return s < 1 ? 1 : s;
 }
 
-void launch_xfused(const float* qt, const void* X, long x_bstride, const int32_t* seq_lens, int T, int H, int d_model,
-                   int nsplit, float* Cpart, float* mpart, float* lpart, int B, hipStream_t st) {
-  dim3 grid(nsplit, (H + 31) / 32, B);
-  hipLaunchKernelGGL(xfused_kernel, grid, dim3(512), 0, st, (const uint16_t*)qt, (const uint16_t*)X, x_bstride, seq_lens, T, B, H,
-                     d_model, nsplit, Cpart, mpart, lpart);
-}
-
 // Units dealt to the 8 XCDs (unit_of_workgroup): only when they spread evenly, within a quarter
 static int colocate_units(int nunits) { return (nunits % 8 == 0 || nunits >= 32) ? 1 : 0; }
 static unsigned unit_grid(int nunits, int ninner, int colocate) {
   return colocate ? 8u * (unsigned)ninner * (unsigned)((nunits + 7) / 8) : (unsigned)nunits * (unsigned)ninner;
+}
+
+void launch_xfused(const float* qt, const void* X, long x_bstride, const int32_t* seq_lens, int T, int H, int d_model,
+                   int nsplit, float* Cpart, float* mpart, float* lpart, int B, hipStream_t st) {
+  const int hg = xfused_head_group(d_model);
+  const int colocate = colocate_units(B * nsplit);
+  dim3 grid(unit_grid(B * nsplit, (H + hg - 1) / hg, colocate));
+  if (hg == 32)
+    hipLaunchKernelGGL((xfused_kernel<8, 2>), grid, dim3(512), 0, st, (const uint16_t*)qt, (const uint16_t*)X, x_bstride, seq_lens, T, B, H,
+                       d_model, nsplit, Cpart, mpart, lpart, colocate);
+  else
+    hipLaunchKernelGGL((xfused_kernel<10, 1>), grid, dim3(640), 0, st, (const uint16_t*)qt, (const uint16_t*)X, x_bstride, seq_lens, T, B, H,
+                       d_model, nsplit, Cpart, mpart, lpart, colocate);
 }
 
 void launch_xq_tilde(const float* q, const void* Wk, float* qt, int B, int H, int d_k, int d_model, int e,

@@ -52,7 +52,7 @@ Plan make_plan(int B, int H, int T, int width, int e) {
   p.off_ctrl = o;    o += up(sizeof(int) * CTRL_INTS);
   p.fused_ok = (width == e) && fused_geometry(B, H, T, width, &p.geom);
   p.nsplit_x = xcache_splits(B, H, T, width);
-  p.nsplit_xf = xfused_ok(width) ? xfused_splits(B, H, T) : 0;
+  p.nsplit_xf = xfused_ok(width) ? xfused_splits(B, H, T, width) : 0;
   size_t nparts = (size_t)B * (p.nsplit > p.nsplit_x ? p.nsplit : p.nsplit_x);
   if ((size_t)B * p.nsplit_xf > nparts) nparts = (size_t)B * p.nsplit_xf;
   if (p.fused_ok && (size_t)p.geom.nparts > nparts) nparts = p.geom.nparts;

@@ -142,7 +142,7 @@ void launch_xq_tilde(const float* q, const void* Wk, float* qt, int B, int H, in
 void launch_xscores(const float* qt, const void* X, long x_bstride, const int32_t* seq_lens, int T, int H,
                     int d_model, float* S, int B, hipStream_t st);
 bool xfused_ok(int d_model);                 // one pass over X instead of xscores + xweighted
-int xfused_splits(int B, int H, int T);
+int xfused_splits(int B, int H, int T, int d_model);
 void launch_xfused(const float* qt, const void* X, long x_bstride, const int32_t* seq_lens, int T, int H, int d_model,
                    int nsplit, float* Cpart, float* mpart, float* lpart, int B, hipStream_t st);
 void launch_xweighted(const float* S, const void* X, long x_bstride, const int32_t* seq_lens, int T, int H,

@@ -184,6 +184,13 @@ def test_xcache_decode_matches_oracle(name, cfg):
     ("xcache-onepass-one-row", synth.scaled(C[4], B=2, H=5, d=512, d_k=32, T=1), 2.0, None),
     ("xcache-onepass-tile-plus-one", synth.scaled(C[4], B=3, H=5, d=640, d_k=32, T=33), 2.0, [33, 1, 32]),
     ("xcache-onepass-many-splits", synth.scaled(C[4], B=1, H=40, d=768, d_k=32, T=2500), 1.0, None),
+    # rows wider than 1024 columns: the one-pass kernel's ten-wave shape (16 heads per group) -- nine column
+    # owners (one wave without columns), one row, one row more than a tile, 40 heads over many splits, peaky scores
+    ("xcache-onepass-wide-nine-owners", synth.scaled(C[4], B=2, H=9, d=1152, d_k=32, T=300), 2.0, [300, 31]),
+    ("xcache-onepass-wide-one-row", synth.scaled(C[4], B=2, H=20, d=1280, d_k=64, T=1), 2.0, None),
+    ("xcache-onepass-wide-tile-plus-one", synth.scaled(C[4], B=3, H=17, d=1280, d_k=32, T=33), 2.0, [33, 1, 32]),
+    ("xcache-onepass-wide-many-splits", synth.scaled(C[4], B=1, H=40, d=1280, d_k=32, T=2500), 1.0, None),
+    ("xcache-onepass-wide-peaky", synth.scaled(C[4], B=2, H=20, d=1280, d_k=64, T=900), 8.0, None),
     # the encoder-decoder section's option 2: the cross-attention K and V of a Whisper-large-shaped layer
     # (square projections, 20 heads: 16 heads per score workgroup, a padded head tile) from the encoder output
     ("ecache-whisper-shape", synth.scaled(C[3], kind="xcache", B=3, T=333), 4.0, None),
