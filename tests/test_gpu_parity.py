@@ -191,6 +191,9 @@ def test_xcache_decode_matches_oracle(name, cfg):
     ("xcache-onepass-wide-tile-plus-one", synth.scaled(C[4], B=3, H=17, d=1280, d_k=32, T=33), 2.0, [33, 1, 32]),
     ("xcache-onepass-wide-many-splits", synth.scaled(C[4], B=1, H=40, d=1280, d_k=32, T=2500), 1.0, None),
     ("xcache-onepass-wide-peaky", synth.scaled(C[4], B=2, H=20, d=1280, d_k=64, T=900), 8.0, None),
+    # 33 (sequence, split) units: dealt to the 8 XCDs with seven empty places at the end of the launch
+    ("xcache-units-not-a-multiple-of-8", synth.scaled(C[4], B=33, H=8, d=512, d_k=32, T=70), 2.0, None),
+    ("xcache-wide-units-not-a-multiple-of-8", synth.scaled(C[4], B=35, H=20, d=1280, d_k=32, T=40), 2.0, None),
     # the encoder-decoder section's option 2: the cross-attention K and V of a Whisper-large-shaped layer
     # (square projections, 20 heads: 16 heads per score workgroup, a padded head tile) from the encoder output
     ("ecache-whisper-shape", synth.scaled(C[3], kind="xcache", B=3, T=333), 4.0, None),
