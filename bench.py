@@ -79,7 +79,7 @@ def calibration_copy(args, torch):
 
 XCACHE_STAGES = ["q_tilde (head_scores on W_K)", "dense_scores", "weighted_sum", "combine", "project"]
 XCACHE_MFMA_STAGES = ["xq_tilde", "xscores", "xweighted", "project_mfma"]     # two passes over X
-XCACHE_ONEPASS_STAGES = ["xq_tilde", "xfused", "project_mfma"]               # d_model <= 1024
+XCACHE_ONEPASS_STAGES = ["xq_tilde", "xfused", "project_mfma"]               # 512 <= d_model <= 1280
 
 
 def bench_xcache(args, cfg, torch, binding, synth, emit=True):
