@@ -687,7 +687,6 @@ __global__ __launch_bounds__(FUSED_WAVES * 64) void fused_stream_kernel(const Fu
       const u32x4* qsrc = reinterpret_cast<const u32x4*>(a.q + (size_t)sg.b * a.d + (col_active ? mycol : 0));
       const u32x4 qraw0 = qsrc[0], qraw1 = qsrc[1];
       unsigned qh[4], ql[4];
-      unsigned ph[4], pl[4];                          // (-q2, q1) of every pair, same split (rotary keys)
       // (lanes without live columns re-read the unit's first columns: finite values that meet a zero
       //  query in the scores and accumulator rows nobody reads in the weighted sum)
       // Byte offset of element (row r, this lane's first column) from the sequence's start:
@@ -816,6 +815,17 @@ __global__ __launch_bounds__(FUSED_WAVES * 64) void fused_stream_kernel(const Fu
         float sc[8];
         float cc[4] = {rot[0][0], rot[0][2], rot[1][0], rot[1][2]};
         float ss[4] = {rot[0][1], rot[0][3], rot[1][1], rot[1][3]};
+        // (-q2, q1) of every pair, same hi + lo split: rebuilt for every tile (three operations per word) so
+        // that the eight registers are free during the rest of the step; the empty asm keeps the compiler
+        // from hoisting them out of the loop again
+        unsigned ph[4], pl[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          unsigned h = qh[c], l = ql[c];
+          asm volatile("" : "+v"(h), "+v"(l));
+          ph[c] = ((h >> 16) ^ 0x8000u) | (h << 16);
+          pl[c] = ((l >> 16) ^ 0x8000u) | (l << 16);
+        }
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
           float sj = 0.f;
@@ -1013,13 +1023,6 @@ __global__ __launch_bounds__(FUSED_WAVES * 64) void fused_stream_kernel(const Fu
         const bf16x2 lo = {(__bf16)(f0 - (float)h0), (__bf16)(f1 - (float)h1)};
         qh[c] = __builtin_bit_cast(unsigned, hi);
         ql[c] = __builtin_bit_cast(unsigned, lo);
-      }
-      if constexpr (ROPE) {
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          ph[c] = ((qh[c] >> 16) ^ 0x8000u) | (qh[c] << 16);
-          pl[c] = ((ql[c] >> 16) ^ 0x8000u) | (ql[c] << 16);
-        }
       }
       {
         using S0 = std::integral_constant<int, 0>;
